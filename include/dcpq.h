@@ -1,0 +1,136 @@
+/*
+ * dcpq.h -- C ABI of libdcpq: two-pass product-quantization nearest-neighbour search with derived
+ * codebooks ("Derived Codebooks for High-Accuracy Nearest Neighbor Search", Alg. 3), hand-written
+ * HIP for gfx950 (MI355X).
+ *
+ * Letters: m sub-quantizers of b = 16 bits (2^16 centroids of dsub floats each); derived codebooks
+ * of bbar = 8 bits (2^8 centroids) indexed by the LOW 8 bits of a sub-code (Sec. 3.2, property
+ * P1); r = size of the candidate set kept by pass one (the paper's r2); k = size of the result set
+ * (the paper's r); D = m * dsub.
+ *
+ * Conventions for every call
+ *   - All array arguments are DEVICE pointers owned by the caller, row-major and contiguous, unless
+ *     a parameter is documented as "host".  The library never allocates, frees or retains them.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *     work on that stream and never synchronise; outputs are valid once the stream has drained.
+ *   - Scratch memory is a caller-provided device workspace of at least the number of bytes the
+ *     matching *_workspace_bytes call returns; its contents on entry do not matter, and two calls
+ *     that share a workspace must not overlap in time.
+ *   - Return value: DCPQ_OK or an error code; dcpq_last_error() then holds a message (thread
+ *     local).  Arguments are validated on the host before anything is launched; on error nothing
+ *     has been enqueued.
+ *   - Ties are always broken by the smaller vector id.  Ids are 32-bit: N < 2^32.
+ */
+#ifndef DCPQ_H
+#define DCPQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DCPQ_OK 0
+#define DCPQ_EINVAL 1        /* bad argument (null pointer, size out of range, k > r, r > N, ...) */
+#define DCPQ_EWORKSPACE 2    /* workspace smaller than *_workspace_bytes */
+#define DCPQ_EHIP 3          /* a HIP runtime call failed */
+#define DCPQ_EUNSUPPORTED 4  /* shape outside what the kernels are built for */
+
+#define DCPQ_PAD_ID 0xFFFFFFFFu /* id written into unused output slots (IVF variant only) */
+
+/* Message of the last error on this thread ("" if none). */
+const char *dcpq_last_error(void);
+
+/* Library ABI version (bumped when a signature changes). */
+int dcpq_version(void);
+
+/* Shapes the kernels accept: m in {1,2,4,8,16,32}, 1 <= dsub <= 128.  Returns 1 / 0. */
+int dcpq_shape_supported(int m, int dsub);
+
+/* ---------------------------------------------------------------------------------------------
+ * derive_codebooks -- Sec. 3.2 (Step 2 and property P1).
+ * derived[j][l][:] = mean of the 256 centroids codebooks[j][(i << 8) | l][:], i = 0..255, in
+ * fp32, added in increasing i and divided once by 256 (bit-reproducible).
+ *   codebooks : const float [m][65536][dsub]      derived : float [m][256][dsub]   (output)
+ * Done once per index, not per query.
+ * ------------------------------------------------------------------------------------------- */
+int dcpq_derive_codebooks(const float *codebooks, int m, int dsub, float *derived, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * build_small_tables -- Sec. 3.3 "Tables step": small lookup tables from the derived codebooks
+ * (Eq. 1), the qmin / qmax bounds, and the 8-bit quantized tables Q_j.
+ *   small[q][j][i] = sum_t (y_q[j*dsub+t] - derived[j][i][t])^2, fp32, t increasing, unfused.
+ *   qmin[q] = min over all m*256 entries; qmax[q] = max over the first min(r, n_codes) codes of
+ *   the fp32 sum over j (increasing) of small[q][j][code[j] & 255].
+ *   qtab[q][j][i] = 255 if (small - qmin) / (qmax - qmin) * 255 >= 255, else its floor; all zero
+ *   when qmax <= qmin.
+ *   queries : const float [nq][D]          derived : const float [m][256][dsub]
+ *   codes   : const uint16_t [n_codes][m]  (only the first min(r, n_codes) rows are read)
+ *   qtab    : uint8_t [nq][m][256] (output)   bounds : float [nq][2] = (qmin, qmax) (output)
+ *   small   : float [nq][m][256] (output) or NULL
+ * Needs no workspace.
+ * ------------------------------------------------------------------------------------------- */
+int dcpq_build_small_tables(const float *queries, int nq, const float *derived, int m, int dsub,
+                            const uint16_t *codes, uint64_t n_codes, uint32_t r, uint8_t *qtab,
+                            float *bounds, float *small, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * build_tables -- Eq. 1 with the full 16-bit codebooks ("Tables step" of Alg. 1), batched over
+ * queries as a matrix product on the matrix cores (double-precision accumulate, one rounding to
+ * fp32 on output).
+ *   tables[q][j][i] = || y_q^j - codebooks[j][i] ||^2
+ *   queries : const float [nq][D]   codebooks : const float [m][65536][dsub]
+ *   tables  : float [nq][m][65536] (output; nq * m * 256 KiB)
+ * Needs no workspace.
+ * ------------------------------------------------------------------------------------------- */
+int dcpq_build_tables(const float *queries, int nq, const float *codebooks, int m, int dsub,
+                      float *tables, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * scan_candidates -- Sec. 3.3 "Scan step" (Alg. 3 scan / adc_low_bits, capped buckets).
+ * For every query q and code i: qd = min(255, sum_j qtab[q][j][codes[i][j] & 255]); the candidate
+ * set is exactly the r smallest by (qd, i), written in that order.
+ *   codes   : const uint16_t [n_codes][m]     qtab : const uint8_t [nq][m][256]
+ *   cand_id : uint32_t [nq][r] (output)       cand_qd : uint8_t [nq][r] (output)
+ *   workspace : at least dcpq_scan_workspace_bytes(n_codes, m, nq, r) bytes, 256-byte aligned
+ * Requires 1 <= r <= n_codes < 2^32.
+ * ------------------------------------------------------------------------------------------- */
+size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r);
+int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                         uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
+                         size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * refine_topk -- Sec. 3.3 "Refine step" (Alg. 3 refine / adc_refine, Eq. 2): exact re-ranking of
+ * the candidates with the full tables, then the k best.
+ *   d(q, i) = sum over j increasing of tables[q][j][codes[i][j]] (fp32 adds)
+ *   ids[q][:], dist[q][:] = the k smallest by (d, i), ascending.
+ *   tables : const float [nq][m][65536]   codes : const uint16_t [n_codes][m]
+ *   cand_id : const uint32_t [nq][r]      ids : uint32_t [nq][k]   dist : float [nq][k] (outputs)
+ *   workspace : at least dcpq_refine_workspace_bytes(nq, r) bytes
+ * Requires 1 <= k <= r.
+ * ------------------------------------------------------------------------------------------- */
+size_t dcpq_refine_workspace_bytes(int nq, uint32_t r);
+int dcpq_refine_topk(const float *tables, const uint16_t *codes, uint64_t n_codes, int m,
+                     const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
+                     float *dist, void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * search -- Alg. 3 nns_derived end to end for a batch of queries without an index: small tables,
+ * quantization, scan, full tables, refine, top-k.  Queries are processed in chunks of
+ * `chunk_queries` (0 = library default) so that the full tables of one chunk live in the
+ * workspace.
+ *   derived : const float [m][256][dsub] from dcpq_derive_codebooks
+ *   workspace : at least dcpq_search_workspace_bytes(...) bytes
+ * ------------------------------------------------------------------------------------------- */
+size_t dcpq_search_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r, int chunk_queries);
+int dcpq_search(const float *queries, int nq, const float *codebooks, const float *derived, int m,
+                int dsub, const uint16_t *codes, uint64_t n_codes, uint32_t r, uint32_t k,
+                uint32_t *ids, float *dist, int chunk_queries, void *workspace,
+                size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DCPQ_H */

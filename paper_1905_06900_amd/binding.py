@@ -1,0 +1,187 @@
+"""Thin Python binding of libdcpq (see include/dcpq.h): argument marshalling only.
+
+torch supplies device memory and the current HIP stream; every step of the search runs inside
+the library's kernels.  Functions carry the names of the C entry points without the prefix.
+There is no CPU fallback: if the library has not been built, importing symbols from it raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libdcpq.so")
+
+OK, EINVAL, EWORKSPACE, EHIP, EUNSUPPORTED = 0, 1, 2, 3, 4
+PAD_ID = 0xFFFFFFFF
+
+
+class DcpqError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__("dcpq error %d: %s" % (code, msg))
+        self.code = code
+
+
+_lib = None
+
+_vp, _i, _u32, _u64, _sz = C.c_void_p, C.c_int, C.c_uint32, C.c_uint64, C.c_size_t
+
+_SIGNATURES = {
+    "dcpq_last_error": (C.c_char_p, []),
+    "dcpq_version": (_i, []),
+    "dcpq_shape_supported": (_i, [_i, _i]),
+    "dcpq_derive_codebooks": (_i, [_vp, _i, _i, _vp, _vp]),
+    "dcpq_build_small_tables": (_i, [_vp, _i, _vp, _i, _i, _vp, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "dcpq_build_tables": (_i, [_vp, _i, _vp, _i, _i, _vp, _vp]),
+    "dcpq_scan_workspace_bytes": (_sz, [_u64, _i, _i, _u32]),
+    "dcpq_scan_candidates": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_refine_workspace_bytes": (_sz, [_i, _u32]),
+    "dcpq_refine_topk": (_i, [_vp, _vp, _u64, _i, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_search_workspace_bytes": (_sz, [_u64, _i, _i, _u32, _i]),
+    "dcpq_search": (_i, [_vp, _i, _vp, _vp, _i, _i, _vp, _u64, _u32, _u32, _vp, _vp, _i, _vp, _sz, _vp]),
+}
+
+
+def exported_symbols() -> list[str]:
+    return sorted(_SIGNATURES)
+
+
+def lib() -> C.CDLL:
+    """Loads the built library; raises if it is missing (there is no fallback path)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                "%s not built: run `python -m paper_1905_06900_amd.build` (hipcc, gfx950)" % LIB_PATH)
+        l = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            f = getattr(l, name)
+            f.restype = res
+            f.argtypes = args
+        _lib = l
+    return _lib
+
+
+def _check(rc: int):
+    if rc != OK:
+        raise DcpqError(rc, lib().dcpq_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> int:
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError("%s must be a contiguous %s tensor on the GPU" % (name, dtype))
+    return t.data_ptr()
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def version() -> int:
+    return int(lib().dcpq_version())
+
+
+def derive_codebooks(codebooks: torch.Tensor) -> torch.Tensor:
+    m, k, dsub = codebooks.shape
+    assert k == 65536
+    out = torch.empty((m, 256, dsub), dtype=torch.float32, device=codebooks.device)
+    _check(lib().dcpq_derive_codebooks(_dev(codebooks, torch.float32, "codebooks"), m, dsub,
+                                       out.data_ptr(), _stream()))
+    return out
+
+
+def build_small_tables(queries: torch.Tensor, derived: torch.Tensor, codes: torch.Tensor, r: int,
+                       want_small: bool = False):
+    """-> (qtab u8 [nq][m][256], bounds f32 [nq][2], small f32 [nq][m][256] or None)"""
+    m, _, dsub = derived.shape
+    nq = queries.shape[0]
+    assert queries.shape[1] == m * dsub and codes.shape[1] == m
+    dev = queries.device
+    qtab = torch.empty((nq, m, 256), dtype=torch.uint8, device=dev)
+    bounds = torch.empty((nq, 2), dtype=torch.float32, device=dev)
+    small = torch.empty((nq, m, 256), dtype=torch.float32, device=dev) if want_small else None
+    _check(lib().dcpq_build_small_tables(
+        _dev(queries, torch.float32, "queries"), nq, _dev(derived, torch.float32, "derived"), m, dsub,
+        _dev(codes, torch.uint16, "codes"), codes.shape[0], r, qtab.data_ptr(), bounds.data_ptr(),
+        small.data_ptr() if small is not None else None, _stream()))
+    return qtab, bounds, small
+
+
+def build_tables(queries: torch.Tensor, codebooks: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    m, k, dsub = codebooks.shape
+    nq = queries.shape[0]
+    assert k == 65536 and queries.shape[1] == m * dsub
+    if out is None:
+        out = torch.empty((nq, m, 65536), dtype=torch.float32, device=queries.device)
+    _check(lib().dcpq_build_tables(_dev(queries, torch.float32, "queries"), nq,
+                                   _dev(codebooks, torch.float32, "codebooks"), m, dsub,
+                                   _dev(out, torch.float32, "tables"), _stream()))
+    return out
+
+
+def scan_workspace_bytes(n_codes: int, m: int, nq: int, r: int) -> int:
+    return int(lib().dcpq_scan_workspace_bytes(n_codes, m, nq, r))
+
+
+def scan_candidates(codes: torch.Tensor, qtab: torch.Tensor, r: int, workspace: torch.Tensor | None = None):
+    """-> (cand_id u32 [nq][r], cand_qd u8 [nq][r]) sorted by (qd, id)"""
+    n, m = codes.shape
+    nq = qtab.shape[0]
+    assert qtab.shape[1:] == (m, 256)
+    dev = codes.device
+    cand_id = torch.empty((nq, r), dtype=torch.uint32, device=dev)
+    cand_qd = torch.empty((nq, r), dtype=torch.uint8, device=dev)
+    if workspace is None:
+        workspace = _workspace(scan_workspace_bytes(n, m, nq, r), dev)
+    _check(lib().dcpq_scan_candidates(_dev(codes, torch.uint16, "codes"), n, m, _dev(qtab, torch.uint8, "qtab"),
+                                      nq, r, cand_id.data_ptr(), cand_qd.data_ptr(), workspace.data_ptr(),
+                                      workspace.numel(), _stream()))
+    return cand_id, cand_qd
+
+
+def refine_topk(tables: torch.Tensor, codes: torch.Tensor, cand_id: torch.Tensor, k: int,
+                workspace: torch.Tensor | None = None):
+    """-> (ids u32 [nq][k], dist f32 [nq][k]) ascending by (dist, id)"""
+    n, m = codes.shape
+    nq, r = cand_id.shape
+    assert tables.shape == (nq, m, 65536)
+    dev = codes.device
+    ids = torch.empty((nq, k), dtype=torch.uint32, device=dev)
+    dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = _workspace(lib().dcpq_refine_workspace_bytes(nq, r), dev)
+    _check(lib().dcpq_refine_topk(_dev(tables, torch.float32, "tables"), _dev(codes, torch.uint16, "codes"), n, m,
+                                  _dev(cand_id, torch.uint32, "cand_id"), nq, r, k, ids.data_ptr(),
+                                  dist.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    return ids, dist
+
+
+def search_workspace_bytes(n_codes: int, m: int, nq: int, r: int, chunk_queries: int = 0) -> int:
+    return int(lib().dcpq_search_workspace_bytes(n_codes, m, nq, r, chunk_queries))
+
+
+def search(queries: torch.Tensor, codebooks: torch.Tensor, derived: torch.Tensor, codes: torch.Tensor,
+           r: int, k: int, chunk_queries: int = 0, workspace: torch.Tensor | None = None,
+           ids: torch.Tensor | None = None, dist: torch.Tensor | None = None):
+    """Alg. 3 end to end without an index -> (ids u32 [nq][k], dist f32 [nq][k])"""
+    m, _, dsub = codebooks.shape
+    n = codes.shape[0]
+    nq = queries.shape[0]
+    dev = queries.device
+    if ids is None:
+        ids = torch.empty((nq, k), dtype=torch.uint32, device=dev)
+    if dist is None:
+        dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = _workspace(search_workspace_bytes(n, m, nq, r, chunk_queries), dev)
+    _check(lib().dcpq_search(_dev(queries, torch.float32, "queries"), nq,
+                             _dev(codebooks, torch.float32, "codebooks"), _dev(derived, torch.float32, "derived"),
+                             m, dsub, _dev(codes, torch.uint16, "codes"), n, r, k, ids.data_ptr(), dist.data_ptr(),
+                             chunk_queries, workspace.data_ptr(), workspace.numel(), _stream()))
+    return ids, dist

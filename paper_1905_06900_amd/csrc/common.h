@@ -1,0 +1,81 @@
+// Internal helpers shared by the translation units of libdcpq (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "dcpq.h"
+
+namespace dcpq {
+
+constexpr int kFullBits = 16;          // b: bits of a sub-code
+constexpr int kFullSize = 1 << 16;     // centroids per sub-quantizer
+constexpr int kSmallBits = 8;          // bbar: bits of a derived-codebook index
+constexpr int kSmallSize = 1 << 8;     // centroids per derived codebook
+constexpr int kWave = 64;              // wavefront width on gfx950
+
+// Records a message for dcpq_last_error() and returns `code`.
+int fail(int code, const char *fmt, ...);
+void clear_error();
+
+inline hipStream_t as_stream(void *s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+#define DCPQ_CHECK_HIP(expr)                                                                   \
+    do {                                                                                       \
+        hipError_t e_ = (expr);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return ::dcpq::fail(DCPQ_EHIP, "%s failed: %s", #expr, hipGetErrorString(e_));     \
+    } while (0)
+
+#define DCPQ_CHECK_LAUNCH(name)                                                                \
+    do {                                                                                       \
+        hipError_t e_ = hipGetLastError();                                                     \
+        if (e_ != hipSuccess)                                                                  \
+            return ::dcpq::fail(DCPQ_EHIP, "launch of %s failed: %s", name,                    \
+                                hipGetErrorString(e_));                                        \
+    } while (0)
+
+#define DCPQ_REQUIRE(cond, ...)                                                                \
+    do {                                                                                       \
+        if (!(cond)) return ::dcpq::fail(DCPQ_EINVAL, __VA_ARGS__);                            \
+    } while (0)
+
+inline bool m_supported(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16 || m == 32; }
+
+// Sortable 64-bit key: major part in the high word, vector id in the low word.
+__host__ __device__ inline uint64_t make_key(uint32_t major, uint32_t id)
+{
+    return (static_cast<uint64_t>(major) << 32) | id;
+}
+
+// Workspace layouts (offsets in bytes from a 256-byte aligned base).
+struct ScanPlan {
+    uint32_t unit;        // codes scanned by one wavefront
+    uint32_t nunits;      // ceil(n_codes / unit)
+    uint32_t qt;          // queries per workgroup tile
+    size_t off_hist;      // uint32 [nq][256]
+    size_t off_thr;       // uint32 [nq][2]   (threshold bucket, ids still needed from it)
+    size_t off_counter;   // uint32 [nq]
+    size_t off_tie;       // uint32 [nq][nunits]
+    size_t off_keys;      // uint64 [nq][r]
+    size_t off_spill;     // uint64 [nq][next_pow2(r)], present only when the sort spills to global memory
+    size_t total;
+};
+ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r);
+
+// Internal launchers used by dcpq_search (same contracts as the public calls, no validation).
+int launch_small_tables(const float *queries, int nq, const float *derived, int m, int dsub,
+                        const uint16_t *codes, uint64_t n_codes, uint32_t r, uint8_t *qtab,
+                        float *bounds, float *small, hipStream_t st);
+int launch_full_tables(const float *queries, int nq, const float *codebooks, int m, int dsub,
+                       float *tables, hipStream_t st);
+int launch_scan(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *ws, hipStream_t st);
+int launch_refine(const float *tables, const uint16_t *codes, int m, const uint32_t *cand_id,
+                  int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws,
+                  hipStream_t st);
+
+}  // namespace dcpq

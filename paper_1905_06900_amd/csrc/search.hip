@@ -1,0 +1,84 @@
+// Alg. 3 nns_derived end to end (no index): Tables -> Scan -> Refine for a batch of queries,
+// in chunks so that the full 2^16-entry tables of one chunk fit the workspace.
+#include "common.h"
+
+namespace dcpq {
+
+struct SearchPlan {
+    int chunk;
+    size_t off_qtab, off_bounds, off_cand_id, off_cand_qd, off_tables, off_scan, off_refine, total;
+};
+
+static SearchPlan plan_search(uint64_t n_codes, int m, int nq, uint32_t r, int chunk_queries)
+{
+    SearchPlan p{};
+    int chunk = chunk_queries;
+    if (chunk <= 0) {   // default: about 2 GiB of full tables per chunk
+        const size_t per_q = sizeof(float) * static_cast<size_t>(m) * kFullSize;
+        chunk = static_cast<int>((static_cast<size_t>(2) << 30) / per_q);
+        if (chunk < 64) chunk = 64;
+    }
+    if (chunk > nq) chunk = nq;
+    p.chunk = chunk;
+    size_t off = 0;
+    p.off_qtab = off;    off = align_up(off + static_cast<size_t>(chunk) * m * kSmallSize, 256);
+    p.off_bounds = off;  off = align_up(off + sizeof(float) * 2 * static_cast<size_t>(chunk), 256);
+    p.off_cand_id = off; off = align_up(off + sizeof(uint32_t) * static_cast<size_t>(chunk) * r, 256);
+    p.off_cand_qd = off; off = align_up(off + static_cast<size_t>(chunk) * r, 256);
+    p.off_tables = off;  off = align_up(off + sizeof(float) * static_cast<size_t>(chunk) * m * kFullSize, 256);
+    p.off_scan = off;    off = align_up(off + dcpq_scan_workspace_bytes(n_codes, m, chunk, r), 256);
+    p.off_refine = off;  off = align_up(off + dcpq_refine_workspace_bytes(chunk, r), 256);
+    p.total = off;
+    return p;
+}
+
+}  // namespace dcpq
+
+using namespace dcpq;
+
+extern "C" size_t dcpq_search_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r, int chunk_queries)
+{
+    if (nq <= 0 || !m_supported(m) || n_codes == 0 || r == 0) return 0;
+    return plan_search(n_codes, m, nq, r, chunk_queries).total;
+}
+
+extern "C" int dcpq_search(const float *queries, int nq, const float *codebooks, const float *derived, int m,
+                           int dsub, const uint16_t *codes, uint64_t n_codes, uint32_t r, uint32_t k,
+                           uint32_t *ids, float *dist, int chunk_queries, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    clear_error();
+    DCPQ_REQUIRE(nq >= 0, "search: nq=%d", nq);
+    if (!dcpq_shape_supported(m, dsub)) return fail(DCPQ_EUNSUPPORTED, "search: m=%d dsub=%d not supported", m, dsub);
+    DCPQ_REQUIRE(n_codes >= 1 && n_codes < (1ull << 32), "search: n_codes out of range");
+    DCPQ_REQUIRE(r >= 1 && r <= n_codes && k >= 1 && k <= r, "search: needs 1 <= k <= r <= n_codes");
+    if (nq == 0) return DCPQ_OK;
+    DCPQ_REQUIRE(queries && codebooks && derived && codes && ids && dist && workspace, "search: null pointer");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "search: workspace must be 256-byte aligned");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(codes) & 15) == 0, "search: codes must be 16-byte aligned");
+    const SearchPlan p = plan_search(n_codes, m, nq, r, chunk_queries);
+    if (workspace_bytes < p.total)
+        return fail(DCPQ_EWORKSPACE, "search: workspace %zu < %zu bytes", workspace_bytes, p.total);
+    uint8_t *base = static_cast<uint8_t *>(workspace);
+    uint8_t *qtab = base + p.off_qtab;
+    float *bounds = reinterpret_cast<float *>(base + p.off_bounds);
+    uint32_t *cand_id = reinterpret_cast<uint32_t *>(base + p.off_cand_id);
+    uint8_t *cand_qd = base + p.off_cand_qd;
+    float *tables = reinterpret_cast<float *>(base + p.off_tables);
+    hipStream_t st = as_stream(stream);
+    const int D = m * dsub;
+    for (int q0 = 0; q0 < nq; q0 += p.chunk) {
+        const int nc = (nq - q0 < p.chunk) ? nq - q0 : p.chunk;
+        const float *y = queries + static_cast<size_t>(q0) * D;
+        int rc = launch_small_tables(y, nc, derived, m, dsub, codes, n_codes, r, qtab, bounds, nullptr, st);
+        if (rc) return rc;
+        rc = launch_scan(codes, n_codes, m, qtab, nc, r, cand_id, cand_qd, base + p.off_scan, st);
+        if (rc) return rc;
+        rc = launch_full_tables(y, nc, codebooks, m, dsub, tables, st);
+        if (rc) return rc;
+        rc = launch_refine(tables, codes, m, cand_id, nc, r, k, ids + static_cast<size_t>(q0) * k,
+                           dist + static_cast<size_t>(q0) * k, base + p.off_refine, st);
+        if (rc) return rc;
+    }
+    return DCPQ_OK;
+}

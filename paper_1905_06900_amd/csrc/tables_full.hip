@@ -1,0 +1,127 @@
+// Full lookup tables of Alg. 1 / Eq. 1 for a batch of queries:
+//   tables[q][j][i] = || y_q^j - C_j[i] ||^2 = ||y_q^j||^2 + ||C_j[i]||^2 - 2 <y_q^j, C_j[i]>.
+// The inner products of (queries x 65536 centroids) per sub-quantizer are a dense contraction and
+// run on the matrix cores.  They run in DOUBLE precision (v_mfma_f64_16x16x4_f64): the expanded
+// form cancels (norms are 10-100x the distances on SIFT-like data), so fp32 products would not
+// hold 1e-5 relative, while fp64 costs nothing here -- K = dsub is tiny (12..60), so the kernel
+// is bound by writing the fp32 tables to HBM, not by the matrix pipe.  One rounding to fp32 at
+// the store.
+#include "common.h"
+
+namespace dcpq {
+
+typedef double double4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kTileQ = 64;     // queries per workgroup   (4 row tiles of 16)
+constexpr int kTileC = 256;    // centroids per workgroup (4 wavefronts x 64)
+
+// MFMA operand/result layout (16x16x4, fp64), lane l = 0..63:
+//   A (16x4):  row l % 16, column l / 16          B (4x16): row l / 16, column l % 16
+//   D (16x16): 4 values per lane, value v is row 4 * v + l / 16, column l % 16
+// Centroid columns are interleaved so that a lane ends up with 4 consecutive centroids of one
+// query row: column c of column-tile nt is centroid c * 4 + nt of the wavefront's 64, which
+// turns the stores into 16-byte vectors, 256 contiguous bytes per 16 lanes.
+__global__ __launch_bounds__(256) void full_tables_kernel(const float *__restrict__ queries, int nq,
+                                                          const float *__restrict__ cb, int m, int dsub,
+                                                          float *__restrict__ tables)
+{
+    __shared__ double ny[kTileQ];
+    __shared__ double nc[kTileC];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = blockIdx.z;
+    const int q0 = blockIdx.y * kTileQ;
+    const int c0 = blockIdx.x * kTileC;
+    const int D = m * dsub;
+    const float *cbj = cb + static_cast<size_t>(j) * kFullSize * dsub;
+
+    {   // squared norms in fp64: one centroid per thread, one query per thread of wave 0
+        const float *c = cbj + static_cast<size_t>(c0 + tid) * dsub;
+        double s = 0.0;
+        for (int t = 0; t < dsub; ++t) { const double v = c[t]; s += v * v; }
+        nc[tid] = s;
+        if (tid < kTileQ) {
+            double sy = 0.0;
+            if (q0 + tid < nq) {
+                const float *y = queries + static_cast<size_t>(q0 + tid) * D + j * dsub;
+                for (int t = 0; t < dsub; ++t) { const double v = y[t]; sy += v * v; }
+            }
+            ny[tid] = sy;
+        }
+    }
+
+    double4_t acc[4][4];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = double4_t{0.0, 0.0, 0.0, 0.0};
+
+    const int lr = lane & 15, lk = lane >> 4;
+    const int cw = c0 + wave * 64;                     // first centroid of this wavefront
+    for (int k0 = 0; k0 < dsub; k0 += 4) {
+        const int k = k0 + lk;
+        const bool kin = k < dsub;
+        double a[4], b[4];
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            const int q = q0 + mt * 16 + lr;
+            a[mt] = (kin && q < nq) ? static_cast<double>(queries[static_cast<size_t>(q) * D + j * dsub + k]) : 0.0;
+        }
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            const int c = cw + lr * 4 + nt;
+            b[nt] = kin ? static_cast<double>(cbj[static_cast<size_t>(c) * dsub + k]) : 0.0;
+        }
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+    }
+    __syncthreads();   // norms visible
+
+    const int cl = wave * 64 + lr * 4;                 // this lane's 4 centroids within the tile
+    const double n0 = nc[cl], n1 = nc[cl + 1], n2 = nc[cl + 2], n3 = nc[cl + 3];
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int ql = mt * 16 + v * 4 + lk;
+            const int q = q0 + ql;
+            if (q >= nq) continue;
+            const double yy = ny[ql];
+            float4 o;
+            o.x = static_cast<float>(fmax(0.0, (yy + n0) - 2.0 * acc[mt][0][v]));
+            o.y = static_cast<float>(fmax(0.0, (yy + n1) - 2.0 * acc[mt][1][v]));
+            o.z = static_cast<float>(fmax(0.0, (yy + n2) - 2.0 * acc[mt][2][v]));
+            o.w = static_cast<float>(fmax(0.0, (yy + n3) - 2.0 * acc[mt][3][v]));
+            float *dst = tables + (static_cast<size_t>(q) * m + j) * kFullSize + c0 + cl;
+            *reinterpret_cast<float4 *>(dst) = o;
+        }
+    }
+}
+
+int launch_full_tables(const float *queries, int nq, const float *codebooks, int m, int dsub,
+                       float *tables, hipStream_t st)
+{
+    if (nq == 0) return DCPQ_OK;
+    const dim3 grid(kFullSize / kTileC, (nq + kTileQ - 1) / kTileQ, m);
+    hipLaunchKernelGGL(full_tables_kernel, grid, dim3(256), 0, st, queries, nq, codebooks, m, dsub, tables);
+    DCPQ_CHECK_LAUNCH("full_tables_kernel");
+    return DCPQ_OK;
+}
+
+}  // namespace dcpq
+
+using namespace dcpq;
+
+extern "C" int dcpq_build_tables(const float *queries, int nq, const float *codebooks, int m, int dsub,
+                                 float *tables, void *stream)
+{
+    clear_error();
+    DCPQ_REQUIRE(nq >= 0, "build_tables: nq=%d", nq);
+    if (!dcpq_shape_supported(m, dsub)) return fail(DCPQ_EUNSUPPORTED, "build_tables: m=%d dsub=%d not supported", m, dsub);
+    if (nq == 0) return DCPQ_OK;
+    DCPQ_REQUIRE(queries && codebooks && tables, "build_tables: null pointer");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(tables) & 15) == 0, "build_tables: tables must be 16-byte aligned");
+    return launch_full_tables(queries, nq, codebooks, m, dsub, tables, as_stream(stream));
+}

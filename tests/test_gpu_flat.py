@@ -1,0 +1,189 @@
+"""GPU parity tests of the flat (no index) path, stage by stage, through the C ABI.
+
+Sizes: the oracle finishes each case in seconds, while N spans many scan units, several query
+tiles and ragged tails (N not a multiple of 64, Q not a multiple of the query tile)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1905_06900_amd import binding, synth
+from parity import FlatCase, to_np, assert_topk_matches, REL_TOL
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+def small_flat(cfg, N, Q, r, **kw):
+    return synth.scaled(synth.WORKLOADS[cfg], N=N, Q=Q, r=r, **kw)
+
+
+@pytest.fixture(scope="module")
+def case0():
+    print("case0: cfg0 recipe N=200003 Q=37 r=1000", flush=True)
+    return FlatCase(small_flat(0, 200_003, 37, 1000), DEV).run_stages().oracle()
+
+
+def test_cfg0_scaled_pass_one_bit_exact(case0):
+    case0.check_pass_one()
+
+
+def test_cfg0_scaled_pass_two(case0):
+    case0.check_pass_two()
+
+
+def test_cfg0_scaled_fused_search_matches_staged(case0):
+    c = case0
+    ids, dist = binding.search(c.queries, c.cb, c.derived, c.codes, c.w.r, c.w.k, chunk_queries=16)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(ids), to_np(c.ids))
+    np.testing.assert_array_equal(to_np(dist), to_np(c.dist))
+
+
+def test_full_tables_against_fp64_definition(case0):
+    c = case0
+    T = to_np(c.tables)
+    for q in (0, 17, 36):
+        want = oracle.compute_tables_f64(c.q_np[q], c.cb_np)
+        np.testing.assert_allclose(T[q], want, rtol=1e-6, atol=1e-30)
+
+
+@pytest.mark.parametrize("cfg,N,Q,r", [(2, 150_001, 21, 700), (4, 60_000, 9, 5000)])
+def test_random_code_recipes_scaled(cfg, N, Q, r):
+    # cfg 2's own recipe (random codes, Deep-like queries) and cfg 4's shape (m=16, dsub=60) with
+    # random codes instead of the encoded ones (encoding is exercised in the full-size test).
+    print("case: cfg%d N=%d Q=%d r=%d" % (cfg, N, Q, r), flush=True)
+    w = small_flat(cfg, N, Q, r)
+    if cfg == 4:
+        w = dataclasses.replace(w, data="deep_random_codes")
+        data = synth.make_flat(w, DEV)
+        # GIST-like queries and codebook scale for the 960-d shape
+        g = synth.WORKLOADS[4]
+        data["codebooks"] = synth.hierarchical_codebooks(g.m, g.dsub, 16, 4, synth._uniform(0.0, 0.3, DEV), 0.03, DEV, 5)
+        data["queries"] = synth.gist_like(Q, DEV, 6, 7).contiguous()
+        c = FlatCase(w, DEV, data)
+    else:
+        c = FlatCase(w, DEV)
+    c.run_stages().oracle()
+    c.check_pass_one()
+    c.check_pass_two()
+
+
+def test_sift_recipe_scaled_with_encoded_codes():
+    print("case: cfg1 recipe N=30000 Q=19 r=500 (nearest-centroid encoded)", flush=True)
+    c = FlatCase(small_flat(1, 30_000, 19, 500), DEV).run_stages().oracle()
+    c.check_pass_one()
+    c.check_pass_two()
+
+
+# ------------------------------------------------------------------------------------------------
+# edge cases of the scan / select
+# ------------------------------------------------------------------------------------------------
+def scan_vs_oracle(codes_np, qtab_np, r):
+    codes = torch.from_numpy(codes_np.view(np.int16)).to(DEV).view(torch.uint16)
+    qtab = torch.from_numpy(qtab_np).to(DEV)
+    cid, cqd = binding.scan_candidates(codes, qtab, r)
+    torch.cuda.synchronize()
+    cid, cqd = to_np(cid), to_np(cqd)
+    for q in range(qtab_np.shape[0]):
+        qd = oracle.adc_low_bits(codes_np, qtab_np[q])
+        wid, wqd = oracle.select(qd, r)
+        np.testing.assert_array_equal(cid[q], wid, err_msg="query %d ids" % q)
+        np.testing.assert_array_equal(cqd[q], wqd, err_msg="query %d qd" % q)
+
+
+@pytest.mark.parametrize("m", [1, 2, 4, 8, 16, 32])
+def test_scan_every_supported_m(m):
+    rng = np.random.default_rng(m)
+    N, Q, r = 70_001, 5, 333
+    codes = rng.integers(0, 65536, size=(N, m)).astype(np.uint16)
+    qtab = rng.integers(0, 256 // m + 8, size=(Q, m, 256)).astype(np.uint8)
+    print("scan m=%d N=%d" % (m, N), flush=True)
+    scan_vs_oracle(codes, qtab, r)
+
+
+@pytest.mark.parametrize("N,r", [(1, 1), (63, 63), (64, 1), (65, 65), (1000, 1000), (5000, 4097), (20000, 9000)])
+def test_scan_tiny_and_r_equal_n(N, r):
+    rng = np.random.default_rng(N)
+    codes = rng.integers(0, 65536, size=(N, 8)).astype(np.uint16)
+    qtab = rng.integers(0, 40, size=(3, 8, 256)).astype(np.uint8)
+    print("scan N=%d r=%d" % (N, r), flush=True)
+    scan_vs_oracle(codes, qtab, r)
+
+
+def test_scan_giant_ties_and_saturation():
+    rng = np.random.default_rng(99)
+    N, r = 100_000, 2000
+    codes = rng.integers(0, 65536, size=(N, 8)).astype(np.uint16)
+    qtab = np.zeros((4, 8, 256), np.uint8)
+    qtab[1] = 255                                    # every qd saturates at 255
+    qtab[2, 0, :] = (np.arange(256) % 2) * 3         # two buckets only: 0 and 3
+    qtab[3] = rng.integers(0, 2, size=(8, 256))      # ~9 buckets, huge ties
+    codes[:, :] = codes[:, :]                        # keep random
+    print("scan giant ties", flush=True)
+    scan_vs_oracle(codes, qtab, r)
+    codes[:] = 7                                     # all codes identical: one bucket holds everything
+    scan_vs_oracle(codes, qtab, r)
+
+
+def test_small_tables_edges_degenerate_range_and_r_beyond_n():
+    rng = np.random.default_rng(5)
+    m, dsub = 8, 16
+    cb = torch.from_numpy((rng.normal(size=(m, 65536, dsub)) * 10).astype(np.float32)).to(DEV)
+    derived = binding.derive_codebooks(cb)
+    queries = torch.from_numpy((rng.normal(size=(3, m * dsub)) * 10).astype(np.float32)).to(DEV)
+    dnp = oracle.derive_codebooks(to_np(cb))
+    np.testing.assert_array_equal(to_np(derived), dnp)
+    # (a) r beyond the number of codes: bounds use all codes
+    codes_np = rng.integers(0, 65536, size=(50, m)).astype(np.uint16)
+    codes = torch.from_numpy(codes_np.view(np.int16)).to(DEV).view(torch.uint16)
+    qtab, bounds, small = binding.build_small_tables(queries, derived, codes, 1000, want_small=True)
+    torch.cuda.synchronize()
+    for q in range(3):
+        D = oracle.compute_tables_f32(to_np(queries)[q], dnp)
+        lo, hi = oracle.bounds(D, codes_np, 50)
+        np.testing.assert_array_equal(to_np(small)[q], D)
+        assert tuple(to_np(bounds)[q]) == (lo, hi)
+        np.testing.assert_array_equal(to_np(qtab)[q], oracle.quantize(D, lo, hi))
+    # (b) degenerate range: m = 1 and the only code seen is the arg-min entry -> qmax == qmin
+    cb1 = cb[:1].contiguous(); d1 = binding.derive_codebooks(cb1)
+    y1 = queries[:, :dsub].contiguous()
+    D = oracle.compute_tables_f32(to_np(y1)[0], to_np(d1))
+    amin = int(D.argmin())
+    c1 = torch.full((10, 1), amin, dtype=torch.int16, device=DEV).view(torch.uint16)
+    qtab, bounds, _ = binding.build_small_tables(y1[:1].contiguous(), d1, c1, 10)
+    torch.cuda.synchronize()
+    assert to_np(bounds)[0, 0] == to_np(bounds)[0, 1]
+    assert (to_np(qtab) == 0).all()
+
+
+def test_argument_errors_are_reported_not_launched():
+    codes = torch.zeros((100, 8), dtype=torch.int16, device=DEV).view(torch.uint16)
+    qtab = torch.zeros((2, 8, 256), dtype=torch.uint8, device=DEV)
+    with pytest.raises(binding.DcpqError) as e:
+        binding.scan_candidates(codes, qtab, 101)            # r > N
+    assert e.value.code == binding.EINVAL
+    with pytest.raises(binding.DcpqError) as e:
+        binding.scan_candidates(codes, qtab, 10, workspace=torch.empty(256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == binding.EWORKSPACE
+    codes3 = torch.zeros((100, 3), dtype=torch.int16, device=DEV).view(torch.uint16)
+    qtab3 = torch.zeros((2, 3, 256), dtype=torch.uint8, device=DEV)
+    with pytest.raises(binding.DcpqError) as e:
+        binding.scan_candidates(codes3, qtab3, 10)            # m = 3 not built
+    assert e.value.code == binding.EUNSUPPORTED
+    tables = torch.zeros((2, 8, 65536), dtype=torch.float32, device=DEV)
+    cand = torch.zeros((2, 10), dtype=torch.int32, device=DEV).view(torch.uint32)
+    with pytest.raises(binding.DcpqError) as e:
+        binding.refine_topk(tables, codes, cand, 11)          # k > r
+    assert e.value.code == binding.EINVAL
+
+
+def test_determinism_two_runs_identical(case0):
+    c = case0
+    a_id, a_qd = binding.scan_candidates(c.codes, c.qtab, c.w.r)
+    b_id, b_qd = binding.scan_candidates(c.codes, c.qtab, c.w.r)
+    torch.cuda.synchronize()
+    assert torch.equal(a_id.view(torch.int32), b_id.view(torch.int32)) and torch.equal(a_qd, b_qd)
