@@ -97,6 +97,8 @@ int dcpq_build_tables(const float *queries, int nq, const float *codebooks, int 
  * Requires 1 <= r <= n_codes < 2^32.
  * ------------------------------------------------------------------------------------------- */
 size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r);
+/* Queries that share one pass over the codes inside the scan kernels (their tables sit in LDS). */
+int dcpq_scan_query_tile(int m);
 int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                          uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
                          size_t workspace_bytes, void *stream);
@@ -125,10 +127,25 @@ int dcpq_refine_topk(const float *tables, const uint16_t *codes, uint64_t n_code
  *   workspace : at least dcpq_search_workspace_bytes(...) bytes
  * ------------------------------------------------------------------------------------------- */
 size_t dcpq_search_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r, int chunk_queries);
+/* Queries per chunk dcpq_search will use for this shape (chunk_queries = 0: the default). */
+int dcpq_search_chunk(int m, int nq, int chunk_queries);
 int dcpq_search(const float *queries, int nq, const float *codebooks, const float *derived, int m,
                 int dsub, const uint16_t *codes, uint64_t n_codes, uint32_t r, uint32_t k,
                 uint32_t *ids, float *dist, int chunk_queries, void *workspace,
                 size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Optional per-kernel timing (measurement aid, not part of the search).  While enabled, every
+ * kernel the library launches is bracketed by two HIP events recorded on the stream it is launched
+ * on.  dcpq_profile_enable(on) clears the accumulated figures; dcpq_profile_read waits for the
+ * pending events (it synchronises with them) and returns the total milliseconds and the number of
+ * launches of one stage; stage names come from dcpq_profile_stage_name(0 .. stage_count-1).
+ * total_ms and launches are HOST pointers.
+ * ------------------------------------------------------------------------------------------- */
+int dcpq_profile_enable(int on);
+int dcpq_profile_stage_count(void);
+const char *dcpq_profile_stage_name(int stage);
+int dcpq_profile_read(int stage, double *total_ms, uint64_t *launches);
 
 #ifdef __cplusplus
 }

@@ -37,9 +37,15 @@ _SIGNATURES = {
     "dcpq_build_tables": (_i, [_vp, _i, _vp, _i, _i, _vp, _vp]),
     "dcpq_scan_workspace_bytes": (_sz, [_u64, _i, _i, _u32]),
     "dcpq_scan_candidates": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_scan_query_tile": (_i, [_i]),
+    "dcpq_search_chunk": (_i, [_i, _i, _i]),
     "dcpq_refine_workspace_bytes": (_sz, [_i, _u32]),
     "dcpq_refine_topk": (_i, [_vp, _vp, _u64, _i, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_search_workspace_bytes": (_sz, [_u64, _i, _i, _u32, _i]),
+    "dcpq_profile_enable": (_i, [_i]),
+    "dcpq_profile_stage_count": (_i, []),
+    "dcpq_profile_stage_name": (C.c_char_p, [_i]),
+    "dcpq_profile_read": (_i, [_i, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]),
     "dcpq_search": (_i, [_vp, _i, _vp, _vp, _i, _i, _vp, _u64, _u32, _u32, _vp, _vp, _i, _vp, _sz, _vp]),
 }
 
@@ -129,6 +135,14 @@ def scan_workspace_bytes(n_codes: int, m: int, nq: int, r: int) -> int:
     return int(lib().dcpq_scan_workspace_bytes(n_codes, m, nq, r))
 
 
+def scan_query_tile(m: int) -> int:
+    return int(lib().dcpq_scan_query_tile(m))
+
+
+def search_chunk(m: int, nq: int, chunk_queries: int = 0) -> int:
+    return int(lib().dcpq_search_chunk(m, nq, chunk_queries))
+
+
 def scan_candidates(codes: torch.Tensor, qtab: torch.Tensor, r: int, workspace: torch.Tensor | None = None):
     """-> (cand_id u32 [nq][r], cand_qd u8 [nq][r]) sorted by (qd, id)"""
     n, m = codes.shape
@@ -185,3 +199,18 @@ def search(queries: torch.Tensor, codebooks: torch.Tensor, derived: torch.Tensor
                              m, dsub, _dev(codes, torch.uint16, "codes"), n, r, k, ids.data_ptr(), dist.data_ptr(),
                              chunk_queries, workspace.data_ptr(), workspace.numel(), _stream()))
     return ids, dist
+
+
+def profile_enable(on: bool) -> None:
+    _check(lib().dcpq_profile_enable(1 if on else 0))
+
+
+def profile_read() -> dict:
+    """{stage name: (total milliseconds, launches)} since profile_enable(True)."""
+    out = {}
+    l = lib()
+    for s in range(l.dcpq_profile_stage_count()):
+        ms, n = C.c_double(), C.c_uint64()
+        _check(l.dcpq_profile_read(s, C.byref(ms), C.byref(n)))
+        out[l.dcpq_profile_stage_name(s).decode()] = (ms.value, int(n.value))
+    return out

@@ -43,6 +43,25 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
         if (!(cond)) return ::dcpq::fail(DCPQ_EINVAL, __VA_ARGS__);                            \
     } while (0)
 
+// Stages reported by the optional event-based profiler (dcpq_profile_*).
+enum Stage {
+    kStageSmallTables = 0, kStageScanHist, kStageScanTieCount, kStageScanCollect, kStageScanFast,
+    kStageSelect, kStageFullTables, kStageRefine, kStageIvf, kStageMisc, kNumStages
+};
+namespace prof {
+bool enabled();
+void *begin(int stage, hipStream_t st);      // returns a token for end(), or nullptr when disabled
+void end(void *token, hipStream_t st);
+}  // namespace prof
+
+// Launches a kernel, bracketed by profiler events when profiling is on.
+#define DCPQ_LAUNCH(stage, st, kernel, grid, block, lds, ...)                                  \
+    do {                                                                                       \
+        void *tok_ = ::dcpq::prof::begin(stage, st);                                           \
+        hipLaunchKernelGGL(kernel, grid, block, lds, st, __VA_ARGS__);                         \
+        ::dcpq::prof::end(tok_, st);                                                           \
+    } while (0)
+
 inline bool m_supported(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16 || m == 32; }
 
 // Sortable 64-bit key: major part in the high word, vector id in the low word.

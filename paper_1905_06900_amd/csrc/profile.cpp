@@ -1,0 +1,96 @@
+// Optional per-kernel timing: when enabled, every kernel launch of the library is bracketed by
+// two HIP events recorded on the stream the kernel is launched on; dcpq_profile_read() waits for
+// the pending events and returns accumulated milliseconds and launch counts per stage.
+#include <mutex>
+#include <vector>
+
+#include "common.h"
+
+namespace dcpq {
+namespace prof {
+
+static const char *const kNames[kNumStages] = {
+    "small_tables", "scan_hist", "scan_tiecount", "scan_collect", "scan_fast", "select", "full_tables",
+    "refine_topk", "ivf", "misc",
+};
+
+struct Pending { int stage; hipEvent_t a, b; };
+
+static std::mutex g_mu;
+static bool g_on = false;
+static std::vector<Pending> g_pending;
+static std::vector<hipEvent_t> g_free;
+static double g_ms[kNumStages];
+static uint64_t g_count[kNumStages];
+
+bool enabled() { return g_on; }
+
+static hipEvent_t get_event()
+{
+    if (!g_free.empty()) { hipEvent_t e = g_free.back(); g_free.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+void *begin(int stage, hipStream_t st)
+{
+    if (!g_on) return nullptr;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Pending p{stage, get_event(), get_event()};
+    if (!p.a || !p.b) return nullptr;
+    (void)hipEventRecord(p.a, st);
+    g_pending.push_back(p);
+    return p.b;
+}
+
+void end(void *token, hipStream_t st)
+{
+    if (token) (void)hipEventRecord(static_cast<hipEvent_t>(token), st);
+}
+
+static void drain()
+{
+    for (const Pending &p : g_pending) {
+        float ms = 0.f;
+        if (hipEventSynchronize(p.b) == hipSuccess && hipEventElapsedTime(&ms, p.a, p.b) == hipSuccess) {
+            g_ms[p.stage] += ms;
+            g_count[p.stage] += 1;
+        }
+        g_free.push_back(p.a);
+        g_free.push_back(p.b);
+    }
+    g_pending.clear();
+}
+
+}  // namespace prof
+}  // namespace dcpq
+
+using namespace dcpq;
+
+extern "C" int dcpq_profile_enable(int on)
+{
+    std::lock_guard<std::mutex> lk(prof::g_mu);
+    prof::drain();
+    for (int s = 0; s < kNumStages; ++s) { prof::g_ms[s] = 0.0; prof::g_count[s] = 0; }
+    prof::g_on = on != 0;
+    return DCPQ_OK;
+}
+
+extern "C" int dcpq_profile_stage_count(void) { return kNumStages; }
+
+extern "C" const char *dcpq_profile_stage_name(int stage)
+{
+    return (stage >= 0 && stage < kNumStages) ? prof::kNames[stage] : "";
+}
+
+extern "C" int dcpq_profile_read(int stage, double *total_ms, uint64_t *launches)
+{
+    clear_error();
+    DCPQ_REQUIRE(stage >= 0 && stage < kNumStages && total_ms && launches, "profile_read: bad argument");
+    std::lock_guard<std::mutex> lk(prof::g_mu);
+    prof::drain();
+    *total_ms = prof::g_ms[stage];
+    *launches = prof::g_count[stage];
+    return DCPQ_OK;
+}

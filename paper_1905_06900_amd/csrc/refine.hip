@@ -77,8 +77,8 @@ int launch_refine(const float *tables, const uint16_t *codes, int m, const uint3
     uint64_t *spill = static_cast<uint64_t *>(ws);
 #define DCPQ_LAUNCH_REFINE(MV)                                                                            \
     case MV:                                                                                              \
-        hipLaunchKernelGGL(refine_topk_kernel<MV>, dim3(nq), dim3(1024), lds, st, tables, codes, cand_id, \
-                           r, k, np2, use_lds, spill, ids, dist);                                         \
+        DCPQ_LAUNCH(kStageRefine, st, refine_topk_kernel<MV>, dim3(nq), dim3(1024), lds, tables, codes,   \
+                    cand_id, r, k, np2, use_lds, spill, ids, dist);                                       \
         break;
     switch (m) {
         DCPQ_LAUNCH_REFINE(1) DCPQ_LAUNCH_REFINE(2) DCPQ_LAUNCH_REFINE(4) DCPQ_LAUNCH_REFINE(8)

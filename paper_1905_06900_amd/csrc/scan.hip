@@ -304,28 +304,28 @@ static int launch_scan_m(const uint16_t *codes, uint64_t n_codes, const uint8_t 
 
     // hist, thr and counter are contiguous at the head of the workspace: one clear.
     const size_t nwords = p.off_tie / sizeof(uint32_t);
-    hipLaunchKernelGGL(zero_words_kernel, dim3((nwords + 255) / 256), dim3(256), 0, st,
-                       reinterpret_cast<uint32_t *>(base), nwords);
+    DCPQ_LAUNCH(kStageMisc, st, zero_words_kernel, dim3((nwords + 255) / 256), dim3(256), 0,
+                reinterpret_cast<uint32_t *>(base), nwords);
     DCPQ_CHECK_LAUNCH("zero_words_kernel");
 
     const dim3 grid((p.nunits + kScanWaves - 1) / kScanWaves, (nq + QT - 1) / QT);
     const size_t lds_tab = static_cast<size_t>(QT) * M * 256;
-    hipLaunchKernelGGL((scan_kernel<M, QT, kHist>), grid, dim3(kScanThreads), lds_tab + QT * 256 * 4, st, codes,
-                       n_codes, p.unit, p.nunits, qtab, nq, r, hist, thr, tie, counter, keys);
+    DCPQ_LAUNCH(kStageScanHist, st, (scan_kernel<M, QT, kHist>), grid, dim3(kScanThreads), lds_tab + QT * 256 * 4,
+                codes, n_codes, p.unit, p.nunits, qtab, nq, r, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("scan_kernel<hist>");
-    hipLaunchKernelGGL(threshold_kernel, dim3(nq), dim3(256), 0, st, hist, r, thr);
+    DCPQ_LAUNCH(kStageSelect, st, threshold_kernel, dim3(nq), dim3(256), 0, hist, r, thr);
     DCPQ_CHECK_LAUNCH("threshold_kernel");
-    hipLaunchKernelGGL((scan_kernel<M, QT, kTieCount>), grid, dim3(kScanThreads), lds_tab, st, codes, n_codes,
-                       p.unit, p.nunits, qtab, nq, r, hist, thr, tie, counter, keys);
+    DCPQ_LAUNCH(kStageScanTieCount, st, (scan_kernel<M, QT, kTieCount>), grid, dim3(kScanThreads), lds_tab, codes,
+                n_codes, p.unit, p.nunits, qtab, nq, r, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("scan_kernel<tiecount>");
-    hipLaunchKernelGGL(tie_quota_kernel, dim3(nq), dim3(256), 0, st, tie, p.nunits, thr);
+    DCPQ_LAUNCH(kStageSelect, st, tie_quota_kernel, dim3(nq), dim3(256), 0, tie, p.nunits, thr);
     DCPQ_CHECK_LAUNCH("tie_quota_kernel");
-    hipLaunchKernelGGL((scan_kernel<M, QT, kCollect>), grid, dim3(kScanThreads), lds_tab, st, codes, n_codes,
-                       p.unit, p.nunits, qtab, nq, r, hist, thr, tie, counter, keys);
+    DCPQ_LAUNCH(kStageScanCollect, st, (scan_kernel<M, QT, kCollect>), grid, dim3(kScanThreads), lds_tab, codes,
+                n_codes, p.unit, p.nunits, qtab, nq, r, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("scan_kernel<collect>");
     const uint32_t np2 = next_pow2(r);
-    hipLaunchKernelGGL(sort_candidates_kernel, dim3(nq), dim3(1024), spill ? 0 : sizeof(uint64_t) * np2, st, keys,
-                       r, np2, spill ? 0 : 1, sorted, cand_id, cand_qd);
+    DCPQ_LAUNCH(kStageSelect, st, sort_candidates_kernel, dim3(nq), dim3(1024), spill ? 0 : sizeof(uint64_t) * np2,
+                keys, r, np2, spill ? 0 : 1, sorted, cand_id, cand_qd);
     DCPQ_CHECK_LAUNCH("sort_candidates_kernel");
     return DCPQ_OK;
 }
@@ -348,6 +348,8 @@ int launch_scan(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *q
 }  // namespace dcpq
 
 using namespace dcpq;
+
+extern "C" int dcpq_scan_query_tile(int m) { return m_supported(m) ? scan_qt(m) : 0; }
 
 extern "C" size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r)
 {

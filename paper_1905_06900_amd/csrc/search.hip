@@ -36,6 +36,12 @@ static SearchPlan plan_search(uint64_t n_codes, int m, int nq, uint32_t r, int c
 
 using namespace dcpq;
 
+extern "C" int dcpq_search_chunk(int m, int nq, int chunk_queries)
+{
+    if (nq <= 0 || !m_supported(m)) return 0;
+    return plan_search(1, m, nq, 1, chunk_queries).chunk;
+}
+
 extern "C" size_t dcpq_search_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r, int chunk_queries)
 {
     if (nq <= 0 || !m_supported(m) || n_codes == 0 || r == 0) return 0;

@@ -105,7 +105,7 @@ int launch_full_tables(const float *queries, int nq, const float *codebooks, int
 {
     if (nq == 0) return DCPQ_OK;
     const dim3 grid(kFullSize / kTileC, (nq + kTileQ - 1) / kTileQ, m);
-    hipLaunchKernelGGL(full_tables_kernel, grid, dim3(256), 0, st, queries, nq, codebooks, m, dsub, tables);
+    DCPQ_LAUNCH(kStageFullTables, st, full_tables_kernel, grid, dim3(256), 0, queries, nq, codebooks, m, dsub, tables);
     DCPQ_CHECK_LAUNCH("full_tables_kernel");
     return DCPQ_OK;
 }

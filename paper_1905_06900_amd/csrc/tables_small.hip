@@ -103,8 +103,8 @@ int launch_small_tables(const float *queries, int nq, const float *derived, int 
     const size_t lds = sizeof(float) * (static_cast<size_t>(m) * dsub + static_cast<size_t>(m) * kSmallSize);
 #define DCPQ_LAUNCH_SMALL(MV)                                                                        \
     case MV:                                                                                         \
-        hipLaunchKernelGGL(small_tables_kernel<MV>, dim3(nq), dim3(256), lds, st, queries, derived, \
-                           dsub, codes, n_first, qtab, bounds, small);                              \
+        DCPQ_LAUNCH(kStageSmallTables, st, small_tables_kernel<MV>, dim3(nq), dim3(256), lds, queries,   \
+                    derived, dsub, codes, n_first, qtab, bounds, small);                             \
         break;
     switch (m) {
         DCPQ_LAUNCH_SMALL(1) DCPQ_LAUNCH_SMALL(2) DCPQ_LAUNCH_SMALL(4) DCPQ_LAUNCH_SMALL(8)
