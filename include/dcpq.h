@@ -102,6 +102,16 @@ int dcpq_scan_query_tile(int m);
 int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                          uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
                          size_t workspace_bytes, void *stream);
+/* Same call with the algorithm chosen by the caller (same outputs either way):
+ *   DCPQ_SCAN_AUTO        single pass over the codes with a running bucket bound (the paper's
+ *                         capped-buckets upper bound); queries whose candidate buffer overflows are
+ *                         redone by the three-pass algorithm.  m = 1, 2 always use three passes.
+ *   DCPQ_SCAN_THREE_PASS  histogram pass, tie-count pass, collect pass: exact for any input. */
+#define DCPQ_SCAN_AUTO 0
+#define DCPQ_SCAN_THREE_PASS 1
+int dcpq_scan_candidates_mode(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                              uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
+                              size_t workspace_bytes, int mode, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * refine_topk -- Sec. 3.3 "Refine step" (Alg. 3 refine / adc_refine, Eq. 2): exact re-ranking of

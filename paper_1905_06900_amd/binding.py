@@ -39,6 +39,7 @@ _SIGNATURES = {
     "dcpq_scan_candidates": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_scan_query_tile": (_i, [_i]),
     "dcpq_search_chunk": (_i, [_i, _i, _i]),
+    "dcpq_scan_candidates_mode": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp, _sz, _i, _vp]),
     "dcpq_refine_workspace_bytes": (_sz, [_i, _u32]),
     "dcpq_refine_topk": (_i, [_vp, _vp, _u64, _i, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_search_workspace_bytes": (_sz, [_u64, _i, _i, _u32, _i]),
@@ -143,7 +144,11 @@ def search_chunk(m: int, nq: int, chunk_queries: int = 0) -> int:
     return int(lib().dcpq_search_chunk(m, nq, chunk_queries))
 
 
-def scan_candidates(codes: torch.Tensor, qtab: torch.Tensor, r: int, workspace: torch.Tensor | None = None):
+SCAN_AUTO, SCAN_THREE_PASS = 0, 1
+
+
+def scan_candidates(codes: torch.Tensor, qtab: torch.Tensor, r: int, workspace: torch.Tensor | None = None,
+                    mode: int = SCAN_AUTO):
     """-> (cand_id u32 [nq][r], cand_qd u8 [nq][r]) sorted by (qd, id)"""
     n, m = codes.shape
     nq = qtab.shape[0]
@@ -153,9 +158,15 @@ def scan_candidates(codes: torch.Tensor, qtab: torch.Tensor, r: int, workspace: 
     cand_qd = torch.empty((nq, r), dtype=torch.uint8, device=dev)
     if workspace is None:
         workspace = _workspace(scan_workspace_bytes(n, m, nq, r), dev)
-    _check(lib().dcpq_scan_candidates(_dev(codes, torch.uint16, "codes"), n, m, _dev(qtab, torch.uint8, "qtab"),
-                                      nq, r, cand_id.data_ptr(), cand_qd.data_ptr(), workspace.data_ptr(),
-                                      workspace.numel(), _stream()))
+    if mode == SCAN_AUTO:
+        _check(lib().dcpq_scan_candidates(_dev(codes, torch.uint16, "codes"), n, m, _dev(qtab, torch.uint8, "qtab"),
+                                          nq, r, cand_id.data_ptr(), cand_qd.data_ptr(), workspace.data_ptr(),
+                                          workspace.numel(), _stream()))
+    else:
+        _check(lib().dcpq_scan_candidates_mode(_dev(codes, torch.uint16, "codes"), n, m,
+                                               _dev(qtab, torch.uint8, "qtab"), nq, r, cand_id.data_ptr(),
+                                               cand_qd.data_ptr(), workspace.data_ptr(), workspace.numel(), mode,
+                                               _stream()))
     return cand_id, cand_qd
 
 

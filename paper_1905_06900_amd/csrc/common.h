@@ -70,31 +70,17 @@ __host__ __device__ inline uint64_t make_key(uint32_t major, uint32_t id)
     return (static_cast<uint64_t>(major) << 32) | id;
 }
 
-// Workspace layouts (offsets in bytes from a 256-byte aligned base).
-struct ScanPlan {
-    uint32_t unit;        // codes scanned by one wavefront
-    uint32_t nunits;      // ceil(n_codes / unit)
-    uint32_t qt;          // queries per workgroup tile
-    size_t off_hist;      // uint32 [nq][256]
-    size_t off_thr;       // uint32 [nq][2]   (threshold bucket, ids still needed from it)
-    size_t off_counter;   // uint32 [nq]
-    size_t off_tie;       // uint32 [nq][nunits]
-    size_t off_keys;      // uint64 [nq][r]
-    size_t off_spill;     // uint64 [nq][next_pow2(r)], present only when the sort spills to global memory
-    size_t total;
-};
-ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r);
-
 // Internal launchers used by dcpq_search (same contracts as the public calls, no validation).
 int launch_small_tables(const float *queries, int nq, const float *derived, int m, int dsub,
                         const uint16_t *codes, uint64_t n_codes, uint32_t r, uint8_t *qtab,
                         float *bounds, float *small, hipStream_t st);
 int launch_full_tables(const float *queries, int nq, const float *codebooks, int m, int dsub,
                        float *tables, hipStream_t st);
+// mode: DCPQ_SCAN_AUTO or DCPQ_SCAN_THREE_PASS
 int launch_scan(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
-                uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *ws, hipStream_t st);
-int launch_refine(const float *tables, const uint16_t *codes, int m, const uint32_t *cand_id,
-                  int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws,
-                  hipStream_t st);
+                uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st);
+int launch_refine(const float *tables, const uint16_t *codes, uint64_t n_codes, int m,
+                  const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist,
+                  void *ws, hipStream_t st);
 
 }  // namespace dcpq

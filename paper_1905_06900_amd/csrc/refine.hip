@@ -35,7 +35,7 @@ __device__ inline void bitonic_sort_keys(uint64_t *a, uint32_t n_pow2)
 
 template <int M>
 __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restrict__ tables,
-                                                          const uint16_t *__restrict__ codes,
+                                                          const uint16_t *__restrict__ codes, uint32_t n_codes,
                                                           const uint32_t *__restrict__ cand_id, uint32_t r,
                                                           uint32_t k, uint32_t n_pow2, int use_lds,
                                                           uint64_t *__restrict__ spill,
@@ -49,7 +49,7 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
         uint64_t key = ~0ull;
         if (t < r) {
             const uint32_t id = cand_id[static_cast<size_t>(q) * r + t];
-            if (id != DCPQ_PAD_ID) {
+            if (id < n_codes) {                 // pad slots (and anything out of range) sort last
                 const uint16_t *c = codes + static_cast<size_t>(id) * M;
                 float d = tq[c[0]];
 #pragma unroll
@@ -67,8 +67,8 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
     }
 }
 
-int launch_refine(const float *tables, const uint16_t *codes, int m, const uint32_t *cand_id, int nq,
-                  uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws, hipStream_t st)
+int launch_refine(const float *tables, const uint16_t *codes, uint64_t n_codes, int m, const uint32_t *cand_id,
+                  int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws, hipStream_t st)
 {
     if (nq == 0) return DCPQ_OK;
     const uint32_t np2 = next_pow2_r(r);
@@ -78,7 +78,7 @@ int launch_refine(const float *tables, const uint16_t *codes, int m, const uint3
 #define DCPQ_LAUNCH_REFINE(MV)                                                                            \
     case MV:                                                                                              \
         DCPQ_LAUNCH(kStageRefine, st, refine_topk_kernel<MV>, dim3(nq), dim3(1024), lds, tables, codes,   \
-                    cand_id, r, k, np2, use_lds, spill, ids, dist);                                       \
+                    static_cast<uint32_t>(n_codes), cand_id, r, k, np2, use_lds, spill, ids, dist);       \
         break;
     switch (m) {
         DCPQ_LAUNCH_REFINE(1) DCPQ_LAUNCH_REFINE(2) DCPQ_LAUNCH_REFINE(4) DCPQ_LAUNCH_REFINE(8)
@@ -115,5 +115,5 @@ extern "C" int dcpq_refine_topk(const float *tables, const uint16_t *codes, uint
     const size_t need = dcpq_refine_workspace_bytes(nq, r);
     if (need && (!workspace || workspace_bytes < need))
         return fail(DCPQ_EWORKSPACE, "refine_topk: workspace %zu < %zu bytes", workspace_bytes, need);
-    return launch_refine(tables, codes, m, cand_id, nq, r, k, ids, dist, workspace, as_stream(stream));
+    return launch_refine(tables, codes, n_codes, m, cand_id, nq, r, k, ids, dist, workspace, as_stream(stream));
 }

@@ -4,18 +4,24 @@
 // The paper's capped buckets (one bucket per integer distance 0..254, ids appended in list
 // order, read out by increasing bucket) have an order-independent meaning: a 256-bin histogram
 // of qd fixes the threshold bucket T that holds the r-th candidate; every id with qd < T is a
-// candidate and bucket T contributes its smallest ids.  That is what is computed here, exactly
-// and deterministically, in three streaming passes over the codes:
+// candidate and bucket T contributes its smallest ids.
+//
+// This file holds (a) the THREE-PASS path, which computes exactly that for any input in three
+// streaming passes over the codes:
 //   pass A  histogram of qd per query                       -> T and the number still needed from T
 //   pass B  per (query, scan unit) count of qd == T         -> quota of bucket T per unit (prefix in id order)
 //   pass C  collect ids with qd < T, and the first `quota` ids of bucket T in each unit
-// followed by a per-query sort of the r keys (qd, id).
+// followed by a per-query sort of the r keys (qd, id); and (b) the driver that runs the
+// single-pass kernel of scan_fast.hip first and sends only the queries it flags through (a).
 //
-// Work layout: a wavefront owns one "unit" of consecutive codes and walks it 64 codes at a time
-// (lane = code, fully coalesced 2m-byte loads), so id order inside a unit is (iteration, lane).
-// A workgroup is 4 wavefronts and serves a tile of QT queries whose u8 tables (QT * m * 256
-// bytes) sit in LDS; each lane gathers its m table bytes per query from LDS.
+// Three-pass work layout: a wavefront owns one "unit" of consecutive codes and walks it 64 codes
+// at a time (lane = code, fully coalesced 2m-byte loads), so id order inside a unit is
+// (iteration, lane).  A workgroup is 4 wavefronts and serves a tile of QT queries whose u8 tables
+// (QT * m * 256 bytes) sit in LDS; each lane gathers its m table bytes per query from LDS.
+// Workgroups walk a list of (query tile, block of 4 units) items with a grid stride, so the same
+// launch shape serves "all queries" and "the few flagged queries" (count read on the device).
 #include "common.h"
+#include "scan_internal.h"
 
 namespace dcpq {
 
@@ -50,10 +56,13 @@ __device__ inline void load_low_bytes(const uint16_t *__restrict__ codes, uint64
     }
 }
 
+// Queries are addressed by their position p in the active list: query id = qlist ? qlist[p] : p.
+// Workspace arrays (hist, thr, tie, counter, keys) are indexed by p; qtab by the query id.
 template <int M, int QT, int MODE>
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(
-    const uint16_t *__restrict__ codes, uint64_t n_codes, uint32_t unit, uint32_t nunits,
-    const uint8_t *__restrict__ qtab, int nq, uint32_t r,
+    const uint16_t *__restrict__ codes, uint64_t n_codes, uint32_t unit, uint32_t nunits, uint64_t unit_stride,
+    const uint8_t *__restrict__ qtab, int nq_host, const int *__restrict__ qlist,
+    const uint32_t *__restrict__ nq_dev, uint32_t r,
     uint32_t *__restrict__ hist,        // [nq][256]          (kHist: accumulated)
     const uint32_t *__restrict__ thr,   // [nq][2]            (kTieCount, kCollect: read)
     uint32_t *__restrict__ tie,         // [nq][nunits]       (kTieCount: counts out; kCollect: quotas in)
@@ -65,104 +74,113 @@ __global__ __launch_bounds__(kScanThreads) void scan_kernel(
     uint32_t *lhist = reinterpret_cast<uint32_t *>(smem + QT * M * 256);    // [QT][256] (kHist)
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int q0 = blockIdx.y * QT;
-    const int nqt = min(QT, nq - q0);
+    const int nq = nq_dev ? static_cast<int>(*nq_dev) : nq_host;
+    const uint32_t nxb = (nunits + kScanWaves - 1) / kScanWaves;
+    const uint64_t nitems = static_cast<uint64_t>((nq + QT - 1) / QT) * nxb;
 
-    // Stage the tile's tables; rows of absent queries are never read.
-    {
-        const uint4 *src = reinterpret_cast<const uint4 *>(qtab + static_cast<size_t>(q0) * M * 256);
-        uint4 *dst = reinterpret_cast<uint4 *>(ltab);
-        const int nvec = nqt * M * 256 / 16;
-        for (int v = tid; v < nvec; v += kScanThreads) dst[v] = src[v];
+    for (uint64_t item = blockIdx.x; item < nitems; item += gridDim.x) {
+        const int q0 = static_cast<int>(item / nxb) * QT;
+        const uint32_t xb = static_cast<uint32_t>(item % nxb);
+        const int nqt = min(QT, nq - q0);
+
+        __syncthreads();                       // previous item's LDS is no longer in use
+        for (int q = 0; q < nqt; ++q) {        // stage the tile's tables (rows of absent queries are never read)
+            const int qid = qlist ? qlist[q0 + q] : q0 + q;
+            const uint4 *src = reinterpret_cast<const uint4 *>(qtab + static_cast<size_t>(qid) * M * 256);
+            uint4 *dst = reinterpret_cast<uint4 *>(ltab + q * M * 256);
+            for (int v = tid; v < M * 256 / 16; v += kScanThreads) dst[v] = src[v];
+        }
         if (MODE == kHist)
             for (int v = tid; v < QT * 256; v += kScanThreads) lhist[v] = 0;
-    }
-    __syncthreads();
+        __syncthreads();
 
-    const uint32_t u = blockIdx.x * kScanWaves + wave;          // this wavefront's unit
-    const uint64_t begin = static_cast<uint64_t>(u) * unit;
-    const uint64_t end = (u < nunits) ? min(n_codes, begin + unit) : begin;
+        const uint32_t u = xb * kScanWaves + wave;          // this wavefront's unit
+        const uint64_t begin = static_cast<uint64_t>(u) * unit_stride;
+        const uint64_t end = (u < nunits) ? min(n_codes, begin + unit) : begin;
 
-    uint32_t T[QT], aux[QT];   // threshold bucket; kTieCount: running count, kCollect: quota left
-#pragma unroll
-    for (int q = 0; q < QT; ++q) {
-        T[q] = 0; aux[q] = 0;
-        if (MODE != kHist && q < nqt) {
-            T[q] = thr[2 * (q0 + q)];
-            if (MODE == kCollect && u < nunits) aux[q] = tie[static_cast<size_t>(q0 + q) * nunits + u];
-        }
-    }
-
-    for (uint64_t base = begin; base < end; base += kWave) {
-        const uint64_t i = base + lane;
-        const bool live = i < end;
-        uint32_t low[M];
-        if (live) {
-            load_low_bytes<M>(codes, i, low);
-        } else {
-#pragma unroll
-            for (int j = 0; j < M; ++j) low[j] = 0;
-        }
+        uint32_t T[QT], aux[QT];   // threshold bucket; kTieCount: running count, kCollect: quota left
 #pragma unroll
         for (int q = 0; q < QT; ++q) {
-            if (q >= nqt) continue;                               // uniform
-            const uint8_t *t = ltab + q * (M * 256);
-            uint32_t s = 0;
-#pragma unroll
-            for (int j = 0; j < M; ++j) s += t[j * 256 + low[j]];
-            const uint32_t qd = min(s, 255u);                     // saturate: 255 = beyond qmax
-            if (MODE == kHist) {
-                if (live) atomicAdd(&lhist[q * 256 + qd], 1u);
-            } else if (MODE == kTieCount) {
-                aux[q] += __popcll(__ballot(live && qd == T[q]));
+            T[q] = 0; aux[q] = 0;
+            if (MODE != kHist && q < nqt) {
+                T[q] = thr[2 * (q0 + q)];
+                if (MODE == kCollect && u < nunits) aux[q] = tie[static_cast<size_t>(q0 + q) * nunits + u];
+            }
+        }
+
+        for (uint64_t base = begin; base < end; base += kWave) {
+            const uint64_t i = base + lane;
+            const bool live = i < end;
+            uint32_t low[M];
+            if (live) {
+                load_low_bytes<M>(codes, i, low);
             } else {
-                const bool below = live && qd < T[q];
-                const bool tied = live && qd == T[q];
-                const uint64_t tied_mask = __ballot(tied);
-                bool take = below;
-                if (tied_mask) {                                  // uniform
-                    const uint32_t rank = __popcll(tied_mask & ((1ull << lane) - 1ull));
-                    take = below || (tied && rank < aux[q]);
-                    const uint32_t n_tied = __popcll(tied_mask);
-                    aux[q] = aux[q] > n_tied ? aux[q] - n_tied : 0u;
-                }
-                const uint64_t take_mask = __ballot(take);
-                if (take_mask) {                                  // uniform, rare
-                    const uint32_t n_take = __popcll(take_mask);
-                    uint32_t slot0 = 0;
-                    if (lane == 0) slot0 = atomicAdd(&counter[q0 + q], n_take);
-                    slot0 = __shfl(slot0, 0, kWave);
-                    if (take) {
-                        const uint32_t slot = slot0 + __popcll(take_mask & ((1ull << lane) - 1ull));
-                        if (slot < r)   // exactly r ids are taken over the whole scan; guard anyway
-                            keys[static_cast<size_t>(q0 + q) * r + slot] = make_key(qd, static_cast<uint32_t>(i));
+#pragma unroll
+                for (int j = 0; j < M; ++j) low[j] = 0;
+            }
+#pragma unroll
+            for (int q = 0; q < QT; ++q) {
+                if (q >= nqt) continue;                               // uniform
+                const uint8_t *t = ltab + q * (M * 256);
+                uint32_t s = 0;
+#pragma unroll
+                for (int j = 0; j < M; ++j) s += t[j * 256 + low[j]];
+                const uint32_t qd = min(s, 255u);                     // saturate: 255 = beyond qmax
+                if (MODE == kHist) {
+                    if (live) atomicAdd(&lhist[q * 256 + qd], 1u);
+                } else if (MODE == kTieCount) {
+                    aux[q] += __popcll(__ballot(live && qd == T[q]));
+                } else {
+                    const bool below = live && qd < T[q];
+                    const bool tied = live && qd == T[q];
+                    const uint64_t tied_mask = __ballot(tied);
+                    bool take = below;
+                    if (tied_mask) {                                  // uniform
+                        const uint32_t rank = __popcll(tied_mask & ((1ull << lane) - 1ull));
+                        take = below || (tied && rank < aux[q]);
+                        const uint32_t n_tied = __popcll(tied_mask);
+                        aux[q] = aux[q] > n_tied ? aux[q] - n_tied : 0u;
+                    }
+                    const uint64_t take_mask = __ballot(take);
+                    if (take_mask) {                                  // uniform, rare
+                        const uint32_t n_take = __popcll(take_mask);
+                        uint32_t slot0 = 0;
+                        if (lane == 0) slot0 = atomicAdd(&counter[q0 + q], n_take);
+                        slot0 = __shfl(slot0, 0, kWave);
+                        if (take) {
+                            const uint32_t slot = slot0 + __popcll(take_mask & ((1ull << lane) - 1ull));
+                            if (slot < r)   // exactly r ids are taken over the whole scan; guard anyway
+                                keys[static_cast<size_t>(q0 + q) * r + slot] = make_key(qd, static_cast<uint32_t>(i));
+                        }
                     }
                 }
             }
         }
-    }
 
-    if (MODE == kHist) {
-        __syncthreads();
-        for (int v = tid; v < nqt * 256; v += kScanThreads) {
-            const uint32_t c = lhist[v];
-            if (c) atomicAdd(&hist[static_cast<size_t>(q0) * 256 + v], c);
-        }
-    } else if (MODE == kTieCount) {
-        if (u < nunits && lane == 0) {
+        if (MODE == kHist) {
+            __syncthreads();
+            for (int v = tid; v < nqt * 256; v += kScanThreads) {
+                const uint32_t c = lhist[v];
+                if (c) atomicAdd(&hist[static_cast<size_t>(q0) * 256 + v], c);
+            }
+        } else if (MODE == kTieCount) {
+            if (u < nunits && lane == 0) {
 #pragma unroll
-            for (int q = 0; q < QT; ++q)
-                if (q < nqt) tie[static_cast<size_t>(q0 + q) * nunits + u] = aux[q];
+                for (int q = 0; q < QT; ++q)
+                    if (q < nqt) tie[static_cast<size_t>(q0 + q) * nunits + u] = aux[q];
+            }
         }
     }
 }
 
 // T = bucket holding the r-th smallest qd; need = ids still to take from bucket T.
 __global__ __launch_bounds__(256) void threshold_kernel(const uint32_t *__restrict__ hist, uint32_t r,
+                                                        const uint32_t *__restrict__ nq_dev,
                                                         uint32_t *__restrict__ thr)
 {
     __shared__ uint32_t cum[256];
     const int q = blockIdx.x, b = threadIdx.x;
+    if (nq_dev && q >= static_cast<int>(*nq_dev)) return;
     cum[b] = hist[static_cast<size_t>(q) * 256 + b];
     __syncthreads();
     for (int off = 1; off < 256; off <<= 1) {            // inclusive scan (Hillis-Steele)
@@ -178,11 +196,13 @@ __global__ __launch_bounds__(256) void threshold_kernel(const uint32_t *__restri
 // Turns per-unit counts of bucket T into per-unit quotas: units are in id order, so unit u may
 // take min(count_u, need - sum of counts before u) ids (its smallest ones).
 __global__ __launch_bounds__(256) void tie_quota_kernel(uint32_t *__restrict__ tie, uint32_t nunits,
+                                                        const uint32_t *__restrict__ nq_dev,
                                                         const uint32_t *__restrict__ thr)
 {
     __shared__ uint32_t part[256];
     __shared__ uint32_t carry;
     const int q = blockIdx.x, t = threadIdx.x;
+    if (nq_dev && q >= static_cast<int>(*nq_dev)) return;
     uint32_t *row = tie + static_cast<size_t>(q) * nunits;
     const uint32_t need = thr[2 * q + 1];
     if (t == 0) carry = 0;
@@ -206,55 +226,50 @@ __global__ __launch_bounds__(256) void tie_quota_kernel(uint32_t *__restrict__ t
     }
 }
 
-// In-place bitonic sort of n_pow2 64-bit keys by one workgroup (array in LDS or global memory).
-__device__ inline void bitonic_sort(uint64_t *a, uint32_t n_pow2)
-{
-    for (uint32_t size = 2; size <= n_pow2; size <<= 1) {
-        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (uint32_t t = threadIdx.x; t < (n_pow2 >> 1); t += blockDim.x) {
-                const uint32_t lo = 2 * t - (t & (stride - 1));
-                const uint32_t hi = lo + stride;
-                const bool up = (lo & size) == 0;
-                const uint64_t x = a[lo], y = a[hi];
-                if ((x > y) == up) { a[lo] = y; a[hi] = x; }
-            }
-        }
-    }
-    __syncthreads();
-}
-
-// Sort the r collected keys of each query by (qd, id) and split them into the two outputs.
+// Sort the r collected keys of each active query by (qd, id) and split them into the two outputs.
 // use_lds: the padded array fits the dynamic LDS allocation; otherwise it is sorted in `spill`.
 __global__ __launch_bounds__(1024) void sort_candidates_kernel(const uint64_t *__restrict__ keys, uint32_t r,
                                                               uint32_t n_pow2, int use_lds,
                                                               uint64_t *__restrict__ spill,
+                                                              const int *__restrict__ qlist,
+                                                              const uint32_t *__restrict__ nq_dev,
                                                               uint32_t *__restrict__ cand_id,
                                                               uint8_t *__restrict__ cand_qd)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    const int q = blockIdx.x;
-    uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(q) * n_pow2;
+    const int p = blockIdx.x;
+    if (nq_dev && p >= static_cast<int>(*nq_dev)) return;
+    const int qid = qlist ? qlist[p] : p;
+    uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(p) * n_pow2;
     for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x)
-        a[t] = t < r ? keys[static_cast<size_t>(q) * r + t] : ~0ull;
+        a[t] = t < r ? keys[static_cast<size_t>(p) * r + t] : ~0ull;
     bitonic_sort(a, n_pow2);
     for (uint32_t t = threadIdx.x; t < r; t += blockDim.x) {
         const uint64_t key = a[t];
-        cand_id[static_cast<size_t>(q) * r + t] = static_cast<uint32_t>(key);
-        cand_qd[static_cast<size_t>(q) * r + t] = static_cast<uint8_t>(key >> 32);
+        cand_id[static_cast<size_t>(qid) * r + t] = static_cast<uint32_t>(key);
+        cand_qd[static_cast<size_t>(qid) * r + t] = static_cast<uint8_t>(key >> 32);
     }
 }
 
-static uint32_t next_pow2(uint32_t x)
+// Clears `n` 32-bit words (a fill kernel rather than a memset node, so that the call sequence
+// stays safe to capture into a HIP graph).
+__global__ void zero_words_kernel(uint32_t *p, size_t n)
 {
-    uint32_t p = 1;
-    while (p < x) p <<= 1;
-    return p;
+    const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
 }
 
-constexpr uint32_t kSortLdsKeys = 8192;   // 64 KiB of keys
-
 constexpr int scan_qt(int m) { return m <= 8 ? 16 : 128 / m; }   // tables of a tile: <= 32 KiB of LDS
+
+int fast_query_tile(int m)
+{
+    switch (m) {
+        case 4: case 8: return 64;
+        case 16: return 32;
+        case 32: return 16;
+        default: return 0;
+    }
+}
 
 ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r)
 {
@@ -267,33 +282,82 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r)
     p.unit = static_cast<uint32_t>(unit);
     p.nunits = static_cast<uint32_t>((n_codes + unit - 1) / unit);
     const uint32_t np2 = next_pow2(r);
+    const size_t Q = static_cast<size_t>(nq);
     size_t off = 0;
-    p.off_hist = off;    off = align_up(off + sizeof(uint32_t) * 256 * static_cast<size_t>(nq), 256);
-    p.off_thr = off;     off = align_up(off + sizeof(uint32_t) * 2 * static_cast<size_t>(nq), 256);
-    p.off_counter = off; off = align_up(off + sizeof(uint32_t) * static_cast<size_t>(nq), 256);
-    p.off_tie = off;     off = align_up(off + sizeof(uint32_t) * static_cast<size_t>(nq) * p.nunits, 256);
-    p.off_keys = off;    off = align_up(off + sizeof(uint64_t) * static_cast<size_t>(nq) * r, 256);
+    p.off_hist = off;    off = align_up(off + sizeof(uint32_t) * 256 * Q, 256);
+    p.off_thr = off;     off = align_up(off + sizeof(uint32_t) * 2 * Q, 256);
+    p.off_counter = off; off = align_up(off + sizeof(uint32_t) * Q, 256);
+    p.zero_bytes = off;
+    p.off_tie = off;     off = align_up(off + sizeof(uint32_t) * Q * p.nunits, 256);
+    p.off_keys = off;    off = align_up(off + sizeof(uint64_t) * Q * r, 256);
     p.off_spill = off;   // sort area in global memory, only when r keys do not fit the LDS sort
-    if (np2 > kSortLdsKeys) off = align_up(off + sizeof(uint64_t) * static_cast<size_t>(nq) * np2, 256);
+    if (np2 > kSortLdsKeys) off = align_up(off + sizeof(uint64_t) * Q * np2, 256);
+
+    p.fqt = static_cast<uint32_t>(fast_query_tile(m));
+    p.fast = p.fqt != 0;
+    if (p.fast) {
+        p.ntiles = static_cast<uint32_t>((Q + p.fqt - 1) / p.fqt);
+        // workgroups along the codes: about 8 rounds of the 256 CUs in total, at least 16 Ki codes each
+        const uint64_t want = (2048 + p.ntiles - 1) / p.ntiles;
+        const uint64_t most = (n_codes + 16383) / 16384;
+        uint64_t fb = want < most ? want : most;
+        if (fb < 1) fb = 1;
+        uint64_t cpb = (n_codes + fb - 1) / fb;
+        cpb = (cpb + 1023) / 1024 * 1024;
+        p.codes_per_block = static_cast<uint32_t>(cpb);
+        p.fblocks = static_cast<uint32_t>((n_codes + cpb - 1) / cpb);
+        p.cap = 16 * r < 2048 ? 2048 : 16 * r;
+        p.upd = r / 8 < 64 ? 64 : r / 8;
+        const uint32_t want_sort = next_pow2(2 * r);
+        p.sortcap = want_sort < kSortLdsKeys ? kSortLdsKeys : want_sort;
+        // sample: runs of 256 codes spread evenly over the array, about 32 r codes (at least 64 Ki)
+        uint64_t s_codes = 32ull * r < 65536 ? 65536 : 32ull * r;
+        if (s_codes > n_codes) s_codes = n_codes;
+        p.s_unit = 256;
+        p.s_nunits = static_cast<uint32_t>((s_codes + 255) / 256);
+        p.s_stride = n_codes / p.s_nunits;
+        if (p.s_stride < p.s_unit) p.s_stride = p.s_unit;
+        p.off_fzero = off;
+        p.off_fcount = off;  off = align_up(off + sizeof(uint32_t) * Q, 256);
+        p.off_chist = off;   off = align_up(off + sizeof(uint32_t) * 256 * Q, 256);
+        p.off_shist = off;   off = align_up(off + sizeof(uint32_t) * 256 * Q, 256);
+        p.off_nflag = off;   off = align_up(off + 256, 256);
+        p.fzero_bytes = off - p.off_fzero;
+        p.off_tcur = off;    off = align_up(off + sizeof(int32_t) * Q, 256);
+        p.off_flags = off;   off = align_up(off + sizeof(uint32_t) * Q, 256);
+        p.off_qlist = off;   off = align_up(off + sizeof(int32_t) * Q, 256);
+        p.off_qsw = off;     off = align_up(off + static_cast<size_t>(p.ntiles) * m * 256 * p.fqt, 256);
+        p.off_fkeys = off;   off = align_up(off + sizeof(uint64_t) * Q * p.cap, 256);
+        p.off_fsort = off;
+        if (p.sortcap > kSortLdsKeys) off = align_up(off + sizeof(uint64_t) * Q * p.sortcap, 256);
+    }
     p.total = off;
     return p;
 }
 
-// Clears `n` 32-bit words (a fill kernel rather than a memset node, so that the call sequence
-// stays safe to capture into a HIP graph).
-__global__ void zero_words_kernel(uint32_t *p, size_t n)
-{
-    const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0u;
-}
-
-template <int M>
-static int launch_scan_m(const uint16_t *codes, uint64_t n_codes, const uint8_t *qtab, int nq, uint32_t r,
-                         uint32_t *cand_id, uint8_t *cand_qd, void *ws, hipStream_t st)
+template <int M, int MODE>
+static void launch_scan_pass(int stage, const uint16_t *codes, uint64_t n_codes, uint32_t unit, uint32_t nunits,
+                             uint64_t stride, const uint8_t *qtab, int nq, const int *qlist, const uint32_t *nq_dev,
+                             uint32_t r, uint32_t *hist, const uint32_t *thr, uint32_t *tie, uint32_t *counter,
+                             uint64_t *keys, bool few_expected, hipStream_t st)
 {
     constexpr int QT = scan_qt(M);
-    const ScanPlan p = plan_scan(n_codes, M, nq, r);
-    uint8_t *base = static_cast<uint8_t *>(ws);
+    const uint64_t nxb = (nunits + kScanWaves - 1) / kScanWaves;
+    const uint64_t items = static_cast<uint64_t>((nq + QT - 1) / QT) * nxb;
+    // Redo launches expect few (usually zero) active queries: keep the grid small, it strides.
+    const uint64_t most = few_expected ? 4096 : (1u << 20);
+    const uint32_t grid = static_cast<uint32_t>(items < most ? (items ? items : 1) : most);
+    const size_t lds = static_cast<size_t>(QT) * M * 256 + (MODE == kHist ? QT * 256 * 4 : 0);
+    DCPQ_LAUNCH(stage, st, (scan_kernel<M, QT, MODE>), dim3(grid), dim3(kScanThreads), lds, codes, n_codes, unit,
+                nunits, stride, qtab, nq, qlist, nq_dev, r, hist, thr, tie, counter, keys);
+}
+
+// The three passes for the queries qlist[0 .. *nq_dev) (or all nq when qlist is null).
+template <int M>
+static int launch_three_pass(const uint16_t *codes, uint64_t n_codes, const uint8_t *qtab, int nq, const int *qlist,
+                             const uint32_t *nq_dev, uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, uint8_t *base,
+                             const ScanPlan &p, hipStream_t st)
+{
     uint32_t *hist = reinterpret_cast<uint32_t *>(base + p.off_hist);
     uint32_t *thr = reinterpret_cast<uint32_t *>(base + p.off_thr);
     uint32_t *counter = reinterpret_cast<uint32_t *>(base + p.off_counter);
@@ -301,46 +365,86 @@ static int launch_scan_m(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     const bool spill = next_pow2(r) > kSortLdsKeys;
     uint64_t *keys = reinterpret_cast<uint64_t *>(base + p.off_keys);
     uint64_t *sorted = reinterpret_cast<uint64_t *>(base + p.off_spill);
+    const bool few = qlist != nullptr;
 
-    // hist, thr and counter are contiguous at the head of the workspace: one clear.
-    const size_t nwords = p.off_tie / sizeof(uint32_t);
+    const size_t nwords = p.zero_bytes / sizeof(uint32_t);
     DCPQ_LAUNCH(kStageMisc, st, zero_words_kernel, dim3((nwords + 255) / 256), dim3(256), 0,
                 reinterpret_cast<uint32_t *>(base), nwords);
     DCPQ_CHECK_LAUNCH("zero_words_kernel");
-
-    const dim3 grid((p.nunits + kScanWaves - 1) / kScanWaves, (nq + QT - 1) / QT);
-    const size_t lds_tab = static_cast<size_t>(QT) * M * 256;
-    DCPQ_LAUNCH(kStageScanHist, st, (scan_kernel<M, QT, kHist>), grid, dim3(kScanThreads), lds_tab + QT * 256 * 4,
-                codes, n_codes, p.unit, p.nunits, qtab, nq, r, hist, thr, tie, counter, keys);
+    launch_scan_pass<M, kHist>(kStageScanHist, codes, n_codes, p.unit, p.nunits, p.unit, qtab, nq, qlist, nq_dev, r,
+                               hist, thr, tie, counter, keys, few, st);
     DCPQ_CHECK_LAUNCH("scan_kernel<hist>");
-    DCPQ_LAUNCH(kStageSelect, st, threshold_kernel, dim3(nq), dim3(256), 0, hist, r, thr);
+    DCPQ_LAUNCH(kStageSelect, st, threshold_kernel, dim3(nq), dim3(256), 0, hist, r, nq_dev, thr);
     DCPQ_CHECK_LAUNCH("threshold_kernel");
-    DCPQ_LAUNCH(kStageScanTieCount, st, (scan_kernel<M, QT, kTieCount>), grid, dim3(kScanThreads), lds_tab, codes,
-                n_codes, p.unit, p.nunits, qtab, nq, r, hist, thr, tie, counter, keys);
+    launch_scan_pass<M, kTieCount>(kStageScanTieCount, codes, n_codes, p.unit, p.nunits, p.unit, qtab, nq, qlist,
+                                   nq_dev, r, hist, thr, tie, counter, keys, few, st);
     DCPQ_CHECK_LAUNCH("scan_kernel<tiecount>");
-    DCPQ_LAUNCH(kStageSelect, st, tie_quota_kernel, dim3(nq), dim3(256), 0, tie, p.nunits, thr);
+    DCPQ_LAUNCH(kStageSelect, st, tie_quota_kernel, dim3(nq), dim3(256), 0, tie, p.nunits, nq_dev, thr);
     DCPQ_CHECK_LAUNCH("tie_quota_kernel");
-    DCPQ_LAUNCH(kStageScanCollect, st, (scan_kernel<M, QT, kCollect>), grid, dim3(kScanThreads), lds_tab, codes,
-                n_codes, p.unit, p.nunits, qtab, nq, r, hist, thr, tie, counter, keys);
+    launch_scan_pass<M, kCollect>(kStageScanCollect, codes, n_codes, p.unit, p.nunits, p.unit, qtab, nq, qlist,
+                                  nq_dev, r, hist, thr, tie, counter, keys, few, st);
     DCPQ_CHECK_LAUNCH("scan_kernel<collect>");
     const uint32_t np2 = next_pow2(r);
     DCPQ_LAUNCH(kStageSelect, st, sort_candidates_kernel, dim3(nq), dim3(1024), spill ? 0 : sizeof(uint64_t) * np2,
-                keys, r, np2, spill ? 0 : 1, sorted, cand_id, cand_qd);
+                keys, r, np2, spill ? 0 : 1, sorted, qlist, nq_dev, cand_id, cand_qd);
     DCPQ_CHECK_LAUNCH("sort_candidates_kernel");
     return DCPQ_OK;
 }
 
+template <int M>
+static int launch_sample_hist_m(const uint16_t *codes, uint64_t n_codes, const uint8_t *qtab, int nq, uint32_t r,
+                                uint32_t *shist, const ScanPlan &p, hipStream_t st)
+{
+    launch_scan_pass<M, kHist>(kStageScanHist, codes, n_codes, p.s_unit, p.s_nunits, p.s_stride, qtab, nq, nullptr,
+                               nullptr, r, shist, nullptr, nullptr, nullptr, nullptr, false, st);
+    DCPQ_CHECK_LAUNCH("scan_kernel<sample hist>");
+    return DCPQ_OK;
+}
+
+int launch_sample_hist(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
+                       uint32_t *shist, const ScanPlan &p, hipStream_t st)
+{
+    switch (m) {
+        case 4: return launch_sample_hist_m<4>(codes, n_codes, qtab, nq, r, shist, p, st);
+        case 8: return launch_sample_hist_m<8>(codes, n_codes, qtab, nq, r, shist, p, st);
+        case 16: return launch_sample_hist_m<16>(codes, n_codes, qtab, nq, r, shist, p, st);
+        case 32: return launch_sample_hist_m<32>(codes, n_codes, qtab, nq, r, shist, p, st);
+        default: return fail(DCPQ_EUNSUPPORTED, "sample histogram: m=%d not supported", m);
+    }
+}
+
+template <int M>
+static int launch_scan_m(const uint16_t *codes, uint64_t n_codes, const uint8_t *qtab, int nq, uint32_t r,
+                         uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st)
+{
+    const ScanPlan p = plan_scan(n_codes, M, nq, r);
+    uint8_t *base = static_cast<uint8_t *>(ws);
+    if (!p.fast || mode == DCPQ_SCAN_THREE_PASS)
+        return launch_three_pass<M>(codes, n_codes, qtab, nq, nullptr, nullptr, r, cand_id, cand_qd, base, p, st);
+
+    const size_t nwords = p.fzero_bytes / sizeof(uint32_t);
+    DCPQ_LAUNCH(kStageMisc, st, zero_words_kernel, dim3((nwords + 255) / 256), dim3(256), 0,
+                reinterpret_cast<uint32_t *>(base + p.off_fzero), nwords);
+    DCPQ_CHECK_LAUNCH("zero_words_kernel");
+    int rc = launch_scan_fast(codes, n_codes, M, qtab, nq, r, cand_id, cand_qd, base, p, st);
+    if (rc) return rc;
+    // queries the single pass could not finish (their count is known on the device only)
+    return launch_three_pass<M>(codes, n_codes, qtab, nq, reinterpret_cast<const int *>(base + p.off_qlist),
+                                reinterpret_cast<const uint32_t *>(base + p.off_nflag), r, cand_id, cand_qd, base,
+                                p, st);
+}
+
 int launch_scan(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
-                uint32_t *cand_id, uint8_t *cand_qd, void *ws, hipStream_t st)
+                uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st)
 {
     if (nq == 0) return DCPQ_OK;
     switch (m) {
-        case 1: return launch_scan_m<1>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, st);
-        case 2: return launch_scan_m<2>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, st);
-        case 4: return launch_scan_m<4>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, st);
-        case 8: return launch_scan_m<8>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, st);
-        case 16: return launch_scan_m<16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, st);
-        case 32: return launch_scan_m<32>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, st);
+        case 1: return launch_scan_m<1>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        case 2: return launch_scan_m<2>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        case 4: return launch_scan_m<4>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        case 8: return launch_scan_m<8>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        case 16: return launch_scan_m<16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        case 32: return launch_scan_m<32>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
         default: return fail(DCPQ_EUNSUPPORTED, "m=%d not supported", m);
     }
 }
@@ -349,7 +453,12 @@ int launch_scan(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *q
 
 using namespace dcpq;
 
-extern "C" int dcpq_scan_query_tile(int m) { return m_supported(m) ? scan_qt(m) : 0; }
+extern "C" int dcpq_scan_query_tile(int m)
+{
+    if (!m_supported(m)) return 0;
+    const int f = fast_query_tile(m);
+    return f ? f : scan_qt(m);
+}
 
 extern "C" size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r)
 {
@@ -357,16 +466,18 @@ extern "C" size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uin
     return plan_scan(n_codes, m, nq, r).total;
 }
 
-extern "C" int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
-                                    uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
-                                    size_t workspace_bytes, void *stream)
+static int scan_checked(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
+                        uint32_t *cand_id, uint8_t *cand_qd, void *workspace, size_t workspace_bytes, int mode,
+                        void *stream)
 {
     clear_error();
     DCPQ_REQUIRE(nq >= 0, "scan_candidates: nq=%d", nq);
+    DCPQ_REQUIRE(mode == DCPQ_SCAN_AUTO || mode == DCPQ_SCAN_THREE_PASS, "scan_candidates: mode=%d", mode);
     if (!m_supported(m)) return fail(DCPQ_EUNSUPPORTED, "scan_candidates: m=%d not supported", m);
     DCPQ_REQUIRE(n_codes >= 1 && n_codes < (1ull << 32), "scan_candidates: n_codes=%llu must be in [1, 2^32)",
                  static_cast<unsigned long long>(n_codes));
     DCPQ_REQUIRE(r >= 1 && r <= n_codes, "scan_candidates: r=%u must be in [1, n_codes]", r);
+    DCPQ_REQUIRE(r <= (1u << 26), "scan_candidates: r=%u above the supported 2^26", r);
     if (nq == 0) return DCPQ_OK;
     DCPQ_REQUIRE(codes && qtab && cand_id && cand_qd && workspace, "scan_candidates: null pointer");
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "scan_candidates: workspace must be 256-byte aligned");
@@ -375,5 +486,20 @@ extern "C" int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int
     const size_t need = dcpq_scan_workspace_bytes(n_codes, m, nq, r);
     if (workspace_bytes < need)
         return fail(DCPQ_EWORKSPACE, "scan_candidates: workspace %zu < %zu bytes", workspace_bytes, need);
-    return launch_scan(codes, n_codes, m, qtab, nq, r, cand_id, cand_qd, workspace, as_stream(stream));
+    return launch_scan(codes, n_codes, m, qtab, nq, r, cand_id, cand_qd, workspace, mode, as_stream(stream));
+}
+
+extern "C" int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                                    uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
+                                    size_t workspace_bytes, void *stream)
+{
+    return scan_checked(codes, n_codes, m, qtab, nq, r, cand_id, cand_qd, workspace, workspace_bytes,
+                        DCPQ_SCAN_AUTO, stream);
+}
+
+extern "C" int dcpq_scan_candidates_mode(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab,
+                                         int nq, uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
+                                         size_t workspace_bytes, int mode, void *stream)
+{
+    return scan_checked(codes, n_codes, m, qtab, nq, r, cand_id, cand_qd, workspace, workspace_bytes, mode, stream);
 }

@@ -1,0 +1,84 @@
+// Shared between the two translation units of the scan stage (not part of the ABI).
+#pragma once
+
+#include "common.h"
+
+namespace dcpq {
+
+constexpr uint32_t kSortLdsKeys = 8192;   // keys a workgroup sorts in LDS (64 KiB)
+
+inline uint32_t next_pow2(uint32_t x)
+{
+    uint32_t p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// Sizes and workspace layout of one scan_candidates call (offsets in bytes from a 256-byte
+// aligned base).  The three-pass path can always run; the single-pass path exists for m >= 4.
+struct ScanPlan {
+    // three-pass path
+    uint32_t unit;        // codes scanned by one wavefront
+    uint32_t nunits;      // ceil(n_codes / unit)
+    uint32_t qt;          // queries per workgroup tile
+    size_t off_hist;      // uint32 [nq][256]
+    size_t off_thr;       // uint32 [nq][2]   (threshold bucket, ids still needed from it)
+    size_t off_counter;   // uint32 [nq]
+    size_t zero_bytes;    // the three arrays above are contiguous from offset 0 and cleared together
+    size_t off_tie;       // uint32 [nq][nunits]
+    size_t off_keys;      // uint64 [nq][r]
+    size_t off_spill;     // uint64 [nq][next_pow2(r)], only when r keys do not fit the LDS sort
+    // single-pass path
+    bool fast;
+    uint32_t fqt;             // queries per tile
+    uint32_t ntiles;
+    uint32_t fblocks;         // workgroups along the code axis
+    uint32_t codes_per_block;
+    uint32_t cap;             // candidate-buffer entries per query
+    uint32_t upd;             // appended candidates between two bound updates
+    uint32_t sortcap;         // keys the final selection can sort (power of two)
+    uint32_t s_unit, s_nunits;    // sample: s_nunits runs of s_unit codes ...
+    uint64_t s_stride;            // ... starting every s_stride codes
+    size_t off_fzero, fzero_bytes;   // fcount, chist, shist, nflag: cleared together
+    size_t off_fcount;    // uint32 [nq]
+    size_t off_chist;     // uint32 [nq][256]
+    size_t off_shist;     // uint32 [nq][256]
+    size_t off_nflag;     // uint32 [1] (+ padding)
+    size_t off_tcur;      // int32 [nq]
+    size_t off_flags;     // uint32 [nq]
+    size_t off_qlist;     // int32 [nq]
+    size_t off_qsw;       // uint8 [ntiles][m*256*fqt]
+    size_t off_fkeys;     // uint64 [nq][cap]
+    size_t off_fsort;     // uint64 [nq][sortcap], only when sortcap exceeds the LDS sort
+    size_t total;
+};
+ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r);
+
+int fast_query_tile(int m);   // 0 when the single-pass path does not exist for this m
+int launch_sample_hist(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                       uint32_t r, uint32_t *shist, const ScanPlan &p, hipStream_t st);
+int launch_scan_fast(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                     uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, uint8_t *base, const ScanPlan &p,
+                     hipStream_t st);
+
+#ifdef __HIPCC__
+// In-place bitonic sort of n_pow2 64-bit keys by one workgroup (array in LDS or global memory).
+__device__ inline void bitonic_sort(uint64_t *a, uint32_t n_pow2)
+{
+    for (uint32_t size = 2; size <= n_pow2; size <<= 1) {
+        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
+            __syncthreads();
+            for (uint32_t t = threadIdx.x; t < (n_pow2 >> 1); t += blockDim.x) {
+                const uint32_t lo = 2 * t - (t & (stride - 1));
+                const uint32_t hi = lo + stride;
+                const bool up = (lo & size) == 0;
+                const uint64_t x = a[lo], y = a[hi];
+                if ((x > y) == up) { a[lo] = y; a[hi] = x; }
+            }
+        }
+    }
+    __syncthreads();
+}
+#endif
+
+}  // namespace dcpq

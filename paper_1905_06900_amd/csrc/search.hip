@@ -78,11 +78,11 @@ extern "C" int dcpq_search(const float *queries, int nq, const float *codebooks,
         const float *y = queries + static_cast<size_t>(q0) * D;
         int rc = launch_small_tables(y, nc, derived, m, dsub, codes, n_codes, r, qtab, bounds, nullptr, st);
         if (rc) return rc;
-        rc = launch_scan(codes, n_codes, m, qtab, nc, r, cand_id, cand_qd, base + p.off_scan, st);
+        rc = launch_scan(codes, n_codes, m, qtab, nc, r, cand_id, cand_qd, base + p.off_scan, DCPQ_SCAN_AUTO, st);
         if (rc) return rc;
         rc = launch_full_tables(y, nc, codebooks, m, dsub, tables, st);
         if (rc) return rc;
-        rc = launch_refine(tables, codes, m, cand_id, nc, r, k, ids + static_cast<size_t>(q0) * k,
+        rc = launch_refine(tables, codes, n_codes, m, cand_id, nc, r, k, ids + static_cast<size_t>(q0) * k,
                            dist + static_cast<size_t>(q0) * k, base + p.off_refine, st);
         if (rc) return rc;
     }

@@ -83,16 +83,20 @@ def test_sift_recipe_scaled_with_encoded_codes():
 # edge cases of the scan / select
 # ------------------------------------------------------------------------------------------------
 def scan_vs_oracle(codes_np, qtab_np, r):
+    """Both scan algorithms (single pass with redo, and three-pass) against the oracle."""
     codes = torch.from_numpy(codes_np.view(np.int16)).to(DEV).view(torch.uint16)
     qtab = torch.from_numpy(qtab_np).to(DEV)
-    cid, cqd = binding.scan_candidates(codes, qtab, r)
-    torch.cuda.synchronize()
-    cid, cqd = to_np(cid), to_np(cqd)
+    want = []
     for q in range(qtab_np.shape[0]):
         qd = oracle.adc_low_bits(codes_np, qtab_np[q])
-        wid, wqd = oracle.select(qd, r)
-        np.testing.assert_array_equal(cid[q], wid, err_msg="query %d ids" % q)
-        np.testing.assert_array_equal(cqd[q], wqd, err_msg="query %d qd" % q)
+        want.append(oracle.select(qd, r))
+    for mode in (binding.SCAN_AUTO, binding.SCAN_THREE_PASS):
+        cid, cqd = binding.scan_candidates(codes, qtab, r, mode=mode)
+        torch.cuda.synchronize()
+        cid, cqd = to_np(cid), to_np(cqd)
+        for q, (wid, wqd) in enumerate(want):
+            np.testing.assert_array_equal(cid[q], wid, err_msg="mode %d query %d ids" % (mode, q))
+            np.testing.assert_array_equal(cqd[q], wqd, err_msg="mode %d query %d qd" % (mode, q))
 
 
 @pytest.mark.parametrize("m", [1, 2, 4, 8, 16, 32])
@@ -181,9 +185,25 @@ def test_argument_errors_are_reported_not_launched():
     assert e.value.code == binding.EINVAL
 
 
-def test_determinism_two_runs_identical(case0):
+def test_determinism_and_both_algorithms_identical(case0):
     c = case0
     a_id, a_qd = binding.scan_candidates(c.codes, c.qtab, c.w.r)
     b_id, b_qd = binding.scan_candidates(c.codes, c.qtab, c.w.r)
+    t_id, t_qd = binding.scan_candidates(c.codes, c.qtab, c.w.r, mode=binding.SCAN_THREE_PASS)
     torch.cuda.synchronize()
     assert torch.equal(a_id.view(torch.int32), b_id.view(torch.int32)) and torch.equal(a_qd, b_qd)
+    assert torch.equal(a_id.view(torch.int32), t_id.view(torch.int32)) and torch.equal(a_qd, t_qd)
+
+
+def test_scan_many_queries_ragged_tiles_and_a_few_pathological_ones():
+    """Several query tiles with a ragged last tile; a handful of queries have degenerate tables whose
+    candidate buffers overflow in the single pass, so they take the redo path while the rest do not."""
+    rng = np.random.default_rng(321)
+    N, Q, r = 300_007, 150, 1200
+    codes = rng.integers(0, 65536, size=(N, 8)).astype(np.uint16)
+    qtab = rng.integers(0, 48, size=(Q, 8, 256)).astype(np.uint8)
+    qtab[3] = 0
+    qtab[64] = 255
+    qtab[149] = (rng.integers(0, 2, size=(8, 256)) * 40).astype(np.uint8)
+    print("scan many queries N=%d Q=%d" % (N, Q), flush=True)
+    scan_vs_oracle(codes, qtab, r)
