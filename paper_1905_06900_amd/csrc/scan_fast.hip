@@ -46,6 +46,8 @@ struct FastCfg {
     static constexpr int NSLOT = 256 / QT;          // table rows per 256-byte LDS line
     static constexpr int NMF = M / 4;               // chained MFMAs per step
     static constexpr int STEPS = 64 / CPS;          // steps per 64-code group
+    static constexpr int UNROLL = NMF >= 8 ? 1 : 8 / NMF;   // steps issued together (8 row reads in flight)
+    static constexpr int PREFETCH = M <= 8 ? 4 : M == 16 ? 2 : 1;   // 64-code groups fetched ahead per wavefront
     static constexpr int CLS = M / 4;               // bytes per residue class j mod 4 in the code scratch
     static constexpr int TAB_BYTES = M * 256 * QT;
     static constexpr int SCR_BYTES = WAVES * 64 * M;
@@ -53,6 +55,7 @@ struct FastCfg {
     static constexpr int Q_BYTES = WAVES * QCAP * 8;
     static constexpr int LDS_BYTES = TAB_BYTES + SCR_BYTES + Q_BYTES + WAVES * 4;
     static_assert(NSLOT <= M && M % 4 == 0, "row slots must rotate within the sub-quantizers");
+    static_assert(STEPS % UNROLL == 0, "unroll must divide the steps of a group");
 };
 
 // Sub-quantizer read by MFMA u, chunk s (= lane / 16), for code slot c: rotate within aligned
@@ -238,7 +241,6 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     };
 
     // ---- main loop: one 64-code group per iteration ---------------------------------------
-    uint32_t w[M / 2];
     auto load_group = [&](uint32_t g, uint32_t (&dst)[M / 2]) {
         const uint64_t id = cbeg + static_cast<uint64_t>(g) * 64 + lane;
         if (g < ngroups && id < cend) {
@@ -258,9 +260,17 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
             for (int v = 0; v < M / 2; ++v) dst[v] = 0;
         }
     };
-    load_group(wave, w);
-    // bucket bounds of this lane's four (code, query) outputs, re-read once per group and one
-    // group ahead of their use; absent queries never match
+    // Groups are fetched PF at a time and one batch ahead of their use, so that each wavefront
+    // keeps PF kilobytes of the code stream in flight (HBM latency x bandwidth needs that much).
+    constexpr int PF = C::PREFETCH;
+    uint32_t wb[PF][M / 2];
+    auto load_batch = [&](uint32_t g0) {
+#pragma unroll
+        for (int pf = 0; pf < PF; ++pf) load_group(g0 + pf * WAVES, wb[pf]);
+    };
+    load_batch(wave);
+    // bucket bounds of this lane's four (code, query) outputs, re-read once per batch and one
+    // batch ahead of their use; absent queries never match
     auto load_bounds = [&](int (&dst)[4]) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
@@ -272,17 +282,34 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     int tl_next[4];
     load_bounds(tl_next);
 
-    for (uint32_t g = wave; g < ngroups; g += WAVES) {
-        const uint64_t gbase = cbeg + static_cast<uint64_t>(g) * 64;
-        uint32_t tb[M / 4];
-        transposed_low_bytes<M>(w, tb);
-        load_group(g + WAVES, w);                                    // prefetch the next group
+    for (uint32_t g0 = wave; g0 < ngroups; g0 += PF * WAVES) {
+        uint32_t tbp[PF][M / 4];
+#pragma unroll
+        for (int pf = 0; pf < PF; ++pf) transposed_low_bytes<M>(wb[pf], tbp[pf]);
+        load_batch(g0 + PF * WAVES);                                 // prefetch the next batch
         int tl[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) tl[v] = tl_next[v];
         load_bounds(tl_next);
+        v4i acc0;
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+            acc0[v] = static_cast<int>(128u * M - static_cast<uint32_t>(tl[v]) - 1u);
+#pragma unroll 1
+      for (int pf = 0; pf < PF; ++pf) {
+        const uint32_t g = g0 + pf * WAVES;
+        if (g >= ngroups) break;                                     // uniform
+        const uint64_t gbase = cbeg + static_cast<uint64_t>(g) * 64;
+        const int nlive = static_cast<int>(min(static_cast<uint64_t>(64), cend - gbase));   // codes in this group
         // publish the low bytes of the group's codes to the wavefront's scratch
         {
+            uint32_t tb[M / 4];
+#pragma unroll
+            for (int d = 0; d < M / 4; ++d) {
+                tb[d] = tbp[0][d];
+#pragma unroll
+                for (int z = 1; z < PF; ++z) tb[d] = pf == z ? tbp[z][d] : tb[d];
+            }
             uint32_t *dst = reinterpret_cast<uint32_t *>(scr + lane * M);
 #pragma unroll
             for (int d = 0; d < M / 4; ++d) dst[d] = tb[d];
@@ -299,38 +326,75 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
             else if constexpr (C::CLS == 4) return *reinterpret_cast<const uint32_t *>(sp);
             else return *reinterpret_cast<const uint64_t *>(sp);
         };
-        uint64_t word_next = read_word(0);
+        // U steps are issued together: all their row reads first, then U independent MFMA chains,
+        // so that several kilobytes of LDS reads per wavefront are in flight at any time.
+        constexpr int U = C::UNROLL;
 #pragma unroll 1
-        for (int t = 0; t < C::STEPS; ++t) {
-            const uint64_t word = word_next;
-            word_next = read_word((t + 1) & (C::STEPS - 1));
-            v4i acc = {128 * M, 128 * M, 128 * M, 128 * M};   // undoes the -128 bias of the M signed bytes
+        for (int t0 = 0; t0 < C::STEPS; t0 += U) {
+            uint64_t word[U];
 #pragma unroll
-            for (int u = 0; u < C::NMF; ++u) {
-                const uint32_t e = static_cast<uint32_t>(word >> shift[u]) & 255u;
-                const v4i a = *reinterpret_cast<const v4i *>(ltab + laneoff[u] + e * 256u);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bsel, acc, 0, 0, 0);
-            }
-            const bool h0 = acc[0] <= tl[0], h1 = acc[1] <= tl[1], h2 = acc[2] <= tl[2], h3 = acc[3] <= tl[3];
-            if (__ballot(h0 | h1 | h2 | h3)) {                       // uniform, rare
+            for (int u = 0; u < U; ++u) word[u] = read_word(t0 + u);
+            v4i a[U][C::NMF];
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const bool h = v == 0 ? h0 : v == 1 ? h1 : v == 2 ? h2 : h3;
-                    const uint64_t id = gbase + t * C::CPS + cd[v];
-                    if (h && id < cend) {
-                        const uint32_t qd = min(static_cast<uint32_t>(acc[v]), 255u);
-                        const uint64_t rec = (static_cast<uint64_t>(ql[v]) << 40) | (static_cast<uint64_t>(qd) << 32) | id;
-                        const uint32_t pos = atomicAdd(wqn, 1u);
-                        if (pos < C::QCAP) wq[pos] = rec;
-                        else insert(rec);                            // queue full: go straight to memory
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int f = 0; f < C::NMF; ++f) {
+                    const uint32_t e = static_cast<uint32_t>(word[u] >> shift[f]) & 255u;
+                    a[u][f] = *reinterpret_cast<const v4i *>(ltab + laneoff[f] + e * 256u);
+                }
+            // Each accumulator starts at 128 * M - (T + 1): the 128 * M undoes the -128 bias of the M
+            // signed bytes and the rest turns "qd <= T" into "result < 0", so one sign test of the
+            // OR of all results of the U steps decides whether anything was hit.
+            v4i acc[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) acc[u] = acc0;
+#pragma unroll
+            for (int f = 0; f < C::NMF; ++f)
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[u][f], bsel, acc[u], 0, 0, 0);
+            int sign = 0;
+#pragma unroll
+            for (int u = 0; u < U; ++u) sign |= acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
+            if (__ballot(sign < 0)) {                                // uniform, rare
+                bool fill = false;                                   // this lane saw the queue half full
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int su = acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
+                    if (!__ballot(su < 0)) continue;                 // uniform: no hit in this step
+                    const int first = (t0 + u) * C::CPS;             // first code of the step within the group
+                    bool h[4];
+                    uint32_t cnt = 0;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        h[v] = acc[u][v] < 0 && first + cd[v] < nlive;
+                        cnt += h[v] ? 1u : 0u;
+                    }
+                    if (cnt) {
+                        uint32_t pos = atomicAdd(wqn, cnt);          // one LDS round trip per lane and step
+                        fill |= pos + cnt >= C::QCAP / 2;
+#pragma unroll
+                        for (int v = 0; v < 4; ++v) {
+                            if (!h[v]) continue;
+                            const uint64_t id = gbase + first + cd[v];
+                            // result + T + 1 is the unsaturated sum (unsigned wrap-around is intended)
+                            const uint32_t sum = static_cast<uint32_t>(acc[u][v]) + static_cast<uint32_t>(tl[v]) + 1u;
+                            const uint32_t qd = min(sum, 255u);
+                            const uint64_t rec =
+                                (static_cast<uint64_t>(ql[v]) << 40) | (static_cast<uint64_t>(qd) << 32) | id;
+                            if (pos < C::QCAP) wq[pos] = rec;
+                            else insert(rec);                        // queue full: go straight to memory
+                            ++pos;
+                        }
                     }
                 }
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                if (queue_len() >= C::QCAP / 2) flush();
+                if (__ballot(fill)) flush();
             }
         }
+      }
     }
     flush();
 }
