@@ -51,9 +51,9 @@ struct FastCfg {
     static constexpr int CLS = M / 4;               // bytes per residue class j mod 4 in the code scratch
     static constexpr int TAB_BYTES = M * 256 * QT;
     static constexpr int SCR_BYTES = WAVES * 64 * M;
-    static constexpr int QCAP = 64;                 // pending-candidate queue entries per wavefront
+    static constexpr int QCAP = 64;                 // pending-candidate queue entries per wavefront (>= 64)
     static constexpr int Q_BYTES = WAVES * QCAP * 8;
-    static constexpr int LDS_BYTES = TAB_BYTES + SCR_BYTES + Q_BYTES + WAVES * 4;
+    static constexpr int LDS_BYTES = TAB_BYTES + SCR_BYTES + Q_BYTES;
     static_assert(NSLOT <= M && M % 4 == 0, "row slots must rotate within the sub-quantizers");
     static_assert(STEPS % UNROLL == 0, "unroll must divide the steps of a group");
 };
@@ -178,7 +178,6 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint8_t *scr = smem + C::TAB_BYTES + wave * (64 * M);
     uint64_t *wq = reinterpret_cast<uint64_t *>(smem + C::TAB_BYTES + C::SCR_BYTES) + wave * C::QCAP;
-    uint32_t *wqn = reinterpret_cast<uint32_t *>(smem + C::TAB_BYTES + C::SCR_BYTES + C::Q_BYTES) + wave;
 
     const int tile = blockIdx.x;
     const int q0 = tile * QT;
@@ -186,7 +185,6 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
         const uint4 *src = reinterpret_cast<const uint4 *>(qsw + static_cast<size_t>(tile) * C::TAB_BYTES);
         uint4 *dst = reinterpret_cast<uint4 *>(ltab);
         for (int v = tid; v < C::TAB_BYTES / 16; v += WAVES * 64) dst[v] = src[v];
-        if (lane == 0) *wqn = 0;
     }
     __syncthreads();
 
@@ -220,22 +218,18 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
 
     auto insert = [&](uint64_t rec) { append_candidate(rec, q0, r, cap, upd, t_cur, count, chist, keys); };
 
-    // The queue counter is only ever touched with LDS (ds_*) instructions: generic-pointer (flat)
-    // accesses to the same word are not ordered against them by the hardware.
-    auto queue_len = [&]() -> uint32_t {
-        return __hip_atomic_load(wqn, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-    };
+    // Pending candidates of this wavefront: records wq[0 .. qlen).  qlen is wave-uniform (it only
+    // changes by ballot counts), so it lives in a scalar register and the queue needs no atomics.
+    uint32_t qlen = 0;
     auto flush = [&]() {
-        const uint32_t n = min(queue_len(), static_cast<uint32_t>(C::QCAP));
-        for (uint32_t e = lane; e < n; e += 64) {
-            const uint64_t rec = wq[e];
-            if ((rec >> 40) < static_cast<uint64_t>(QT)) insert(rec);
-        }
-        // every lane has read its entry before the counter is reset, and the reset is in place
-        // before any lane pushes again (the wavefront runs in lockstep; the barriers say so)
+        // the wavefront runs in lockstep; the barriers say that every push is in place before the
+        // entries are read, and that every lane has read its entry before the next push overwrites it
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
-        if (lane == 0) __hip_atomic_store(wqn, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (uint32_t e = lane; e < qlen; e += 64) insert(wq[e]);
+        qlen = 0;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
@@ -357,41 +351,29 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
 #pragma unroll
             for (int u = 0; u < U; ++u) sign |= acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
             if (__ballot(sign < 0)) {                                // uniform, rare
-                bool fill = false;                                   // this lane saw the queue half full
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     const int su = acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
                     if (!__ballot(su < 0)) continue;                 // uniform: no hit in this step
                     const int first = (t0 + u) * C::CPS;             // first code of the step within the group
-                    bool h[4];
-                    uint32_t cnt = 0;
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        h[v] = acc[u][v] < 0 && first + cd[v] < nlive;
-                        cnt += h[v] ? 1u : 0u;
-                    }
-                    if (cnt) {
-                        uint32_t pos = atomicAdd(wqn, cnt);          // one LDS round trip per lane and step
-                        fill |= pos + cnt >= C::QCAP / 2;
-#pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            if (!h[v]) continue;
+                        const bool h = acc[u][v] < 0 && first + cd[v] < nlive;
+                        const uint64_t mask = __ballot(h);
+                        if (!mask) continue;                         // uniform
+                        const uint32_t cnt = __popcll(mask);
+                        if (qlen + cnt > C::QCAP) flush();           // uniform: make room (cnt <= 64 = QCAP)
+                        if (h) {
                             const uint64_t id = gbase + first + cd[v];
                             // result + T + 1 is the unsaturated sum (unsigned wrap-around is intended)
                             const uint32_t sum = static_cast<uint32_t>(acc[u][v]) + static_cast<uint32_t>(tl[v]) + 1u;
                             const uint32_t qd = min(sum, 255u);
-                            const uint64_t rec =
+                            wq[qlen + __popcll(mask & ((1ull << lane) - 1ull))] =
                                 (static_cast<uint64_t>(ql[v]) << 40) | (static_cast<uint64_t>(qd) << 32) | id;
-                            if (pos < C::QCAP) wq[pos] = rec;
-                            else insert(rec);                        // queue full: go straight to memory
-                            ++pos;
                         }
+                        qlen += cnt;
                     }
                 }
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                if (__ballot(fill)) flush();
             }
         }
       }
