@@ -144,6 +144,61 @@ int dcpq_search(const float *queries, int nq, const float *codebooks, const floa
                 uint32_t *ids, float *dist, int chunk_queries, void *workspace,
                 size_t workspace_bytes, void *stream);
 
+/* =============================================================================================
+ * Inverted-index variant (Sec. 2.2 inverted lists with residual encoding; Sec. 2.3 Index step and
+ * "each step is repeated ma times"; Sec. 3.3 with derived codebooks).
+ *
+ * Layout: nlist cells with centres coarse[nlist][D]; list l holds the codes at positions
+ * offsets[l] .. offsets[l+1]-1 of the code array (offsets: int64 [nlist+1], increasing, last one =
+ * number of codes < 2^32); a vector's id is its position in the code array; codes quantize the
+ * residual x - coarse[l].  nprobe (the paper's ma) lists are scanned per query, nprobe <= 512, and
+ * the lists named in one row of `probe` must be distinct.
+ * ============================================================================================= */
+
+/* Index step: probe[q][:] = the nprobe cells with the smallest || y_q - coarse[l] ||^2 (matrix
+ * cores, double-precision accumulate, compared after rounding to fp32), ordered by (distance, l).
+ *   probe : int32_t [nq][nprobe] (output)   workspace : dcpq_ivf_probe_workspace_bytes(nq, nlist) */
+size_t dcpq_ivf_probe_workspace_bytes(int nq, int nlist);
+int dcpq_ivf_probe(const float *queries, int nq, int D, const float *coarse, int nlist, int nprobe,
+                   int32_t *probe, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Tables step: for every query q and probed list p, the residual rho = y_q - coarse[probe[q][p]]
+ * (fp32), its small tables on the derived codebooks (as in dcpq_build_small_tables), and their
+ * 8-bit quantization with ONE pair of bounds per query: qmin = smallest entry over all nprobe
+ * tables of the query; qmax = largest small-table distance over the first min(r, total) codes met
+ * when walking the probed lists in probe order, each code against its own list's tables.  If the
+ * probed lists are empty the bounds are (0, 0) and the tables all zero.
+ *   qtab : uint8_t [nq][nprobe][m][256] (output)   bounds : float [nq][2] (output)
+ *   workspace : dcpq_ivf_tables_workspace_bytes(nq) */
+size_t dcpq_ivf_tables_workspace_bytes(int nq);
+int dcpq_ivf_build_small_tables(const float *queries, int nq, const float *coarse, int nlist,
+                                const int32_t *probe, int nprobe, const float *derived, int m, int dsub,
+                                const uint16_t *codes, const int64_t *offsets, uint32_t r, uint8_t *qtab,
+                                float *bounds, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Scan step over the probed lists: the r smallest by (qd, id) over their union, qd computed with
+ * the tables of the list the code lies in.  If the probed lists hold fewer than r codes the tail
+ * is padded with id DCPQ_PAD_ID and qd 255; count[q] = number of valid candidates.
+ *   cand_id : uint32_t [nq][r]  cand_qd : uint8_t [nq][r]  count : uint32_t [nq]  (outputs)
+ *   workspace : dcpq_ivf_scan_workspace_bytes(nq, r), 256-byte aligned */
+size_t dcpq_ivf_scan_workspace_bytes(int nq, uint32_t r);
+int dcpq_ivf_scan_candidates(const uint16_t *codes, const int64_t *offsets, int nlist, int m,
+                             const int32_t *probe, int nprobe, const uint8_t *qtab, int nq, uint32_t r,
+                             uint32_t *cand_id, uint8_t *cand_qd, uint32_t *count, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/* Refine step: d(q, i) = sum_j || (y_q - coarse[l(i)])^j - codebooks[j][codes[i][j]] ||^2 with l(i)
+ * the probed list holding i, computed directly in double precision (Eq. 3 on the residual) and
+ * rounded to fp32; the k smallest by (d, i), ascending; padded candidates give id DCPQ_PAD_ID and
+ * distance +inf.
+ *   ids : uint32_t [nq][k]  dist : float [nq][k] (outputs)
+ *   workspace : dcpq_ivf_refine_workspace_bytes(nq, r) (may be 0) */
+size_t dcpq_ivf_refine_workspace_bytes(int nq, uint32_t r);
+int dcpq_ivf_refine_topk(const float *queries, const float *coarse, int nlist, const float *codebooks, int m,
+                         int dsub, const uint16_t *codes, const int64_t *offsets, const int32_t *probe,
+                         int nprobe, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
+                         float *dist, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Optional per-kernel timing (measurement aid, not part of the search).  While enabled, every
  * kernel the library launches is bracketed by two HIP events recorded on the stream it is launched

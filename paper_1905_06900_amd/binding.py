@@ -43,6 +43,14 @@ _SIGNATURES = {
     "dcpq_refine_workspace_bytes": (_sz, [_i, _u32]),
     "dcpq_refine_topk": (_i, [_vp, _vp, _u64, _i, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_search_workspace_bytes": (_sz, [_u64, _i, _i, _u32, _i]),
+    "dcpq_ivf_probe_workspace_bytes": (_sz, [_i, _i]),
+    "dcpq_ivf_probe": (_i, [_vp, _i, _i, _vp, _i, _i, _vp, _vp, _sz, _vp]),
+    "dcpq_ivf_tables_workspace_bytes": (_sz, [_i]),
+    "dcpq_ivf_build_small_tables": (_i, [_vp, _i, _vp, _i, _vp, _i, _vp, _i, _i, _vp, _vp, _u32, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_ivf_scan_workspace_bytes": (_sz, [_i, _u32]),
+    "dcpq_ivf_scan_candidates": (_i, [_vp, _vp, _i, _i, _vp, _i, _vp, _i, _u32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_ivf_refine_workspace_bytes": (_sz, [_i, _u32]),
+    "dcpq_ivf_refine_topk": (_i, [_vp, _vp, _i, _vp, _i, _i, _vp, _vp, _vp, _i, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_profile_enable": (_i, [_i]),
     "dcpq_profile_stage_count": (_i, []),
     "dcpq_profile_stage_name": (C.c_char_p, [_i]),
@@ -225,3 +233,70 @@ def profile_read() -> dict:
         _check(l.dcpq_profile_read(s, C.byref(ms), C.byref(n)))
         out[l.dcpq_profile_stage_name(s).decode()] = (ms.value, int(n.value))
     return out
+
+
+# ---- inverted-index variant ---------------------------------------------------------------------
+def ivf_probe(queries: torch.Tensor, coarse: torch.Tensor, nprobe: int) -> torch.Tensor:
+    """-> probe int32 [nq][nprobe], ordered by (distance, list id)"""
+    nq, D = queries.shape
+    nlist = coarse.shape[0]
+    assert coarse.shape[1] == D
+    dev = queries.device
+    probe = torch.empty((nq, nprobe), dtype=torch.int32, device=dev)
+    ws = _workspace(lib().dcpq_ivf_probe_workspace_bytes(nq, nlist), dev)
+    _check(lib().dcpq_ivf_probe(_dev(queries, torch.float32, "queries"), nq, D, _dev(coarse, torch.float32, "coarse"),
+                                nlist, nprobe, probe.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return probe
+
+
+def ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r: int):
+    """-> (qtab u8 [nq][nprobe][m][256], bounds f32 [nq][2])"""
+    m, _, dsub = derived.shape
+    nq, nprobe = probe.shape
+    nlist = coarse.shape[0]
+    dev = queries.device
+    qtab = torch.empty((nq, nprobe, m, 256), dtype=torch.uint8, device=dev)
+    bounds = torch.empty((nq, 2), dtype=torch.float32, device=dev)
+    ws = _workspace(lib().dcpq_ivf_tables_workspace_bytes(nq), dev)
+    _check(lib().dcpq_ivf_build_small_tables(
+        _dev(queries, torch.float32, "queries"), nq, _dev(coarse, torch.float32, "coarse"), nlist,
+        _dev(probe, torch.int32, "probe"), nprobe, _dev(derived, torch.float32, "derived"), m, dsub,
+        _dev(codes, torch.uint16, "codes"), _dev(offsets, torch.int64, "offsets"), r, qtab.data_ptr(),
+        bounds.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return qtab, bounds
+
+
+def ivf_scan_candidates(codes, offsets, probe, qtab, r: int):
+    """-> (cand_id u32 [nq][r], cand_qd u8 [nq][r], count u32 [nq])"""
+    m = codes.shape[1]
+    nq, nprobe = probe.shape
+    nlist = offsets.shape[0] - 1
+    dev = codes.device
+    cand_id = torch.empty((nq, r), dtype=torch.uint32, device=dev)
+    cand_qd = torch.empty((nq, r), dtype=torch.uint8, device=dev)
+    count = torch.empty((nq,), dtype=torch.uint32, device=dev)
+    ws = _workspace(lib().dcpq_ivf_scan_workspace_bytes(nq, r), dev)
+    _check(lib().dcpq_ivf_scan_candidates(
+        _dev(codes, torch.uint16, "codes"), _dev(offsets, torch.int64, "offsets"), nlist, m,
+        _dev(probe, torch.int32, "probe"), nprobe, _dev(qtab, torch.uint8, "qtab"), nq, r, cand_id.data_ptr(),
+        cand_qd.data_ptr(), count.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return cand_id, cand_qd, count
+
+
+def ivf_refine_topk(queries, coarse, codebooks, codes, offsets, probe, cand_id, k: int):
+    """-> (ids u32 [nq][k], dist f32 [nq][k])"""
+    m, _, dsub = codebooks.shape
+    nq, r = cand_id.shape
+    nprobe = probe.shape[1]
+    nlist = coarse.shape[0]
+    dev = queries.device
+    ids = torch.empty((nq, k), dtype=torch.uint32, device=dev)
+    dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    ws = _workspace(lib().dcpq_ivf_refine_workspace_bytes(nq, r), dev)
+    _check(lib().dcpq_ivf_refine_topk(
+        _dev(queries, torch.float32, "queries"), _dev(coarse, torch.float32, "coarse"), nlist,
+        _dev(codebooks, torch.float32, "codebooks"), m, dsub, _dev(codes, torch.uint16, "codes"),
+        _dev(offsets, torch.int64, "offsets"), _dev(probe, torch.int32, "probe"), nprobe,
+        _dev(cand_id, torch.uint32, "cand_id"), nq, r, k, ids.data_ptr(), dist.data_ptr(), ws.data_ptr(),
+        ws.numel(), _stream()))
+    return ids, dist

@@ -76,6 +76,9 @@ int launch_small_tables(const float *queries, int nq, const float *derived, int 
                         float *bounds, float *small, hipStream_t st);
 int launch_full_tables(const float *queries, int nq, const float *codebooks, int m, int dsub,
                        float *tables, hipStream_t st);
+// Same kernel for any number of centroids (the coarse quantizer: m = 1, dsub = D, ncent = nlist).
+int launch_distance_tables(const float *queries, int nq, const float *codebooks, int m, int dsub, int ncent,
+                           float *tables, int stage, hipStream_t st);
 // mode: DCPQ_SCAN_AUTO or DCPQ_SCAN_THREE_PASS
 int launch_scan(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                 uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st);

@@ -1,0 +1,644 @@
+// Alg. 3 with an inverted index and residual encoding (Sec. 2.2, Sec. 2.3 "each step is repeated
+// ma times", Sec. 3.3).  List l holds the codes at positions offsets[l] .. offsets[l+1]-1 of the
+// code array (a vector's id is its position); codes quantize the residual x - c_l.
+//
+//   Index   ivf_probe           the nprobe closest cell centres per query (matrix cores, fp64)
+//   Tables  ivf_small_tables    per (query, probed list): small tables of the residual query
+//                               rho = y - c_l on the derived codebooks; ONE (qmin, qmax) pair per
+//                               query -- qmin over all its lists' tables, qmax over the first
+//                               min(r, total) codes met walking its lists in probe order -- so that
+//                               integer distances from different lists are comparable
+//   Scan    ivf_scan            the r smallest (qd, id) over the union of the probed lists: the
+//                               three-pass selection of scan.hip over a per-query list of "units"
+//                               (runs of codes inside one list, in increasing id order), one
+//                               wavefront per unit with that (query, list)'s 8-bit tables in LDS
+//   Refine  ivf_refine_topk     Eq. 3 on the residual of each candidate's own list, directly from
+//                               the full codebooks in double precision (per-list 2^16-entry tables
+//                               would cost nprobe table builds per query), then the k best
+#include "common.h"
+#include "scan_internal.h"
+
+namespace dcpq {
+
+constexpr int kIvfUnitsPerQuery = 1024;   // upper bound of scan units per query (unit size adapts)
+constexpr int kIvfMaxProbe = 512;         // nprobe supported by the per-query planning kernels
+
+struct IvfUnit {
+    uint64_t begin;    // first code of the unit (global position)
+    uint32_t count;    // codes in the unit
+    uint32_t p;        // index of the list in the query's probe order (selects the tables)
+};
+
+// ------------------------------------------------------------------------------------------------
+// Index step: nprobe smallest coarse distances per query, ordered by (distance, list id).
+// dist: [nq][nlist] fp32 squared distances.  One workgroup per query, 4-level radix select on the
+// bit patterns (non-negative floats order like their bits), ties at the cut taken in id order.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(1024) void ivf_select_probe_kernel(const float *__restrict__ dist, int nlist, int nprobe,
+                                                               int32_t *__restrict__ probe)
+{
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_prefix, s_need, s_pos;
+    __shared__ uint32_t part[1024];
+    __shared__ uint64_t sel[kIvfMaxProbe * 2];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const uint32_t *d = reinterpret_cast<const uint32_t *>(dist) + static_cast<size_t>(q) * nlist;
+
+    // value of the nprobe-th smallest key, one byte at a time from the top
+    uint32_t prefix = 0, need = nprobe;
+    for (int level = 3; level >= 0; --level) {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        const uint32_t shift = 8 * level;
+        const uint32_t hi_mask = level == 3 ? 0u : ~0u << (shift + 8);
+        for (int l = tid; l < nlist; l += 1024) {
+            const uint32_t key = d[l];
+            if ((key & hi_mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t cum = 0, b = 0;
+            for (; b < 256; ++b) {
+                if (cum + hist[b] >= need) break;
+                cum += hist[b];
+            }
+            s_prefix = prefix | (b << shift);
+            s_need = need - cum;
+        }
+        __syncthreads();
+        prefix = s_prefix;
+        need = s_need;
+        __syncthreads();
+    }
+    const uint32_t kth = prefix;          // exact key of the nprobe-th smallest; `need` of the equal keys are taken
+    // contiguous id ranges per thread so that equal keys can be ranked in id order
+    const int per = (nlist + 1023) / 1024;
+    const int lo = tid * per, hi = min(nlist, lo + per);
+    uint32_t eq = 0;
+    for (int l = lo; l < hi; ++l) eq += d[l] == kth ? 1u : 0u;
+    part[tid] = eq;
+    if (tid == 0) s_pos = 0;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+        const uint32_t add = tid >= off ? part[tid - off] : 0u;
+        __syncthreads();
+        part[tid] += add;
+        __syncthreads();
+    }
+    uint32_t rank = part[tid] - eq;       // equal keys before this thread's range
+    for (int l = lo; l < hi; ++l) {
+        const uint32_t key = d[l];
+        bool take = key < kth;
+        if (key == kth) { take = rank < need; ++rank; }
+        if (take) {
+            const uint32_t pos = atomicAdd(&s_pos, 1u);
+            if (pos < static_cast<uint32_t>(nprobe)) sel[pos] = make_key(key, static_cast<uint32_t>(l));
+        }
+    }
+    __syncthreads();
+    uint32_t np2 = 1;
+    while (np2 < static_cast<uint32_t>(nprobe)) np2 <<= 1;
+    for (uint32_t t = nprobe + tid; t < np2; t += 1024) sel[t] = ~0ull;
+    bitonic_sort(sel, np2);
+    for (int t = tid; t < nprobe; t += 1024) probe[static_cast<size_t>(q) * nprobe + t] = static_cast<int32_t>(sel[t] & 0xFFFFFFFFu);
+}
+
+// ------------------------------------------------------------------------------------------------
+// Tables step.  All arithmetic fp32, one rounding per operation, fixed order (feeds integers).
+// ------------------------------------------------------------------------------------------------
+__device__ inline float ivf_block_reduce(float v, bool want_max, float *red)
+{
+    for (int off = 32; off > 0; off >>= 1) {
+        const float o = __shfl_xor(v, off, kWave);
+        v = want_max ? fmaxf(v, o) : fminf(v, o);
+    }
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    __syncthreads();
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    float out = red[0];
+    for (int w = 1; w < 4; ++w) out = want_max ? fmaxf(out, red[w]) : fminf(out, red[w]);
+    return out;
+}
+
+// Small-table entry i of sub-quantizer j for the residual rho (in LDS): sum_t (rho_jt - cbar_jit)^2.
+__device__ inline float ivf_entry(const float *rho, const float *derived, int dsub, int j, int i)
+{
+    const float *c = derived + (static_cast<size_t>(j) * kSmallSize + i) * dsub;
+    float acc = 0.0f;
+    for (int t = 0; t < dsub; ++t) {
+        const float diff = __fsub_rn(rho[j * dsub + t], c[t]);
+        acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+    }
+    return acc;
+}
+
+// MODE 0: smallest entry of the (query, list) tables -> atomic min into qmin_bits[q].
+// MODE 1: quantize with the query's bounds -> qtab[q][p][m][256].
+// grid (nprobe, nq), 256 threads; thread i owns entry i of every table.
+template <int MODE>
+__global__ __launch_bounds__(256) void ivf_tables_kernel(const float *__restrict__ queries, const float *__restrict__ coarse,
+                                                        const int32_t *__restrict__ probe, int nprobe,
+                                                        const float *__restrict__ derived, int m, int dsub,
+                                                        uint32_t *__restrict__ qmin_bits, const float *__restrict__ bounds,
+                                                        uint8_t *__restrict__ qtab)
+{
+    extern __shared__ float lds[];         // rho [m*dsub]
+    __shared__ float red[4];
+    const int p = blockIdx.x, q = blockIdx.y, tid = threadIdx.x;
+    const int D = m * dsub;
+    const int l = probe[static_cast<size_t>(q) * nprobe + p];
+    for (int t = tid; t < D; t += 256)
+        lds[t] = __fsub_rn(queries[static_cast<size_t>(q) * D + t], coarse[static_cast<size_t>(l) * D + t]);
+    __syncthreads();
+    if (MODE == 0) {
+        float lo = INFINITY;
+        for (int j = 0; j < m; ++j) lo = fminf(lo, ivf_entry(lds, derived, dsub, j, tid));
+        lo = ivf_block_reduce(lo, false, red);
+        if (tid == 0) atomicMin(&qmin_bits[q], __float_as_uint(lo));    // entries are >= +0
+    } else {
+        const float qmin = bounds[2 * q], qmax = bounds[2 * q + 1];
+        const float den = __fsub_rn(qmax, qmin);
+        for (int j = 0; j < m; ++j) {
+            const float v = ivf_entry(lds, derived, dsub, j, tid);
+            uint8_t code = 0;
+            if (den > 0.0f) {
+                const float u = __fmul_rn(__fdiv_rn(__fsub_rn(v, qmin), den), 255.0f);
+                code = (u >= 255.0f) ? static_cast<uint8_t>(255) : static_cast<uint8_t>(floorf(u));
+            }
+            qtab[((static_cast<size_t>(q) * nprobe + p) * m + j) * kSmallSize + tid] = code;
+        }
+    }
+}
+
+// qmax: largest small-table distance over the first min(r, total) codes met walking the probed
+// lists in probe order (each code against its own list's residual).  One workgroup per query.
+// Also finishes the bounds: (qmin, qmax), or (0, 0) when the probed lists are empty.
+__global__ __launch_bounds__(256) void ivf_qmax_kernel(const float *__restrict__ queries, const float *__restrict__ coarse,
+                                                      const int32_t *__restrict__ probe, int nprobe,
+                                                      const float *__restrict__ derived, int m, int dsub,
+                                                      const uint16_t *__restrict__ codes, const int64_t *__restrict__ offsets,
+                                                      uint32_t r, const uint32_t *__restrict__ qmin_bits,
+                                                      float *__restrict__ bounds)
+{
+    __shared__ uint64_t start[kIvfMaxProbe + 1];   // exclusive prefix of the list sizes in probe order
+    __shared__ int lst[kIvfMaxProbe];
+    __shared__ float red[4];
+    const int q = blockIdx.x, tid = threadIdx.x;
+    const int D = m * dsub;
+    for (int p = tid; p < nprobe; p += 256) lst[p] = probe[static_cast<size_t>(q) * nprobe + p];
+    __syncthreads();
+    if (tid == 0) {
+        uint64_t s = 0;
+        for (int p = 0; p < nprobe; ++p) { start[p] = s; s += static_cast<uint64_t>(offsets[lst[p] + 1] - offsets[lst[p]]); }
+        start[nprobe] = s;
+    }
+    __syncthreads();
+    const uint64_t total = start[nprobe];
+    const uint32_t n_first = static_cast<uint32_t>(total < r ? total : r);
+    const float *y = queries + static_cast<size_t>(q) * D;
+    float hi = -INFINITY;
+    for (uint32_t i = tid; i < n_first; i += 256) {
+        int p = 0;                                    // list holding the i-th code of the walk:
+        for (int lo = 0, up = nprobe; ;) {            // the first p with start[p + 1] > i (skips empty lists)
+            if (lo >= up) { p = lo; break; }
+            const int mid = (lo + up) / 2;
+            if (start[mid + 1] <= i) lo = mid + 1; else up = mid;
+        }
+        const int l = lst[p];
+        const uint16_t *c = codes + (static_cast<size_t>(offsets[l]) + (i - start[p])) * m;
+        const float *cl = coarse + static_cast<size_t>(l) * D;
+        float d = 0.0f;
+        for (int j = 0; j < m; ++j) {
+            const float *cen = derived + (static_cast<size_t>(j) * kSmallSize + (c[j] & 255)) * dsub;
+            float acc = 0.0f;
+            for (int t = 0; t < dsub; ++t) {
+                const float rho = __fsub_rn(y[j * dsub + t], cl[j * dsub + t]);
+                const float diff = __fsub_rn(rho, cen[t]);
+                acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+            }
+            d = j == 0 ? acc : __fadd_rn(d, acc);
+        }
+        hi = fmaxf(hi, d);
+    }
+    hi = ivf_block_reduce(hi, true, red);
+    if (tid == 0) {
+        if (total == 0) { bounds[2 * q] = 0.0f; bounds[2 * q + 1] = 0.0f; }
+        else { bounds[2 * q] = __uint_as_float(qmin_bits[q]); bounds[2 * q + 1] = hi; }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Scan step: per-query unit lists.
+// ------------------------------------------------------------------------------------------------
+// One workgroup per query: probed lists sorted by list id (so that units follow increasing vector
+// id), a unit size that keeps the query within kIvfUnitsPerQuery units, and the unit records.
+__global__ __launch_bounds__(256) void ivf_plan_kernel(const int32_t *__restrict__ probe, int nprobe,
+                                                      const int64_t *__restrict__ offsets, uint32_t r,
+                                                      IvfUnit *__restrict__ units, uint32_t *__restrict__ nunits,
+                                                      uint32_t *__restrict__ count)
+{
+    __shared__ uint64_t key[kIvfMaxProbe];         // (list id << 32) | probe position
+    __shared__ uint32_t ubase[kIvfMaxProbe + 1];
+    __shared__ uint64_t s_total;
+    __shared__ uint32_t s_unit;
+    const int q = blockIdx.x, tid = threadIdx.x;
+    uint32_t np2 = 1;
+    while (np2 < static_cast<uint32_t>(nprobe)) np2 <<= 1;
+    for (uint32_t p = tid; p < np2; p += 256)
+        key[p] = p < static_cast<uint32_t>(nprobe)
+                     ? make_key(static_cast<uint32_t>(probe[static_cast<size_t>(q) * nprobe + p]), p) : ~0ull;
+    bitonic_sort(key, np2);
+    if (tid == 0) {
+        uint64_t total = 0;
+        for (int s = 0; s < nprobe; ++s) { const int l = static_cast<int>(key[s] >> 32); total += static_cast<uint64_t>(offsets[l + 1] - offsets[l]); }
+        uint64_t unit = (total + (kIvfUnitsPerQuery - nprobe) - 1) / (kIvfUnitsPerQuery - nprobe);
+        unit = (unit + 63) / 64 * 64;
+        if (unit < 256) unit = 256;
+        uint32_t u = 0;
+        for (int s = 0; s < nprobe; ++s) {
+            const int l = static_cast<int>(key[s] >> 32);
+            ubase[s] = u;
+            u += static_cast<uint32_t>((static_cast<uint64_t>(offsets[l + 1] - offsets[l]) + unit - 1) / unit);
+        }
+        ubase[nprobe] = u;
+        s_total = total; s_unit = static_cast<uint32_t>(unit);
+        nunits[q] = u;
+        count[q] = static_cast<uint32_t>(total < r ? total : r);
+    }
+    __syncthreads();
+    const uint32_t unit = s_unit;
+    for (int s = 0; s < nprobe; ++s) {
+        const int l = static_cast<int>(key[s] >> 32);
+        const uint64_t lo = static_cast<uint64_t>(offsets[l]), size = static_cast<uint64_t>(offsets[l + 1]) - lo;
+        const uint32_t nu = ubase[s + 1] - ubase[s];
+        for (uint32_t c = tid; c < nu; c += 256) {
+            IvfUnit rec;
+            rec.begin = lo + static_cast<uint64_t>(c) * unit;
+            rec.count = static_cast<uint32_t>(min(static_cast<uint64_t>(unit), size - static_cast<uint64_t>(c) * unit));
+            rec.p = static_cast<uint32_t>(key[s] & 0xFFFFFFFFu);
+            units[static_cast<size_t>(q) * kIvfUnitsPerQuery + ubase[s] + c] = rec;
+        }
+    }
+}
+
+enum IvfMode { kIvfHist = 0, kIvfTieCount = 1, kIvfCollect = 2 };
+
+// One wavefront per unit; grid (kIvfUnitsPerQuery / 4, nq), 256 threads.  The wavefront keeps the
+// 8-bit tables of its (query, list) in its own LDS slot and walks the unit 64 codes at a time.
+template <int M, int MODE>
+__global__ __launch_bounds__(256) void ivf_scan_kernel(const uint16_t *__restrict__ codes, const IvfUnit *__restrict__ units,
+                                                      const uint32_t *__restrict__ nunits, const uint8_t *__restrict__ qtab,
+                                                      int nprobe, uint32_t r, uint32_t *__restrict__ hist,
+                                                      const uint32_t *__restrict__ thr, uint32_t *__restrict__ tie,
+                                                      uint32_t *__restrict__ counter, uint64_t *__restrict__ keys)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = blockIdx.y;
+    const uint32_t u = blockIdx.x * 4 + wave;
+    uint8_t *tab = smem + wave * (M * 256);                                      // [M][256]
+    uint32_t *lhist = reinterpret_cast<uint32_t *>(smem + 4 * M * 256) + wave * 256;   // kIvfHist only
+    const bool active = u < nunits[q];
+    IvfUnit un{0, 0, 0};
+    if (active) un = units[static_cast<size_t>(q) * kIvfUnitsPerQuery + u];
+    if (active) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(qtab + (static_cast<size_t>(q) * nprobe + un.p) * M * 256);
+        uint4 *dst = reinterpret_cast<uint4 *>(tab);
+        for (int v = lane; v < M * 256 / 16; v += 64) dst[v] = src[v];
+        if (MODE == kIvfHist)
+            for (int v = lane; v < 256; v += 64) lhist[v] = 0;
+    }
+    __syncthreads();
+    if (!active) return;
+
+    uint32_t T = 0, aux = 0;
+    if (MODE != kIvfHist) {
+        T = thr[2 * q];
+        if (MODE == kIvfCollect) aux = tie[static_cast<size_t>(q) * kIvfUnitsPerQuery + u];
+    }
+    for (uint32_t base = 0; base < un.count; base += 64) {
+        const uint32_t k = base + lane;
+        const bool live = k < un.count;
+        const uint64_t id = un.begin + k;
+        uint32_t s = 0;
+        if (live) {
+            const uint16_t *c = codes + id * M;
+#pragma unroll
+            for (int j = 0; j < M; ++j) s += tab[j * 256 + (c[j] & 255)];
+        }
+        const uint32_t qd = min(s, 255u);
+        if (MODE == kIvfHist) {
+            if (live) atomicAdd(&lhist[qd], 1u);
+        } else if (MODE == kIvfTieCount) {
+            aux += __popcll(__ballot(live && qd == T));
+        } else {
+            const bool below = live && qd < T;
+            const bool tied = live && qd == T;
+            const uint64_t tied_mask = __ballot(tied);
+            bool take = below;
+            if (tied_mask) {
+                const uint32_t rank = __popcll(tied_mask & ((1ull << lane) - 1ull));
+                take = below || (tied && rank < aux);
+                const uint32_t n_tied = __popcll(tied_mask);
+                aux = aux > n_tied ? aux - n_tied : 0u;
+            }
+            const uint64_t take_mask = __ballot(take);
+            if (take_mask) {
+                uint32_t slot0 = 0;
+                if (lane == 0) slot0 = atomicAdd(&counter[q], static_cast<uint32_t>(__popcll(take_mask)));
+                slot0 = __shfl(slot0, 0, kWave);
+                if (take) {
+                    const uint32_t slot = slot0 + __popcll(take_mask & ((1ull << lane) - 1ull));
+                    if (slot < r) keys[static_cast<size_t>(q) * r + slot] = make_key(qd, static_cast<uint32_t>(id));
+                }
+            }
+        }
+    }
+    if (MODE == kIvfHist) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int v = lane; v < 256; v += 64) {
+            const uint32_t c = lhist[v];
+            if (c) atomicAdd(&hist[static_cast<size_t>(q) * 256 + v], c);
+        }
+    } else if (MODE == kIvfTieCount) {
+        if (lane == 0) tie[static_cast<size_t>(q) * kIvfUnitsPerQuery + u] = aux;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Refine step: Eq. 3 on residuals, double precision, then top-k.  One workgroup per query.
+// ------------------------------------------------------------------------------------------------
+template <int M>
+__global__ __launch_bounds__(1024) void ivf_refine_kernel(const float *__restrict__ queries, const float *__restrict__ coarse,
+                                                         const float *__restrict__ cb, int dsub,
+                                                         const uint16_t *__restrict__ codes, const int64_t *__restrict__ offsets,
+                                                         const int32_t *__restrict__ probe, int nprobe,
+                                                         const uint32_t *__restrict__ cand_id, uint32_t r, uint32_t k,
+                                                         uint32_t n_pow2, int use_lds, uint64_t *__restrict__ spill,
+                                                         uint32_t *__restrict__ ids, float *__restrict__ dist)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    __shared__ uint32_t lbeg[kIvfMaxProbe], lend[kIvfMaxProbe];   // ids are 32-bit, so are list bounds
+    __shared__ int lst[kIvfMaxProbe];
+    const int q = blockIdx.x;
+    const int D = M * dsub;
+    for (int p = threadIdx.x; p < nprobe; p += blockDim.x) {
+        const int l = probe[static_cast<size_t>(q) * nprobe + p];
+        lst[p] = l;
+        lbeg[p] = static_cast<uint32_t>(offsets[l]);
+        lend[p] = static_cast<uint32_t>(offsets[l + 1]);
+    }
+    __syncthreads();
+    uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(q) * n_pow2;
+    const float *y = queries + static_cast<size_t>(q) * D;
+    for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x) {
+        uint64_t key = ~0ull;
+        if (t < r) {
+            const uint32_t id = cand_id[static_cast<size_t>(q) * r + t];
+            int p = -1;
+            for (int z = 0; z < nprobe; ++z)
+                if (id >= lbeg[z] && id < lend[z]) { p = z; break; }
+            if (p >= 0) {          // pad slots (id 0xFFFFFFFF) belong to no probed list
+                const float *cl = coarse + static_cast<size_t>(lst[p]) * D;
+                const uint16_t *c = codes + static_cast<size_t>(id) * M;
+                double d = 0.0;
+                for (int j = 0; j < M; ++j) {
+                    const float *cen = cb + (static_cast<size_t>(j) * kFullSize + c[j]) * dsub;
+                    double dj = 0.0;
+                    for (int tt = 0; tt < dsub; ++tt) {
+                        const double diff = (static_cast<double>(y[j * dsub + tt]) - static_cast<double>(cl[j * dsub + tt])) -
+                                            static_cast<double>(cen[tt]);
+                        dj += diff * diff;
+                    }
+                    d += dj;
+                }
+                key = make_key(__float_as_uint(static_cast<float>(d)), id);
+            }
+        }
+        a[t] = key;
+    }
+    bitonic_sort(a, n_pow2);
+    for (uint32_t t = threadIdx.x; t < k; t += blockDim.x) {
+        const uint64_t key = a[t];
+        ids[static_cast<size_t>(q) * k + t] = static_cast<uint32_t>(key);
+        dist[static_cast<size_t>(q) * k + t] = (key == ~0ull) ? INFINITY : __uint_as_float(static_cast<uint32_t>(key >> 32));
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+struct IvfScanPlan {
+    size_t off_hist, off_thr, off_counter, off_nunits, zero_bytes, off_tie, off_units, off_keys, off_spill, total;
+};
+
+static IvfScanPlan plan_ivf_scan(int nq, uint32_t r)
+{
+    IvfScanPlan p{};
+    const size_t Q = static_cast<size_t>(nq);
+    size_t off = 0;
+    p.off_hist = off;    off = align_up(off + sizeof(uint32_t) * 256 * Q, 256);
+    p.off_thr = off;     off = align_up(off + sizeof(uint32_t) * 2 * Q, 256);
+    p.off_counter = off; off = align_up(off + sizeof(uint32_t) * Q, 256);
+    p.off_nunits = off;  off = align_up(off + sizeof(uint32_t) * Q, 256);
+    p.off_tie = off;     off = align_up(off + sizeof(uint32_t) * Q * kIvfUnitsPerQuery, 256);
+    p.zero_bytes = off;  // everything above is cleared together
+    p.off_units = off;   off = align_up(off + sizeof(IvfUnit) * Q * kIvfUnitsPerQuery, 256);
+    p.off_keys = off;    off = align_up(off + sizeof(uint64_t) * Q * r, 256);
+    p.off_spill = off;
+    if (next_pow2(r) > kSortLdsKeys) off = align_up(off + sizeof(uint64_t) * Q * next_pow2(r), 256);
+    p.total = off;
+    return p;
+}
+
+template <int M>
+static int ivf_scan_m(const uint16_t *codes, const int64_t *offsets, const int32_t *probe, int nprobe,
+                      const uint8_t *qtab, int nq, uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, uint32_t *count,
+                      uint8_t *base, hipStream_t st)
+{
+    const IvfScanPlan p = plan_ivf_scan(nq, r);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(base + p.off_hist);
+    uint32_t *thr = reinterpret_cast<uint32_t *>(base + p.off_thr);
+    uint32_t *counter = reinterpret_cast<uint32_t *>(base + p.off_counter);
+    uint32_t *nunits = reinterpret_cast<uint32_t *>(base + p.off_nunits);
+    uint32_t *tie = reinterpret_cast<uint32_t *>(base + p.off_tie);
+    IvfUnit *units = reinterpret_cast<IvfUnit *>(base + p.off_units);
+    uint64_t *keys = reinterpret_cast<uint64_t *>(base + p.off_keys);
+    uint64_t *spill = reinterpret_cast<uint64_t *>(base + p.off_spill);
+    int rc = launch_zero_words(reinterpret_cast<uint32_t *>(base), p.zero_bytes / 4, st);
+    if (rc) return rc;
+    rc = launch_fill_u64(keys, static_cast<size_t>(nq) * r, ~0ull, st);     // unused slots read as padding
+    if (rc) return rc;
+    DCPQ_LAUNCH(kStageIvf, st, ivf_plan_kernel, dim3(nq), dim3(256), 0, probe, nprobe, offsets, r, units, nunits, count);
+    DCPQ_CHECK_LAUNCH("ivf_plan_kernel");
+    const dim3 grid(kIvfUnitsPerQuery / 4, nq);
+    const size_t lds_tab = 4 * M * 256;
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
+                nunits, qtab, nprobe, r, hist, thr, tie, counter, keys);
+    DCPQ_CHECK_LAUNCH("ivf_scan_kernel<hist>");
+    rc = launch_threshold(hist, nq, r, thr, st);
+    if (rc) return rc;
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfTieCount>), grid, dim3(256), lds_tab, codes, units, nunits, qtab,
+                nprobe, r, hist, thr, tie, counter, keys);
+    DCPQ_CHECK_LAUNCH("ivf_scan_kernel<tiecount>");
+    rc = launch_tie_quota(tie, kIvfUnitsPerQuery, nq, thr, st);
+    if (rc) return rc;
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfCollect>), grid, dim3(256), lds_tab, codes, units, nunits, qtab,
+                nprobe, r, hist, thr, tie, counter, keys);
+    DCPQ_CHECK_LAUNCH("ivf_scan_kernel<collect>");
+    return launch_sort_candidates(keys, nq, r, spill, cand_id, cand_qd, st);
+}
+
+static int ivf_check_common(const char *what, int nq, int m, int dsub, int nlist, int nprobe)
+{
+    DCPQ_REQUIRE(nq >= 0, "%s: nq=%d", what, nq);
+    if (!dcpq_shape_supported(m, dsub)) return fail(DCPQ_EUNSUPPORTED, "%s: m=%d dsub=%d not supported", what, m, dsub);
+    DCPQ_REQUIRE(nlist >= 1 && nprobe >= 1 && nprobe <= nlist, "%s: needs 1 <= nprobe <= nlist (nprobe=%d nlist=%d)", what, nprobe, nlist);
+    if (nprobe > kIvfMaxProbe) return fail(DCPQ_EUNSUPPORTED, "%s: nprobe=%d above the supported %d", what, nprobe, kIvfMaxProbe);
+    return DCPQ_OK;
+}
+
+}  // namespace dcpq
+
+using namespace dcpq;
+
+extern "C" size_t dcpq_ivf_probe_workspace_bytes(int nq, int nlist)
+{
+    if (nq <= 0 || nlist <= 0) return 0;
+    return align_up(sizeof(float) * static_cast<size_t>(nq) * nlist, 256);
+}
+
+extern "C" int dcpq_ivf_probe(const float *queries, int nq, int D, const float *coarse, int nlist, int nprobe,
+                              int32_t *probe, void *workspace, size_t workspace_bytes, void *stream)
+{
+    clear_error();
+    DCPQ_REQUIRE(nq >= 0 && D >= 1, "ivf_probe: nq=%d D=%d", nq, D);
+    DCPQ_REQUIRE(nlist >= 1 && nprobe >= 1 && nprobe <= nlist, "ivf_probe: needs 1 <= nprobe <= nlist");
+    if (nprobe > kIvfMaxProbe) return fail(DCPQ_EUNSUPPORTED, "ivf_probe: nprobe=%d above the supported %d", nprobe, kIvfMaxProbe);
+    if (nq == 0) return DCPQ_OK;
+    DCPQ_REQUIRE(queries && coarse && probe && workspace, "ivf_probe: null pointer");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "ivf_probe: workspace must be 256-byte aligned");
+    const size_t need = dcpq_ivf_probe_workspace_bytes(nq, nlist);
+    if (workspace_bytes < need) return fail(DCPQ_EWORKSPACE, "ivf_probe: workspace %zu < %zu bytes", workspace_bytes, need);
+    hipStream_t st = as_stream(stream);
+    float *dist = static_cast<float *>(workspace);
+    int rc = launch_distance_tables(queries, nq, coarse, 1, D, nlist, dist, kStageIvf, st);
+    if (rc) return rc;
+    DCPQ_LAUNCH(kStageIvf, st, ivf_select_probe_kernel, dim3(nq), dim3(1024), 0, dist, nlist, nprobe, probe);
+    DCPQ_CHECK_LAUNCH("ivf_select_probe_kernel");
+    return DCPQ_OK;
+}
+
+extern "C" size_t dcpq_ivf_tables_workspace_bytes(int nq) { return nq > 0 ? align_up(sizeof(uint32_t) * static_cast<size_t>(nq), 256) : 0; }
+
+extern "C" int dcpq_ivf_build_small_tables(const float *queries, int nq, const float *coarse, int nlist,
+                                           const int32_t *probe, int nprobe, const float *derived, int m, int dsub,
+                                           const uint16_t *codes, const int64_t *offsets, uint32_t r, uint8_t *qtab,
+                                           float *bounds, void *workspace, size_t workspace_bytes, void *stream)
+{
+    clear_error();
+    int rc = ivf_check_common("ivf_build_small_tables", nq, m, dsub, nlist, nprobe);
+    if (rc) return rc;
+    DCPQ_REQUIRE(r >= 1, "ivf_build_small_tables: r=%u", r);
+    if (nq == 0) return DCPQ_OK;
+    DCPQ_REQUIRE(queries && coarse && probe && derived && codes && offsets && qtab && bounds && workspace,
+                 "ivf_build_small_tables: null pointer");
+    if (workspace_bytes < dcpq_ivf_tables_workspace_bytes(nq))
+        return fail(DCPQ_EWORKSPACE, "ivf_build_small_tables: workspace too small");
+    hipStream_t st = as_stream(stream);
+    uint32_t *qmin_bits = static_cast<uint32_t *>(workspace);
+    // +inf as the starting minimum
+    rc = launch_fill_u64(reinterpret_cast<uint64_t *>(qmin_bits), (static_cast<size_t>(nq) + 1) / 2, 0x7f8000007f800000ull, st);
+    if (rc) return rc;
+    const size_t lds = sizeof(float) * static_cast<size_t>(m) * dsub;
+    DCPQ_LAUNCH(kStageIvf, st, ivf_tables_kernel<0>, dim3(nprobe, nq), dim3(256), lds, queries, coarse, probe, nprobe,
+                derived, m, dsub, qmin_bits, bounds, qtab);
+    DCPQ_CHECK_LAUNCH("ivf_tables_kernel<min>");
+    DCPQ_LAUNCH(kStageIvf, st, ivf_qmax_kernel, dim3(nq), dim3(256), 0, queries, coarse, probe, nprobe, derived, m, dsub,
+                codes, offsets, r, qmin_bits, bounds);
+    DCPQ_CHECK_LAUNCH("ivf_qmax_kernel");
+    DCPQ_LAUNCH(kStageIvf, st, ivf_tables_kernel<1>, dim3(nprobe, nq), dim3(256), lds, queries, coarse, probe, nprobe,
+                derived, m, dsub, qmin_bits, bounds, qtab);
+    DCPQ_CHECK_LAUNCH("ivf_tables_kernel<quantize>");
+    return DCPQ_OK;
+}
+
+extern "C" size_t dcpq_ivf_scan_workspace_bytes(int nq, uint32_t r)
+{
+    if (nq <= 0 || r == 0) return 0;
+    return plan_ivf_scan(nq, r).total;
+}
+
+extern "C" int dcpq_ivf_scan_candidates(const uint16_t *codes, const int64_t *offsets, int nlist, int m,
+                                        const int32_t *probe, int nprobe, const uint8_t *qtab, int nq, uint32_t r,
+                                        uint32_t *cand_id, uint8_t *cand_qd, uint32_t *count, void *workspace,
+                                        size_t workspace_bytes, void *stream)
+{
+    clear_error();
+    int rc = ivf_check_common("ivf_scan_candidates", nq, m, 1, nlist, nprobe);
+    if (rc) return rc;
+    DCPQ_REQUIRE(r >= 1 && r <= (1u << 26), "ivf_scan_candidates: r=%u out of range", r);
+    if (nq == 0) return DCPQ_OK;
+    DCPQ_REQUIRE(codes && offsets && probe && qtab && cand_id && cand_qd && count && workspace, "ivf_scan_candidates: null pointer");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "ivf_scan_candidates: workspace must be 256-byte aligned");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(qtab) & 15) == 0, "ivf_scan_candidates: qtab must be 16-byte aligned");
+    if (workspace_bytes < dcpq_ivf_scan_workspace_bytes(nq, r))
+        return fail(DCPQ_EWORKSPACE, "ivf_scan_candidates: workspace %zu < %zu bytes", workspace_bytes, dcpq_ivf_scan_workspace_bytes(nq, r));
+    hipStream_t st = as_stream(stream);
+    uint8_t *base = static_cast<uint8_t *>(workspace);
+    switch (m) {
+        case 1: return ivf_scan_m<1>(codes, offsets, probe, nprobe, qtab, nq, r, cand_id, cand_qd, count, base, st);
+        case 2: return ivf_scan_m<2>(codes, offsets, probe, nprobe, qtab, nq, r, cand_id, cand_qd, count, base, st);
+        case 4: return ivf_scan_m<4>(codes, offsets, probe, nprobe, qtab, nq, r, cand_id, cand_qd, count, base, st);
+        case 8: return ivf_scan_m<8>(codes, offsets, probe, nprobe, qtab, nq, r, cand_id, cand_qd, count, base, st);
+        case 16: return ivf_scan_m<16>(codes, offsets, probe, nprobe, qtab, nq, r, cand_id, cand_qd, count, base, st);
+        case 32: return ivf_scan_m<32>(codes, offsets, probe, nprobe, qtab, nq, r, cand_id, cand_qd, count, base, st);
+        default: return fail(DCPQ_EUNSUPPORTED, "m=%d not supported", m);
+    }
+}
+
+extern "C" size_t dcpq_ivf_refine_workspace_bytes(int nq, uint32_t r)
+{
+    if (nq <= 0 || r == 0) return 0;
+    const uint32_t np2 = next_pow2(r);
+    return np2 <= kSortLdsKeys ? 0 : sizeof(uint64_t) * static_cast<size_t>(nq) * np2;
+}
+
+extern "C" int dcpq_ivf_refine_topk(const float *queries, const float *coarse, int nlist, const float *codebooks, int m,
+                                    int dsub, const uint16_t *codes, const int64_t *offsets, const int32_t *probe,
+                                    int nprobe, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
+                                    float *dist, void *workspace, size_t workspace_bytes, void *stream)
+{
+    clear_error();
+    int rc = ivf_check_common("ivf_refine_topk", nq, m, dsub, nlist, nprobe);
+    if (rc) return rc;
+    DCPQ_REQUIRE(k >= 1 && k <= r, "ivf_refine_topk: needs 1 <= k <= r (k=%u r=%u)", k, r);
+    if (nq == 0) return DCPQ_OK;
+    DCPQ_REQUIRE(queries && coarse && codebooks && codes && offsets && probe && cand_id && ids && dist, "ivf_refine_topk: null pointer");
+    const size_t need = dcpq_ivf_refine_workspace_bytes(nq, r);
+    if (need && (!workspace || workspace_bytes < need)) return fail(DCPQ_EWORKSPACE, "ivf_refine_topk: workspace too small");
+    hipStream_t st = as_stream(stream);
+    const uint32_t np2 = next_pow2(r);
+    const int use_lds = np2 <= kSortLdsKeys;
+    const size_t lds = use_lds ? sizeof(uint64_t) * np2 : 0;
+    uint64_t *spill = static_cast<uint64_t *>(workspace);
+#define DCPQ_LAUNCH_IVF_REFINE(MV)                                                                                   \
+    case MV:                                                                                                         \
+        DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&ivf_refine_kernel<MV>),                  \
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,                              \
+                                           static_cast<int>(sizeof(uint64_t) * kSortLdsKeys)));                      \
+        DCPQ_LAUNCH(kStageIvf, st, ivf_refine_kernel<MV>, dim3(nq), dim3(1024), lds, queries, coarse, codebooks, dsub, \
+                    codes, offsets, probe, nprobe, cand_id, r, k, np2, use_lds, spill, ids, dist);                   \
+        break;
+    switch (m) {
+        DCPQ_LAUNCH_IVF_REFINE(1) DCPQ_LAUNCH_IVF_REFINE(2) DCPQ_LAUNCH_IVF_REFINE(4) DCPQ_LAUNCH_IVF_REFINE(8)
+        DCPQ_LAUNCH_IVF_REFINE(16) DCPQ_LAUNCH_IVF_REFINE(32)
+        default: return fail(DCPQ_EUNSUPPORTED, "m=%d not supported", m);
+    }
+#undef DCPQ_LAUNCH_IVF_REFINE
+    DCPQ_CHECK_LAUNCH("ivf_refine_kernel");
+    return DCPQ_OK;
+}

@@ -191,6 +191,8 @@ __global__ __launch_bounds__(256) void threshold_kernel(const uint32_t *__restri
     }
     const uint32_t before = b ? cum[b - 1] : 0u;
     if (before < r && cum[b] >= r) { thr[2 * q] = b; thr[2 * q + 1] = r - before; }
+    // fewer than r codes in all (inverted lists only): bucket "256" takes everything
+    if (b == 255 && cum[255] < r) { thr[2 * q] = 256; thr[2 * q + 1] = 0; }
 }
 
 // Turns per-unit counts of bucket T into per-unit quotas: units are in id order, so unit u may
@@ -257,6 +259,53 @@ __global__ void zero_words_kernel(uint32_t *p, size_t n)
 {
     const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0u;
+}
+
+__global__ void fill_u64_kernel(uint64_t *p, size_t n, uint64_t v)
+{
+    const size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+int launch_zero_words(uint32_t *p, size_t nwords, hipStream_t st)
+{
+    if (!nwords) return DCPQ_OK;
+    DCPQ_LAUNCH(kStageMisc, st, zero_words_kernel, dim3((nwords + 255) / 256), dim3(256), 0, p, nwords);
+    DCPQ_CHECK_LAUNCH("zero_words_kernel");
+    return DCPQ_OK;
+}
+
+int launch_fill_u64(uint64_t *p, size_t n, uint64_t v, hipStream_t st)
+{
+    if (!n) return DCPQ_OK;
+    DCPQ_LAUNCH(kStageMisc, st, fill_u64_kernel, dim3((n + 255) / 256), dim3(256), 0, p, n, v);
+    DCPQ_CHECK_LAUNCH("fill_u64_kernel");
+    return DCPQ_OK;
+}
+
+int launch_threshold(const uint32_t *hist, int nq, uint32_t r, uint32_t *thr, hipStream_t st)
+{
+    DCPQ_LAUNCH(kStageSelect, st, threshold_kernel, dim3(nq), dim3(256), 0, hist, r, nullptr, thr);
+    DCPQ_CHECK_LAUNCH("threshold_kernel");
+    return DCPQ_OK;
+}
+
+int launch_tie_quota(uint32_t *tie, uint32_t nunits, int nq, const uint32_t *thr, hipStream_t st)
+{
+    DCPQ_LAUNCH(kStageSelect, st, tie_quota_kernel, dim3(nq), dim3(256), 0, tie, nunits, nullptr, thr);
+    DCPQ_CHECK_LAUNCH("tie_quota_kernel");
+    return DCPQ_OK;
+}
+
+int launch_sort_candidates(const uint64_t *keys, int nq, uint32_t r, uint64_t *spill, uint32_t *cand_id,
+                           uint8_t *cand_qd, hipStream_t st)
+{
+    const uint32_t np2 = next_pow2(r);
+    const bool use_spill = np2 > kSortLdsKeys;
+    DCPQ_LAUNCH(kStageSelect, st, sort_candidates_kernel, dim3(nq), dim3(1024), use_spill ? 0 : sizeof(uint64_t) * np2,
+                keys, r, np2, use_spill ? 0 : 1, spill, nullptr, nullptr, cand_id, cand_qd);
+    DCPQ_CHECK_LAUNCH("sort_candidates_kernel");
+    return DCPQ_OK;
 }
 
 constexpr int scan_qt(int m) { return m <= 8 ? 16 : 128 / m; }   // tables of a tile: <= 32 KiB of LDS

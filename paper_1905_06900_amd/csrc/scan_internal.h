@@ -61,6 +61,14 @@ int launch_scan_fast(const uint16_t *codes, uint64_t n_codes, int m, const uint8
                      uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, uint8_t *base, const ScanPlan &p,
                      hipStream_t st);
 
+// Small shared steps of the three-pass selection, reused by the inverted-list variant.
+int launch_zero_words(uint32_t *p, size_t nwords, hipStream_t st);
+int launch_fill_u64(uint64_t *p, size_t n, uint64_t v, hipStream_t st);
+int launch_threshold(const uint32_t *hist, int nq, uint32_t r, uint32_t *thr, hipStream_t st);
+int launch_tie_quota(uint32_t *tie, uint32_t nunits, int nq, const uint32_t *thr, hipStream_t st);
+int launch_sort_candidates(const uint64_t *keys, int nq, uint32_t r, uint64_t *spill, uint32_t *cand_id,
+                           uint8_t *cand_qd, hipStream_t st);
+
 #ifdef __HIPCC__
 // In-place bitonic sort of n_pow2 64-bit keys by one workgroup (array in LDS or global memory).
 __device__ inline void bitonic_sort(uint64_t *a, uint32_t n_pow2)

@@ -21,9 +21,11 @@ constexpr int kTileC = 256;    // centroids per workgroup (4 wavefronts x 64)
 // Centroid columns are interleaved so that a lane ends up with 4 consecutive centroids of one
 // query row: column c of column-tile nt is centroid c * 4 + nt of the wavefront's 64, which
 // turns the stores into 16-byte vectors, 256 contiguous bytes per 16 lanes.
+// ncent = centroids per sub-quantizer (65536 for the product quantizer; any count for the coarse
+// quantizer of the inverted index, which is the same computation with m = 1 and dsub = D).
 __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restrict__ queries, int nq,
                                                           const float *__restrict__ cb, int m, int dsub,
-                                                          float *__restrict__ tables)
+                                                          int ncent, float *__restrict__ tables)
 {
     __shared__ double ny[kTileQ];
     __shared__ double nc[kTileC];
@@ -32,12 +34,14 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
     const int q0 = blockIdx.y * kTileQ;
     const int c0 = blockIdx.x * kTileC;
     const int D = m * dsub;
-    const float *cbj = cb + static_cast<size_t>(j) * kFullSize * dsub;
+    const float *cbj = cb + static_cast<size_t>(j) * ncent * dsub;
 
     {   // squared norms in fp64: one centroid per thread, one query per thread of wave 0
-        const float *c = cbj + static_cast<size_t>(c0 + tid) * dsub;
         double s = 0.0;
-        for (int t = 0; t < dsub; ++t) { const double v = c[t]; s += v * v; }
+        if (c0 + tid < ncent) {
+            const float *c = cbj + static_cast<size_t>(c0 + tid) * dsub;
+            for (int t = 0; t < dsub; ++t) { const double v = c[t]; s += v * v; }
+        }
         nc[tid] = s;
         if (tid < kTileQ) {
             double sy = 0.0;
@@ -69,7 +73,7 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
             const int c = cw + lr * 4 + nt;
-            b[nt] = kin ? static_cast<double>(cbj[static_cast<size_t>(c) * dsub + k]) : 0.0;
+            b[nt] = (kin && c < ncent) ? static_cast<double>(cbj[static_cast<size_t>(c) * dsub + k]) : 0.0;
         }
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt)
@@ -94,20 +98,32 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
             o.y = static_cast<float>(fmax(0.0, (yy + n1) - 2.0 * acc[mt][1][v]));
             o.z = static_cast<float>(fmax(0.0, (yy + n2) - 2.0 * acc[mt][2][v]));
             o.w = static_cast<float>(fmax(0.0, (yy + n3) - 2.0 * acc[mt][3][v]));
-            float *dst = tables + (static_cast<size_t>(q) * m + j) * kFullSize + c0 + cl;
-            *reinterpret_cast<float4 *>(dst) = o;
+            float *dst = tables + (static_cast<size_t>(q) * m + j) * ncent + c0 + cl;
+            if (c0 + cl + 3 < ncent && (ncent & 3) == 0) {
+                *reinterpret_cast<float4 *>(dst) = o;
+            } else {
+                const float ov[4] = {o.x, o.y, o.z, o.w};
+                for (int z = 0; z < 4; ++z)
+                    if (c0 + cl + z < ncent) dst[z] = ov[z];
+            }
         }
     }
+}
+
+int launch_distance_tables(const float *queries, int nq, const float *codebooks, int m, int dsub, int ncent,
+                           float *tables, int stage, hipStream_t st)
+{
+    if (nq == 0) return DCPQ_OK;
+    const dim3 grid((ncent + kTileC - 1) / kTileC, (nq + kTileQ - 1) / kTileQ, m);
+    DCPQ_LAUNCH(stage, st, full_tables_kernel, grid, dim3(256), 0, queries, nq, codebooks, m, dsub, ncent, tables);
+    DCPQ_CHECK_LAUNCH("full_tables_kernel");
+    return DCPQ_OK;
 }
 
 int launch_full_tables(const float *queries, int nq, const float *codebooks, int m, int dsub,
                        float *tables, hipStream_t st)
 {
-    if (nq == 0) return DCPQ_OK;
-    const dim3 grid(kFullSize / kTileC, (nq + kTileQ - 1) / kTileQ, m);
-    DCPQ_LAUNCH(kStageFullTables, st, full_tables_kernel, grid, dim3(256), 0, queries, nq, codebooks, m, dsub, tables);
-    DCPQ_CHECK_LAUNCH("full_tables_kernel");
-    return DCPQ_OK;
+    return launch_distance_tables(queries, nq, codebooks, m, dsub, kFullSize, tables, kStageFullTables, st);
 }
 
 }  // namespace dcpq
