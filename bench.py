@@ -29,6 +29,8 @@ def main() -> int:
     ap.add_argument("--q", type=int, default=None, help="override query batch (experiments only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--chunk", type=int, default=0, help="queries per chunk of the fused search (0 = default)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one 1 GiB calibration_copy_kernel (for scaling rocprofv3 --pmc traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -60,6 +62,13 @@ def main() -> int:
     def step():
         binding.search(queries, cb, derived, codes, w.r, w.k, args.chunk, ws, ids, dist)
 
+    if args.calibration_copy:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        b = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        a.zero_()
+        binding.profile_copy(a, b)
+        torch.cuda.synchronize()
+        del a, b
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -87,9 +96,18 @@ def main() -> int:
     avg_launch_s = dom_ms / dom_launches * 1e-3
     achieved = bytes_per_launch / avg_launch_s / 1e9
     scan_ms = sum(stages.get(s, (0.0, 0))[0] for s in SCAN_STAGES) / args.steps
+    # HBM-side bytes per launch of that kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    # WRITE_SIZE scaled by the calibration copy); only meaningful for the workload it was taken on.
+    traffic = None
+    prof = os.path.join(ROOT, "profiles", "scan_fast_cfg2_counters.txt")
+    if dom == "scan_fast" and args.cfg == 2 and args.n is None and args.q is None and args.chunk == 0 and os.path.exists(prof):
+        import re
+        mt = re.search(r"measured traffic below the L2 = .*?\((\d+) bytes\)", open(prof).read())
+        if mt:
+            traffic = int(mt.group(1))
     roofline = {
         "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
         "bytes_per_launch": bytes_per_launch, "avg_launch_ms": round(dom_ms / dom_launches, 4),
         "launches_per_step": launches_per_step, "queries_per_pass": qt,
         "code_passes_per_step": passes_per_step,

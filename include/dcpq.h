@@ -211,6 +211,10 @@ int dcpq_profile_enable(int on);
 int dcpq_profile_stage_count(void);
 const char *dcpq_profile_stage_name(int stage);
 int dcpq_profile_read(int stage, double *total_ms, uint64_t *launches);
+/* Plain device-to-device copy of `bytes` (multiple of 16) by a kernel named
+ * calibration_copy_kernel: reads `bytes`, writes `bytes`.  Hardware traffic counters collected for
+ * the search kernels are scaled by what the same counters report for this copy of known size. */
+int dcpq_profile_copy(const void *src, void *dst, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -55,6 +55,7 @@ _SIGNATURES = {
     "dcpq_profile_stage_count": (_i, []),
     "dcpq_profile_stage_name": (C.c_char_p, [_i]),
     "dcpq_profile_read": (_i, [_i, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]),
+    "dcpq_profile_copy": (_i, [_vp, _vp, _sz, _vp]),
     "dcpq_search": (_i, [_vp, _i, _vp, _vp, _i, _i, _vp, _u64, _u32, _u32, _vp, _vp, _i, _vp, _sz, _vp]),
 }
 
@@ -300,3 +301,9 @@ def ivf_refine_topk(queries, coarse, codebooks, codes, offsets, probe, cand_id, 
         _dev(cand_id, torch.uint32, "cand_id"), nq, r, k, ids.data_ptr(), dist.data_ptr(), ws.data_ptr(),
         ws.numel(), _stream()))
     return ids, dist
+
+
+def profile_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    """Calibration copy kernel of known size (for scaling hardware traffic counters)."""
+    assert src.numel() * src.element_size() == dst.numel() * dst.element_size()
+    _check(lib().dcpq_profile_copy(src.data_ptr(), dst.data_ptr(), src.numel() * src.element_size(), _stream()))

@@ -77,6 +77,26 @@ extern "C" int dcpq_profile_enable(int on)
     return DCPQ_OK;
 }
 
+// Plain device-to-device copy of known size: the yardstick the HBM traffic counters are scaled by.
+__global__ __launch_bounds__(256) void calibration_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n)
+{
+    for (size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x; i < n;
+         i += static_cast<size_t>(gridDim.x) * blockDim.x)
+        dst[i] = src[i];
+}
+
+extern "C" int dcpq_profile_copy(const void *src, void *dst, size_t bytes, void *stream)
+{
+    clear_error();
+    DCPQ_REQUIRE(src && dst && bytes % 16 == 0, "profile_copy: needs non-null pointers and a multiple of 16 bytes");
+    DCPQ_REQUIRE(((reinterpret_cast<uintptr_t>(src) | reinterpret_cast<uintptr_t>(dst)) & 15) == 0, "profile_copy: 16-byte alignment");
+    if (bytes == 0) return DCPQ_OK;
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(8192), dim3(256), 0, as_stream(stream),
+                       static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), bytes / 16);
+    DCPQ_CHECK_LAUNCH("calibration_copy_kernel");
+    return DCPQ_OK;
+}
+
 extern "C" int dcpq_profile_stage_count(void) { return kNumStages; }
 
 extern "C" const char *dcpq_profile_stage_name(int stage)
