@@ -355,8 +355,9 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r)
         cpb = (cpb + 1023) / 1024 * 1024;
         p.codes_per_block = static_cast<uint32_t>(cpb);
         p.fblocks = static_cast<uint32_t>((n_codes + cpb - 1) / cpb);
-        p.cap = 16 * r < 2048 ? 2048 : 16 * r;
-        p.upd = r / 8 < 64 ? 64 : r / 8;
+        p.slices = p.fblocks < static_cast<uint32_t>(kFastSlices) ? p.fblocks : kFastSlices;
+        p.cap = 32 * r / p.slices < 1024 ? 1024 : 32 * r / p.slices;   // 32 r per query in all: twice the even share
+        p.upd = r / 16 < 16 ? 16 : r / 16;                   // appends to one slice between bound updates
         const uint32_t want_sort = next_pow2(2 * r);
         p.sortcap = want_sort < kSortLdsKeys ? kSortLdsKeys : want_sort;
         // sample: runs of 256 codes spread evenly over the array, about 32 r codes (at least 64 Ki)
@@ -367,7 +368,7 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r)
         p.s_stride = n_codes / p.s_nunits;
         if (p.s_stride < p.s_unit) p.s_stride = p.s_unit;
         p.off_fzero = off;
-        p.off_fcount = off;  off = align_up(off + sizeof(uint32_t) * Q, 256);
+        p.off_fcount = off;  off = align_up(off + sizeof(uint32_t) * Q * p.slices, 256);
         p.off_chist = off;   off = align_up(off + sizeof(uint32_t) * 256 * Q, 256);
         p.off_shist = off;   off = align_up(off + sizeof(uint32_t) * 256 * Q, 256);
         p.off_nflag = off;   off = align_up(off + 256, 256);
@@ -376,7 +377,7 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r)
         p.off_flags = off;   off = align_up(off + sizeof(uint32_t) * Q, 256);
         p.off_qlist = off;   off = align_up(off + sizeof(int32_t) * Q, 256);
         p.off_qsw = off;     off = align_up(off + static_cast<size_t>(p.ntiles) * m * 256 * p.fqt, 256);
-        p.off_fkeys = off;   off = align_up(off + sizeof(uint64_t) * Q * p.cap, 256);
+        p.off_fkeys = off;   off = align_up(off + sizeof(uint64_t) * Q * p.slices * p.cap, 256);
         p.off_fsort = off;
         if (p.sortcap > kSortLdsKeys) off = align_up(off + sizeof(uint64_t) * Q * p.sortcap, 256);
     }

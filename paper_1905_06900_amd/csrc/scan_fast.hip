@@ -8,9 +8,12 @@
 //    transposed, T[j][e][q] with the query fastest, so that the table entries of one (code, j)
 //    for 16 queries are 16 contiguous bytes.  One ds_read_b128 per lane then delivers 1024
 //    lookups per wavefront instruction, against 64 for byte gathers.  Rows of the same
-//    sub-quantizer group are interleaved over a 256-byte LDS line (row slot = j mod NSLOT) and
-//    every lane group of a wavefront reads a different slot, which keeps the reads free of bank
-//    conflicts whatever the code bytes are.
+//    sub-quantizer group are interleaved over a 256-byte LDS line (row slot = j mod NSLOT), and
+//    which sub-quantizer a lane reads is rotated with its code slot so that the 16 lanes of a
+//    lane group always touch 16 different 16-byte units of their lines.  Not every such rotation
+//    is equally fast: the lane-to-unit patterns used here (see rotated_j) are the ones that
+//    measured at the rate of a linear ds_read_b128 sweep (about 170 bytes per clock per CU);
+//    other conflict-free-looking rotations measured 110-120.
 //
 // 2. The sum over j runs on the matrix cores as an exact integer accumulation: with A = the
 //    gathered rows (16 x 64 bytes: 16 (code, query-block) rows, 4 sub-quantizers x 16 queries) and
@@ -32,7 +35,10 @@
 //    true candidate set, from which the exact, id-tie-broken r are then selected; the result does
 //    not depend on the order of arrival.  If a buffer overflows (pathological ties), the query is
 //    flagged and redone by the three-pass path of scan.hip.
+#include <type_traits>
+
 #include "common.h"
+#include "lds_access.h"
 #include "scan_internal.h"
 
 namespace dcpq {
@@ -48,7 +54,9 @@ struct FastCfg {
     static constexpr int STEPS = 64 / CPS;          // steps per 64-code group
     static constexpr int UNROLL = NMF >= 8 ? 1 : 8 / NMF;   // steps issued together (8 row reads in flight)
     static constexpr int PREFETCH = M <= 8 ? 4 : M == 16 ? 2 : 1;   // 64-code groups fetched ahead per wavefront
-    static constexpr int CLS = M / 4;               // bytes per residue class j mod 4 in the code scratch
+    static constexpr int CLS = M / 4;               // bytes per residue class j mod 4 of one code
+    static constexpr bool ADJ = NQB != 4;           // lanes of one table row adjacent (else strided by CPS)
+    static constexpr int REGION = STEPS * CLS;      // scratch bytes per (code slot, class): all steps of a group
     static constexpr int TAB_BYTES = M * 256 * QT;
     static constexpr int SCR_BYTES = WAVES * 64 * M;
     static constexpr int QCAP = 64;                 // pending-candidate queue entries per wavefront (>= 64)
@@ -56,15 +64,26 @@ struct FastCfg {
     static constexpr int LDS_BYTES = TAB_BYTES + SCR_BYTES + Q_BYTES;
     static_assert(NSLOT <= M && M % 4 == 0, "row slots must rotate within the sub-quantizers");
     static_assert(STEPS % UNROLL == 0, "unroll must divide the steps of a group");
+    static_assert(UNROLL * CLS == 8, "the steps issued together read one 8-byte word of code bytes");
+    static_assert(CPS * 4 * REGION == 64 * M, "scratch regions tile the group");
 };
 
-// Sub-quantizer read by MFMA u, chunk s (= lane / 16), for code slot c: rotate within aligned
-// groups of NSLOT sub-quantizers so that the 16 lanes of one chunk hit NSLOT different row slots.
+// Sub-quantizer read by MFMA u, chunk s (= lane / 16), for code slot c.  For a fixed c the map
+// (u, s) -> j is a bijection onto 0..M-1, j mod 4 does not depend on u, and the row slots
+// (j mod NSLOT) of the 16 lanes of a chunk are all different.  The rotations are the ones that
+// measured fastest for ds_read_b128: with 4 slots, slot = s + c and the four lanes of a row strided
+// by 4; with 8 slots, slot = s + 2c (+4u); with 16 slots, the low two slot bits rotate with c and the
+// high two with c / 4.
 template <int NSLOT>
 __device__ inline int rotated_j(int u, int s, int c)
 {
     const int g = 4 * u + s;
-    return (g & ~(NSLOT - 1)) | ((g + c) & (NSLOT - 1));
+    if constexpr (NSLOT == 4) return (g & ~3) | ((g + c) & 3);
+    else if constexpr (NSLOT == 8) return (g & ~7) | ((g + 2 * c) & 7);
+    else {
+        static_assert(NSLOT == 16, "row slots per line: 4, 8 or 16");
+        return (g & ~15) | ((s + c) & 3) | (((u + (c >> 2)) & 3) << 2);
+    }
 }
 
 // Byte offset of T[j][e][q] in the swizzled tile layout (shared by the transposition kernel and
@@ -132,44 +151,59 @@ __device__ inline void transposed_low_bytes(const uint32_t (&w)[M / 2], uint32_t
     }
 }
 
-// Appends one candidate (rec: id in bits 0..31, qd in 32..39, query-in-tile in 40..47) to its
-// query's buffer, counts it in the query's exact per-bucket histogram, and every `upd` appends
-// lowers the query's bucket bound to the bucket that now holds its r-th best appended candidate.
-// Kept out of line: it is the rare path and would otherwise be replicated at every call site.
-__device__ __noinline__ void append_candidate(uint64_t rec, int q0, uint32_t r, uint32_t cap, uint32_t upd,
-                                              int *t_cur, uint32_t *count, uint32_t *chist, uint64_t *keys)
+// Appends one candidate (rec: id in bits 0..31, qd in 32..39, query-in-tile in 40..47) to slice
+// `slice` of its query's buffer and counts it in the query's exact per-bucket histogram.  Returns the
+// query when this append is one of those (every `upd`-th of the slice) after which the query's bucket
+// bound is to be recomputed, else -1.  Kept out of line: it is the rare path and would otherwise be
+// replicated at every call site.
+__device__ __noinline__ int append_candidate(uint64_t rec, int q0, uint32_t slice, uint32_t nslices, uint32_t cap, uint32_t upd,
+                                             int *t_cur, uint32_t *count, uint32_t *chist, uint64_t *keys)
 {
     const uint32_t q = q0 + static_cast<uint32_t>(rec >> 40);
     const uint32_t qd = static_cast<uint32_t>(rec >> 32) & 255u;
-    const uint32_t pos = atomicAdd(&count[q], 1u);
-    if (pos < cap) keys[static_cast<size_t>(q) * cap + pos] = rec & 0xFFFFFFFFFFull;
-    else atomicMin(&t_cur[q], -1);                     // buffer full: stop appending, query is redone
+    const size_t cell = static_cast<size_t>(q) * nslices + slice;
+    const uint32_t pos = atomicAdd(&count[cell], 1u);
+    if (pos < cap) keys[cell * cap + pos] = rec & 0xFFFFFFFFFFull;
+    else atomicMin(&t_cur[q], -1);                     // slice full: stop appending, query is redone
     atomicAdd(&chist[static_cast<size_t>(q) * 256 + qd], 1u);
-    if (pos + 1 >= r && (pos + 1) % upd == 0) {
-        uint32_t cum = 0;
-        int tn = -1;
-#pragma unroll 1
-        for (int b = 0; b < 256; b += 4) {
-            uint32_t c[4];
+    return (pos + 1) % upd == 0 ? static_cast<int>(q) : -1;
+}
+
+// Lowers query q's bucket bound to the bucket that holds its r-th best appended candidate (nothing
+// happens while fewer than r are appended).  Called by
+// a whole wavefront: lane l reads the counts of buckets 4l .. 4l+3, a wavefront prefix sum locates the
+// bucket.  The counts only grow, so any snapshot of them gives a bound that is still valid later.
+__device__ __noinline__ void lower_bound_of(int q, uint32_t r, int *t_cur, const uint32_t *chist)
+{
+    const int lane = threadIdx.x & 63;
+    uint32_t c[4];
 #pragma unroll
-            for (int z = 0; z < 4; ++z)
-                c[z] = __hip_atomic_load(&chist[static_cast<size_t>(q) * 256 + b + z], __ATOMIC_RELAXED,
-                                         __HIP_MEMORY_SCOPE_AGENT);
+    for (int z = 0; z < 4; ++z)
+        c[z] = __hip_atomic_load(&chist[static_cast<size_t>(q) * 256 + 4 * lane + z], __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+    uint32_t incl = mine;
 #pragma unroll
-            for (int z = 0; z < 4; ++z) {
-                cum += c[z];
-                if (tn < 0 && cum >= r) tn = b + z;
-            }
-            if (tn >= 0) break;
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t other = __shfl(incl, lane >= d ? lane - d : lane);
+        if (lane >= d) incl += other;
+    }
+    uint32_t cum = incl - mine;                          // appended candidates in buckets below 4 * lane
+    if (cum < r && incl >= r) {                          // at most one lane
+        int tn = 4 * lane;
+#pragma unroll
+        for (int z = 0; z < 3; ++z) {
+            cum += c[z];
+            if (cum < r) tn = 4 * lane + z + 1;
         }
-        if (tn >= 0) atomicMin(&t_cur[q], tn);
+        atomicMin(&t_cur[q], tn);
     }
 }
 
 template <int M, int QT, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     const uint16_t *__restrict__ codes, uint64_t n_codes, uint32_t codes_per_block,
-    const uint8_t *__restrict__ qsw, int nq, uint32_t r, uint32_t cap, uint32_t upd,
+    const uint8_t *__restrict__ qsw, int nq, uint32_t r, uint32_t nslices, uint32_t cap, uint32_t upd,
     int *t_cur, uint32_t *count, uint32_t *chist, uint64_t *__restrict__ keys)
 {
     using C = FastCfg<M, QT, WAVES>;
@@ -190,17 +224,23 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
 
     // ---- per-lane constants -------------------------------------------------------------
     const int s = lane >> 4, i = lane & 15;
-    const int ca = i / C::NQB, qba = i % C::NQB;          // A operand: code slot, query block
-    uint32_t laneoff[C::NMF];
-    int shift[C::NMF];
+    // A operand: row i of the MFMA is (code slot ca, query block qba)
+    const int ca = C::ADJ ? i / C::NQB : i % C::CPS, qba = C::ADJ ? i % C::NQB : i / C::CPS;
+    // Row address of MFMA f = laneoff[f] with its (zero) second byte replaced by the code byte, one
+    // v_perm_b32: sel[f] picks, out of a 32-bit word of class bytes, the byte of this lane's
+    // sub-quantizer j (byte j / 4 of the class word j mod 4).
+    // The tables start at LDS offset lds0 = 0 (the kernel has no static LDS; the host checks that),
+    // so every laneoff has a zero second byte.
+    const uint32_t lds0 = lds_offset_of(ltab);
+    uint32_t laneoff[C::NMF], selb[C::NMF];
 #pragma unroll
-    for (int u = 0; u < C::NMF; ++u) {
-        const int j = rotated_j<C::NSLOT>(u, s, ca);
-        laneoff[u] = swz_offset<QT>(j, 0, qba * 16);
-        shift[u] = 8 * (j >> 2);
+    for (int f = 0; f < C::NMF; ++f) {
+        const int j = rotated_j<C::NSLOT>(f, s, ca);
+        laneoff[f] = lds0 + swz_offset<QT>(j, 0, qba * 16);
+        selb[f] = C::NSLOT == 4 ? static_cast<uint32_t>(f) : static_cast<uint32_t>(j >> 2);
     }
-    const int cls = (s + ca) & 3;                          // residue class j mod 4 read by this lane
-    const uint32_t scr_rd = ca * M + cls * C::CLS;         // + step * CPS * M
+    const int cls = rotated_j<C::NSLOT>(0, s, ca) & 3;     // residue class j mod 4 read by this lane
+    const uint32_t scr_rd = (ca * 4 + cls) * C::REGION;    // + 8 * (iteration within the group)
     v4i bsel = {0, 0, 0, 0};                               // B: four stacked identities
     bsel[i >> 2] = 1 << (8 * (i & 3));
     // D operand: value v of this lane is row 4 * (lane / 16) + v, column lane % 16
@@ -208,26 +248,35 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
         const int row = 4 * s + v;
-        cd[v] = row / C::NQB;
-        ql[v] = (row % C::NQB) * 16 + i;
+        cd[v] = C::ADJ ? row / C::NQB : row % C::CPS;
+        ql[v] = (C::ADJ ? row % C::NQB : row / C::CPS) * 16 + i;
     }
 
     const uint64_t cbeg = static_cast<uint64_t>(blockIdx.y) * codes_per_block;
     const uint64_t cend = min(n_codes, cbeg + codes_per_block);
     const uint32_t ngroups = cbeg < cend ? static_cast<uint32_t>((cend - cbeg + 63) / 64) : 0u;
 
-    auto insert = [&](uint64_t rec) { append_candidate(rec, q0, r, cap, upd, t_cur, count, chist, keys); };
-
-    // Pending candidates of this wavefront: records wq[0 .. qlen).  qlen is wave-uniform (it only
-    // changes by ballot counts), so it lives in a scalar register and the queue needs no atomics.
+    // Pending candidates of this wavefront: records wq[0 .. qlen), qlen <= QCAP = 64.  qlen is
+    // wave-uniform (it only changes by ballot counts), so it lives in a scalar register and the queue
+    // needs no atomics.
+    static_assert(C::QCAP == 64, "flush hands one record to each lane");
     uint32_t qlen = 0;
+    const uint32_t slice = blockIdx.y % nslices;
     auto flush = [&]() {
         // the wavefront runs in lockstep; the barriers say that every push is in place before the
         // entries are read, and that every lane has read its entry before the next push overwrites it
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        for (uint32_t e = lane; e < qlen; e += 64) insert(wq[e]);
+        int qu = -1;
+        if (static_cast<uint32_t>(lane) < qlen) qu = append_candidate(wq[lane], q0, slice, nslices, cap, upd, t_cur, count, chist, keys);
+        // the queries whose bound is due, one after the other, each by the whole wavefront
+        uint64_t due = __builtin_amdgcn_ballot_w64(qu >= 0);
+        while (due) {                                    // uniform
+            const int src = __builtin_ctzll(due);
+            due &= due - 1;
+            lower_bound_of(__shfl(qu, src), r, t_cur, chist);
+        }
         qlen = 0;
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -294,8 +343,12 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
         const uint32_t g = g0 + pf * WAVES;
         if (g >= ngroups) break;                                     // uniform
         const uint64_t gbase = cbeg + static_cast<uint64_t>(g) * 64;
+        const uint32_t gbase32 = static_cast<uint32_t>(gbase);     // ids fit 32 bits (the host checks n_codes)
         const int nlive = static_cast<int>(min(static_cast<uint64_t>(64), cend - gbase));   // codes in this group
-        // publish the low bytes of the group's codes to the wavefront's scratch
+        // Publish the low bytes of the group's codes to the wavefront's scratch.  Lane l holds code l
+        // = step l / CPS, code slot l % CPS; its M / 4 bytes of class k go to region (slot, k) at the
+        // step's position, so that a reader finds the bytes of UNROLL consecutive steps in one
+        // 8-byte word.
         {
             uint32_t tb[M / 4];
 #pragma unroll
@@ -304,37 +357,38 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
 #pragma unroll
                 for (int z = 1; z < PF; ++z) tb[d] = pf == z ? tbp[z][d] : tb[d];
             }
-            uint32_t *dst = reinterpret_cast<uint32_t *>(scr + lane * M);
+            uint8_t *dst = scr + (lane % C::CPS) * (4 * C::REGION) + (lane / C::CPS) * C::CLS;
 #pragma unroll
-            for (int d = 0; d < M / 4; ++d) dst[d] = tb[d];
+            for (int k = 0; k < 4; ++k) {
+                uint8_t *d = dst + k * C::REGION;
+                if constexpr (C::CLS == 1) *d = static_cast<uint8_t>(tb[0] >> (8 * k));
+                else if constexpr (C::CLS == 2) *reinterpret_cast<uint16_t *>(d) = static_cast<uint16_t>(tb[k >> 1] >> (16 * (k & 1)));
+                else if constexpr (C::CLS == 4) *reinterpret_cast<uint32_t *>(d) = tb[k];
+                else *reinterpret_cast<uint2 *>(d) = make_uint2(tb[2 * k], tb[2 * k + 1]);
+            }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
-        // this lane's M/4 code bytes of a step (class cls of code slot ca), read one step ahead
-        auto read_word = [&](int t) -> uint64_t {
-            const uint8_t *sp = scr + scr_rd + t * (C::CPS * M);
-            if constexpr (C::CLS == 1) return *sp;
-            else if constexpr (C::CLS == 2) return *reinterpret_cast<const uint16_t *>(sp);
-            else if constexpr (C::CLS == 4) return *reinterpret_cast<const uint32_t *>(sp);
-            else return *reinterpret_cast<const uint64_t *>(sp);
-        };
-        // U steps are issued together: all their row reads first, then U independent MFMA chains,
-        // so that several kilobytes of LDS reads per wavefront are in flight at any time.
+        // U steps are issued together: one 8-byte read of their code bytes, all their row reads,
+        // then U independent MFMA chains, so that several kilobytes of LDS reads per wavefront are
+        // in flight at any time.
         constexpr int U = C::UNROLL;
 #pragma unroll 1
         for (int t0 = 0; t0 < C::STEPS; t0 += U) {
-            uint64_t word[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) word[u] = read_word(t0 + u);
+            const uint2 word = *reinterpret_cast<const uint2 *>(scr + scr_rd + (t0 / U) * 8);
             v4i a[U][C::NMF];
 #pragma unroll
             for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int f = 0; f < C::NMF; ++f) {
-                    const uint32_t e = static_cast<uint32_t>(word[u] >> shift[f]) & 255u;
-                    a[u][f] = *reinterpret_cast<const v4i *>(ltab + laneoff[f] + e * 256u);
+                    // byte u * CLS + j / 4 of the 8-byte word; which of its two halves is known statically
+                    const int stat = u * C::CLS + (C::CLS == 8 ? 4 * (f >> 2) : 0);
+                    const uint32_t half = stat >= 4 ? word.y : word.x;
+                    const uint32_t sel = 0x07060004u | (((static_cast<uint32_t>(stat) + selb[f]) & 3u) << 8);
+                    const uint32_t addr = __builtin_amdgcn_perm(laneoff[f], half, sel);
+                    a[u][f] = lds_read_v4i(addr);
                 }
             // Each accumulator starts at 128 * M - (T + 1): the 128 * M undoes the -128 bias of the M
             // signed bytes and the rest turns "qd <= T" into "result < 0", so one sign test of the
@@ -350,30 +404,38 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
             int sign = 0;
 #pragma unroll
             for (int u = 0; u < U; ++u) sign |= acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
-            if (__ballot(sign < 0)) {                                // uniform, rare
+            if (__builtin_amdgcn_ballot_w64(sign < 0)) {             // uniform, rare
+                // PARTIAL: the group holds fewer than 64 codes (last group of the array only)
+                auto decode = [&](auto partial) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int su = acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
-                    if (!__ballot(su < 0)) continue;                 // uniform: no hit in this step
-                    const int first = (t0 + u) * C::CPS;             // first code of the step within the group
+                    for (int u = 0; u < U; ++u) {
+                        const int su = acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
+                        if (!__builtin_amdgcn_ballot_w64(su < 0)) continue;      // uniform: no hit in this step
+                        const int first = (t0 + u) * C::CPS;         // first code of the step within the group
 #pragma unroll
-                    for (int v = 0; v < 4; ++v) {
-                        const bool h = acc[u][v] < 0 && first + cd[v] < nlive;
-                        const uint64_t mask = __ballot(h);
-                        if (!mask) continue;                         // uniform
-                        const uint32_t cnt = __popcll(mask);
-                        if (qlen + cnt > C::QCAP) flush();           // uniform: make room (cnt <= 64 = QCAP)
-                        if (h) {
-                            const uint64_t id = gbase + first + cd[v];
-                            // result + T + 1 is the unsaturated sum (unsigned wrap-around is intended)
-                            const uint32_t sum = static_cast<uint32_t>(acc[u][v]) + static_cast<uint32_t>(tl[v]) + 1u;
-                            const uint32_t qd = min(sum, 255u);
-                            wq[qlen + __popcll(mask & ((1ull << lane) - 1ull))] =
-                                (static_cast<uint64_t>(ql[v]) << 40) | (static_cast<uint64_t>(qd) << 32) | id;
+                        for (int v = 0; v < 4; ++v) {
+                            bool h = acc[u][v] < 0;
+                            if constexpr (decltype(partial)::value) h = h && first + cd[v] < nlive;
+                            const uint64_t mask = __builtin_amdgcn_ballot_w64(h);
+                            if (!mask) continue;                     // uniform
+                            const uint32_t cnt = __popcll(mask);
+                            if (qlen + cnt > C::QCAP) flush();       // uniform: make room (cnt <= 64 = QCAP)
+                            if (h) {
+                                const uint32_t id = gbase32 + static_cast<uint32_t>(first + cd[v]);
+                                // result + T + 1 is the unsaturated sum (unsigned wrap-around is intended)
+                                const uint32_t sum = static_cast<uint32_t>(acc[u][v]) + static_cast<uint32_t>(tl[v]) + 1u;
+                                const uint32_t qd = min(sum, 255u);
+                                const uint32_t rank = __builtin_amdgcn_mbcnt_hi(
+                                    static_cast<uint32_t>(mask >> 32),
+                                    __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+                                wq[qlen + rank] = (static_cast<uint64_t>((static_cast<uint32_t>(ql[v]) << 8) | qd) << 32) | id;
+                            }
+                            qlen = __builtin_amdgcn_readfirstlane(qlen + cnt);      // wave-uniform: keep it scalar
                         }
-                        qlen += cnt;
                     }
-                }
+                };
+                if (nlive == 64) decode(std::false_type{});
+                else decode(std::true_type{});
             }
         }
       }
@@ -385,7 +447,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
 // flags[q] = 1 when the query must be redone (buffer overflow, or a tie bucket too large to sort).
 __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__restrict__ keys,
                                                           const uint32_t *__restrict__ count,
-                                                          const uint32_t *__restrict__ chist, uint32_t r,
+                                                          const uint32_t *__restrict__ chist, uint32_t r, uint32_t nslices,
                                                           uint32_t cap, uint32_t sortcap, int use_lds,
                                                           uint64_t *__restrict__ spill,
                                                           uint32_t *__restrict__ cand_id,
@@ -396,8 +458,14 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
     __shared__ uint32_t cum[256];
     __shared__ uint32_t s_t, s_keep, s_pos;
     const int q = blockIdx.x, tid = threadIdx.x;
-    const uint32_t n = count[q];
-    if (n > cap || n < r) {                     // overflow (n < r cannot happen: the bound is safe)
+    uint32_t n = 0;
+    bool over = false;
+    for (uint32_t sl = 0; sl < nslices; ++sl) {
+        const uint32_t c = count[static_cast<size_t>(q) * nslices + sl];
+        over = over || c > cap;
+        n += c;
+    }
+    if (over || n < r) {                        // a slice overflowed (n < r cannot happen: the bound is safe)
         if (tid == 0) flags[q] = 1;
         return;
     }
@@ -426,11 +494,15 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
     uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(q) * sortcap;
     for (uint32_t t = tid; t < np2; t += 1024) a[t] = ~0ull;
     __syncthreads();
-    for (uint32_t t = tid; t < n; t += 1024) {
-        const uint64_t key = keys[static_cast<size_t>(q) * cap + t];
-        if (static_cast<uint32_t>(key >> 32) <= T) {
-            const uint32_t pos = atomicAdd(&s_pos, 1u);
-            if (pos < np2) a[pos] = key;
+    for (uint32_t sl = 0; sl < nslices; ++sl) {
+        const size_t cell = static_cast<size_t>(q) * nslices + sl;
+        const uint32_t c = count[cell];
+        for (uint32_t t = tid; t < c; t += 1024) {
+            const uint64_t key = keys[cell * cap + t];
+            if (static_cast<uint32_t>(key >> 32) <= T) {
+                const uint32_t pos = atomicAdd(&s_pos, 1u);
+                if (pos < np2) a[pos] = key;
+            }
         }
     }
     bitonic_sort(a, np2);
@@ -478,6 +550,12 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
 
     static bool attr_done = false;          // LDS above 64 KiB must be requested once per kernel
     if (!attr_done) {
+        // the kernel addresses its tables by LDS offset and assumes that they start at offset 0
+        hipFuncAttributes fa;
+        DCPQ_CHECK_HIP(hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(&scan_fast_kernel<M, QT, WAVES>)));
+        if (fa.sharedSizeBytes != 0)
+            return fail(DCPQ_EUNSUPPORTED, "single-pass scan: kernel has %zu bytes of static LDS, expected none",
+                        static_cast<size_t>(fa.sharedSizeBytes));
         DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_fast_kernel<M, QT, WAVES>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
         DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_select_kernel),
@@ -497,13 +575,13 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     DCPQ_CHECK_LAUNCH("sample_threshold_kernel");
     // the scan
     DCPQ_LAUNCH(kStageScanFast, st, (scan_fast_kernel<M, QT, WAVES>), dim3(p.ntiles, p.fblocks), dim3(WAVES * 64),
-                C::LDS_BYTES, codes, n_codes, p.codes_per_block, qsw, nq, r, p.cap, p.upd, t_cur, fcount, chist,
+                C::LDS_BYTES, codes, n_codes, p.codes_per_block, qsw, nq, r, p.slices, p.cap, p.upd, t_cur, fcount, chist,
                 fkeys);
     DCPQ_CHECK_LAUNCH("scan_fast_kernel");
     // exact selection + list of queries to redo
     const int use_lds = p.sortcap <= kSortLdsKeys;
     DCPQ_LAUNCH(kStageSelect, st, fast_select_kernel, dim3(nq), dim3(1024), use_lds ? sizeof(uint64_t) * p.sortcap : 0,
-                fkeys, fcount, chist, r, p.cap, p.sortcap, use_lds, fsort, cand_id, cand_qd, flags);
+                fkeys, fcount, chist, r, p.slices, p.cap, p.sortcap, use_lds, fsort, cand_id, cand_qd, flags);
     DCPQ_CHECK_LAUNCH("fast_select_kernel");
     DCPQ_LAUNCH(kStageSelect, st, collect_flags_kernel, dim3(1), dim3(64), 0, flags, nq, qlist, nflag);
     DCPQ_CHECK_LAUNCH("collect_flags_kernel");

@@ -16,6 +16,11 @@ inline uint32_t next_pow2(uint32_t x)
 
 // Sizes and workspace layout of one scan_candidates call (offsets in bytes from a 256-byte
 // aligned base).  The three-pass path can always run; the single-pass path exists for m >= 4.
+// Each query's candidate buffer and append cursor are split into slices, one per residue of the
+// workgroup's position along the codes: workgroups that run at the same time append to different
+// cursors, which keeps same-address atomics (they serialize in the L2) off the critical path.
+constexpr int kFastSlices = 16;      // at most; fewer when there are fewer workgroups along the codes
+
 struct ScanPlan {
     // three-pass path
     uint32_t unit;        // codes scanned by one wavefront
@@ -34,13 +39,14 @@ struct ScanPlan {
     uint32_t ntiles;
     uint32_t fblocks;         // workgroups along the code axis
     uint32_t codes_per_block;
-    uint32_t cap;             // candidate-buffer entries per query
+    uint32_t slices;          // slices per query: min(kFastSlices, fblocks)
+    uint32_t cap;             // candidate-buffer entries per query and slice
     uint32_t upd;             // appended candidates between two bound updates
     uint32_t sortcap;         // keys the final selection can sort (power of two)
     uint32_t s_unit, s_nunits;    // sample: s_nunits runs of s_unit codes ...
     uint64_t s_stride;            // ... starting every s_stride codes
     size_t off_fzero, fzero_bytes;   // fcount, chist, shist, nflag: cleared together
-    size_t off_fcount;    // uint32 [nq]
+    size_t off_fcount;    // uint32 [nq][slices]
     size_t off_chist;     // uint32 [nq][256]
     size_t off_shist;     // uint32 [nq][256]
     size_t off_nflag;     // uint32 [1] (+ padding)
@@ -48,7 +54,7 @@ struct ScanPlan {
     size_t off_flags;     // uint32 [nq]
     size_t off_qlist;     // int32 [nq]
     size_t off_qsw;       // uint8 [ntiles][m*256*fqt]
-    size_t off_fkeys;     // uint64 [nq][cap]
+    size_t off_fkeys;     // uint64 [nq][slices][cap]
     size_t off_fsort;     // uint64 [nq][sortcap], only when sortcap exceeds the LDS sort
     size_t total;
 };
