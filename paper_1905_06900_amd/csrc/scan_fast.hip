@@ -209,7 +209,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     using C = FastCfg<M, QT, WAVES>;
     extern __shared__ __align__(16) uint8_t smem[];
     uint8_t *ltab = smem;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: keep it (and what derives from it) scalar
     uint8_t *scr = smem + C::TAB_BYTES + wave * (64 * M);
     uint64_t *wq = reinterpret_cast<uint64_t *>(smem + C::TAB_BYTES + C::SCR_BYTES) + wave * C::QCAP;
 
