@@ -97,7 +97,8 @@ int dcpq_build_tables(const float *queries, int nq, const float *codebooks, int 
  * Requires 1 <= r <= n_codes < 2^32.
  * ------------------------------------------------------------------------------------------- */
 size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r);
-/* Queries that share one pass over the codes inside the scan kernels (their tables sit in LDS). */
+/* Queries that share one pass over the codes inside the scan kernels for a large batch (their tables
+ * sit in LDS). */
 int dcpq_scan_query_tile(int m);
 int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                          uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
@@ -106,9 +107,17 @@ int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int m, const u
  *   DCPQ_SCAN_AUTO        single pass over the codes with a running bucket bound (the paper's
  *                         capped-buckets upper bound); queries whose candidate buffer overflows are
  *                         redone by the three-pass algorithm.  m = 1, 2 always use three passes.
- *   DCPQ_SCAN_THREE_PASS  histogram pass, tie-count pass, collect pass: exact for any input. */
+ *   DCPQ_SCAN_THREE_PASS  histogram pass, tie-count pass, collect pass: exact for any input.
+ *   DCPQ_SCAN_TILE16/32/64  the single pass with tiles of 16, 32 or 64 queries sharing one pass over the
+ *                         codes (AUTO takes the largest tile the kernel has for m, and for m = 8 the
+ *                         smallest of 16, 32, 64 that holds the whole batch); DCPQ_EUNSUPPORTED when the
+ *                         kernel does not exist for (m, tile).  Tiles: m = 4: 64; m = 8: 16, 32, 64;
+ *                         m = 16: 32; m = 32: 16. */
 #define DCPQ_SCAN_AUTO 0
 #define DCPQ_SCAN_THREE_PASS 1
+#define DCPQ_SCAN_TILE16 2
+#define DCPQ_SCAN_TILE32 3
+#define DCPQ_SCAN_TILE64 4
 int dcpq_scan_candidates_mode(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                               uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
                               size_t workspace_bytes, int mode, void *stream);

@@ -153,7 +153,7 @@ def search_chunk(m: int, nq: int, chunk_queries: int = 0) -> int:
     return int(lib().dcpq_search_chunk(m, nq, chunk_queries))
 
 
-SCAN_AUTO, SCAN_THREE_PASS = 0, 1
+SCAN_AUTO, SCAN_THREE_PASS, SCAN_TILE16, SCAN_TILE32, SCAN_TILE64 = 0, 1, 2, 3, 4
 
 
 def scan_candidates(codes: torch.Tensor, qtab: torch.Tensor, r: int, workspace: torch.Tensor | None = None,

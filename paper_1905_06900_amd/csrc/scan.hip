@@ -310,17 +310,25 @@ int launch_sort_candidates(const uint64_t *keys, int nq, uint32_t r, uint64_t *s
 
 constexpr int scan_qt(int m) { return m <= 8 ? 16 : 128 / m; }   // tables of a tile: <= 32 KiB of LDS
 
-int fast_query_tile(int m)
+// Queries per tile of the single-pass kernel.  Large batches take the largest tile (most queries per
+// byte of code stream); for m = 8 a batch that fits a smaller tile takes that one, so that a small
+// batch does not pay for absent queries and the scan runs at the speed of the code stream.
+int fast_query_tile(int m, int nq, int mode)
 {
+    if (mode == DCPQ_SCAN_TILE16 || mode == DCPQ_SCAN_TILE32 || mode == DCPQ_SCAN_TILE64) {
+        const int qt = mode == DCPQ_SCAN_TILE16 ? 16 : mode == DCPQ_SCAN_TILE32 ? 32 : 64;
+        return fast_table_bytes(m, qt) ? qt : 0;
+    }
     switch (m) {
-        case 4: case 8: return 64;
+        case 4: return 64;
+        case 8: return nq <= 16 ? 16 : nq <= 32 ? 32 : 64;
         case 16: return 32;
         case 32: return 16;
         default: return 0;
     }
 }
 
-ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r)
+ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode)
 {
     ScanPlan p{};
     p.qt = scan_qt(m);
@@ -342,7 +350,7 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r)
     p.off_spill = off;   // sort area in global memory, only when r keys do not fit the LDS sort
     if (np2 > kSortLdsKeys) off = align_up(off + sizeof(uint64_t) * Q * np2, 256);
 
-    p.fqt = static_cast<uint32_t>(fast_query_tile(m));
+    p.fqt = static_cast<uint32_t>(mode == DCPQ_SCAN_THREE_PASS ? 0 : fast_query_tile(m, nq, mode));
     p.fast = p.fqt != 0;
     if (p.fast) {
         p.ntiles = static_cast<uint32_t>((Q + p.fqt - 1) / p.fqt);
@@ -376,7 +384,7 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r)
         p.off_tcur = off;    off = align_up(off + sizeof(int32_t) * Q, 256);
         p.off_flags = off;   off = align_up(off + sizeof(uint32_t) * Q, 256);
         p.off_qlist = off;   off = align_up(off + sizeof(int32_t) * Q, 256);
-        p.off_qsw = off;     off = align_up(off + static_cast<size_t>(p.ntiles) * m * 256 * p.fqt, 256);
+        p.off_qsw = off;     off = align_up(off + static_cast<size_t>(p.ntiles) * fast_table_bytes(m, p.fqt), 256);
         p.off_fkeys = off;   off = align_up(off + sizeof(uint64_t) * Q * p.slices * p.cap, 256);
         p.off_fsort = off;
         if (p.sortcap > kSortLdsKeys) off = align_up(off + sizeof(uint64_t) * Q * p.sortcap, 256);
@@ -467,9 +475,9 @@ template <int M>
 static int launch_scan_m(const uint16_t *codes, uint64_t n_codes, const uint8_t *qtab, int nq, uint32_t r,
                          uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st)
 {
-    const ScanPlan p = plan_scan(n_codes, M, nq, r);
+    const ScanPlan p = plan_scan(n_codes, M, nq, r, mode);
     uint8_t *base = static_cast<uint8_t *>(ws);
-    if (!p.fast || mode == DCPQ_SCAN_THREE_PASS)
+    if (!p.fast)
         return launch_three_pass<M>(codes, n_codes, qtab, nq, nullptr, nullptr, r, cand_id, cand_qd, base, p, st);
 
     const size_t nwords = p.fzero_bytes / sizeof(uint32_t);
@@ -506,14 +514,21 @@ using namespace dcpq;
 extern "C" int dcpq_scan_query_tile(int m)
 {
     if (!m_supported(m)) return 0;
-    const int f = fast_query_tile(m);
+    const int f = fast_query_tile(m, 1 << 30, DCPQ_SCAN_AUTO);
     return f ? f : scan_qt(m);
 }
 
 extern "C" size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r)
 {
     if (nq <= 0 || !m_supported(m) || n_codes == 0 || r == 0) return 0;
-    return plan_scan(n_codes, m, nq, r).total;
+    // enough for every algorithm the caller may ask for
+    size_t most = 0;
+    const int modes[] = {DCPQ_SCAN_AUTO, DCPQ_SCAN_THREE_PASS, DCPQ_SCAN_TILE16, DCPQ_SCAN_TILE32, DCPQ_SCAN_TILE64};
+    for (int mode : modes) {
+        const size_t t = plan_scan(n_codes, m, nq, r, mode).total;
+        most = t > most ? t : most;
+    }
+    return most;
 }
 
 static int scan_checked(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
@@ -522,8 +537,12 @@ static int scan_checked(const uint16_t *codes, uint64_t n_codes, int m, const ui
 {
     clear_error();
     DCPQ_REQUIRE(nq >= 0, "scan_candidates: nq=%d", nq);
-    DCPQ_REQUIRE(mode == DCPQ_SCAN_AUTO || mode == DCPQ_SCAN_THREE_PASS, "scan_candidates: mode=%d", mode);
+    DCPQ_REQUIRE(mode == DCPQ_SCAN_AUTO || mode == DCPQ_SCAN_THREE_PASS || mode == DCPQ_SCAN_TILE16 ||
+                     mode == DCPQ_SCAN_TILE32 || mode == DCPQ_SCAN_TILE64,
+                 "scan_candidates: mode=%d", mode);
     if (!m_supported(m)) return fail(DCPQ_EUNSUPPORTED, "scan_candidates: m=%d not supported", m);
+    if (mode >= DCPQ_SCAN_TILE16 && fast_query_tile(m, nq, mode) == 0)
+        return fail(DCPQ_EUNSUPPORTED, "scan_candidates: no single-pass kernel for m=%d with the tile of mode %d", m, mode);
     DCPQ_REQUIRE(n_codes >= 1 && n_codes < (1ull << 32), "scan_candidates: n_codes=%llu must be in [1, 2^32)",
                  static_cast<unsigned long long>(n_codes));
     DCPQ_REQUIRE(r >= 1 && r <= n_codes, "scan_candidates: r=%u must be in [1, n_codes]", r);

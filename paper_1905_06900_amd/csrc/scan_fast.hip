@@ -57,20 +57,26 @@ struct FastCfg {
     static constexpr int CLS = M / 4;               // bytes per residue class j mod 4 of one code
     static constexpr bool ADJ = NQB != 4;           // lanes of one table row adjacent (else strided by CPS)
     static constexpr int REGION = STEPS * CLS;      // scratch bytes per (code slot, class): all steps of a group
-    static constexpr int TAB_BYTES = M * 256 * QT;
+    // Table rows per code value: when a line has more row slots than there are sub-quantizers the
+    // tables are stored NSLOT / M times, so that every lane still finds its row in the slot its
+    // position in the wavefront asks for.
+    static constexpr int VJ = NSLOT > M ? NSLOT : M;
+    static constexpr int TAB_BYTES = VJ * 256 * QT;
     static constexpr int SCR_BYTES = WAVES * 64 * M;
     static constexpr int QCAP = 64;                 // pending-candidate queue entries per wavefront (>= 64)
     static constexpr int Q_BYTES = WAVES * QCAP * 8;
     static constexpr int LDS_BYTES = TAB_BYTES + SCR_BYTES + Q_BYTES;
-    static_assert(NSLOT <= M && M % 4 == 0, "row slots must rotate within the sub-quantizers");
+    static_assert(M % 4 == 0 && VJ % M == 0, "row slots rotate within the (possibly repeated) sub-quantizers");
+    static_assert(LDS_BYTES <= 160 * 1024, "one workgroup must fit the LDS of a CU");
     static_assert(STEPS % UNROLL == 0, "unroll must divide the steps of a group");
     static_assert(UNROLL * CLS == 8, "the steps issued together read one 8-byte word of code bytes");
     static_assert(CPS * 4 * REGION == 64 * M, "scratch regions tile the group");
 };
 
-// Sub-quantizer read by MFMA u, chunk s (= lane / 16), for code slot c.  For a fixed c the map
-// (u, s) -> j is a bijection onto 0..M-1, j mod 4 does not depend on u, and the row slots
-// (j mod NSLOT) of the 16 lanes of a chunk are all different.  The rotations are the ones that
+// Table row set jv read by MFMA u, chunk s (= lane / 16), for code slot c; the sub-quantizer is
+// j = jv mod M (row sets M and above are the repeated copies).  For a fixed c the map (u, s) -> j is
+// a bijection onto 0..M-1, j mod 4 does not depend on u, and the row slots (jv mod NSLOT) of the 16
+// lanes of a chunk are all different.  The rotations are the ones that
 // measured fastest for ds_read_b128: with 4 slots, slot = s + c and the four lanes of a row strided
 // by 4; with 8 slots, slot = s + 2c (+4u); with 16 slots, the low two slot bits rotate with c and the
 // high two with c / 4.
@@ -95,17 +101,18 @@ __host__ __device__ inline uint32_t swz_offset(int j, int e, int q)
     return (static_cast<uint32_t>(j / NSLOT) * 256u + e) * 256u + (j % NSLOT) * QT + q;
 }
 
-// qtab [nq][M][256] -> per-tile swizzled tables [ntiles][M*256*QT], each byte stored as x - 128
+// qtab [nq][M][256] -> per-tile swizzled tables [ntiles][VJ*256*QT], each byte stored as x - 128
 // (x ^ 0x80) for the signed matrix instruction; absent queries read 255.
 template <int M, int QT>
 __global__ __launch_bounds__(256) void swizzle_tables_kernel(const uint8_t *__restrict__ qtab, int nq,
                                                              uint8_t *__restrict__ out)
 {
     const int tile = blockIdx.y;
-    const int idx = blockIdx.x * 256 + threadIdx.x;      // (j, e, qb)
+    const int idx = blockIdx.x * 256 + threadIdx.x;      // (jv, e, qb)
     constexpr int NQB = QT / 16;
-    if (idx >= M * 256 * NQB) return;
-    const int qb = idx % NQB, e = (idx / NQB) % 256, j = idx / (NQB * 256);
+    constexpr int VJ = 256 / QT > M ? 256 / QT : M;      // row sets, repeated copies included
+    if (idx >= VJ * 256 * NQB) return;
+    const int qb = idx % NQB, e = (idx / NQB) % 256, jv = idx / (NQB * 256), j = jv % M;
     uint32_t w[4] = {0, 0, 0, 0};
 #pragma unroll
     for (int t = 0; t < 16; ++t) {
@@ -113,7 +120,7 @@ __global__ __launch_bounds__(256) void swizzle_tables_kernel(const uint8_t *__re
         const uint32_t v = q < nq ? qtab[(static_cast<size_t>(q) * M + j) * 256 + e] : 255u;
         w[t >> 2] |= (v ^ 0x80u) << (8 * (t & 3));
     }
-    uint8_t *dst = out + static_cast<size_t>(tile) * (M * 256 * QT) + swz_offset<QT>(j, e, qb * 16);
+    uint8_t *dst = out + static_cast<size_t>(tile) * (VJ * 256 * QT) + swz_offset<QT>(jv, e, qb * 16);
     *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
@@ -236,9 +243,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     uint32_t laneoff[C::NMF], selb[C::NMF];
 #pragma unroll
     for (int f = 0; f < C::NMF; ++f) {
-        const int j = rotated_j<C::NSLOT>(f, s, ca);
-        laneoff[f] = lds0 + swz_offset<QT>(j, 0, qba * 16);
-        selb[f] = C::NSLOT == 4 ? static_cast<uint32_t>(f) : static_cast<uint32_t>(j >> 2);
+        const int jv = rotated_j<C::NSLOT>(f, s, ca);
+        laneoff[f] = lds0 + swz_offset<QT>(jv, 0, qba * 16);
+        selb[f] = C::NSLOT == 4 ? static_cast<uint32_t>(f) : static_cast<uint32_t>((jv % M) >> 2);
     }
     const int cls = rotated_j<C::NSLOT>(0, s, ca) & 3;     // residue class j mod 4 read by this lane
     const uint32_t scr_rd = (ca * 4 + cls) * C::REGION;    // + 8 * (iteration within the group)
@@ -566,7 +573,7 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     }
 
     // swizzled tables
-    DCPQ_LAUNCH(kStageMisc, st, (swizzle_tables_kernel<M, QT>), dim3((M * 256 * C::NQB + 255) / 256, p.ntiles),
+    DCPQ_LAUNCH(kStageMisc, st, (swizzle_tables_kernel<M, QT>), dim3((C::VJ * 256 * C::NQB + 255) / 256, p.ntiles),
                 dim3(256), 0, qtab, nq, qsw);
     DCPQ_CHECK_LAUNCH("swizzle_tables_kernel");
     // sample histogram -> starting bounds
@@ -589,13 +596,16 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     return DCPQ_OK;
 }
 
-int fast_lds_bytes(int m)
+// Bytes of swizzled tables per query tile, 0 when the single-pass kernel does not exist for (m, qt).
+size_t fast_table_bytes(int m, int qt)
 {
-    switch (m) {
-        case 4: return FastCfg<4, 64, 16>::LDS_BYTES;
-        case 8: return FastCfg<8, 64, 16>::LDS_BYTES;
-        case 16: return FastCfg<16, 32, 16>::LDS_BYTES;
-        case 32: return FastCfg<32, 16, 8>::LDS_BYTES;
+    switch (m * 1000 + qt) {
+        case 4064: return FastCfg<4, 64, 16>::TAB_BYTES;
+        case 8064: return FastCfg<8, 64, 16>::TAB_BYTES;
+        case 8032: return FastCfg<8, 32, 16>::TAB_BYTES;
+        case 8016: return FastCfg<8, 16, 16>::TAB_BYTES;
+        case 16032: return FastCfg<16, 32, 16>::TAB_BYTES;
+        case 32016: return FastCfg<32, 16, 8>::TAB_BYTES;
         default: return 0;
     }
 }
@@ -603,12 +613,14 @@ int fast_lds_bytes(int m)
 int launch_scan_fast(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
                      uint32_t *cand_id, uint8_t *cand_qd, uint8_t *base, const ScanPlan &p, hipStream_t st)
 {
-    switch (m) {
-        case 4: return launch_fast_t<4, 64, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
-        case 8: return launch_fast_t<8, 64, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
-        case 16: return launch_fast_t<16, 32, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
-        case 32: return launch_fast_t<32, 16, 8>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
-        default: return fail(DCPQ_EUNSUPPORTED, "single-pass scan: m=%d not supported", m);
+    switch (m * 1000 + static_cast<int>(p.fqt)) {
+        case 4064: return launch_fast_t<4, 64, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 8064: return launch_fast_t<8, 64, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 8032: return launch_fast_t<8, 32, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 8016: return launch_fast_t<8, 16, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 16032: return launch_fast_t<16, 32, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 32016: return launch_fast_t<32, 16, 8>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        default: return fail(DCPQ_EUNSUPPORTED, "single-pass scan: m=%d with tiles of %u queries not supported", m, p.fqt);
     }
 }
 

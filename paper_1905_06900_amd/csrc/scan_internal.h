@@ -53,14 +53,16 @@ struct ScanPlan {
     size_t off_tcur;      // int32 [nq]
     size_t off_flags;     // uint32 [nq]
     size_t off_qlist;     // int32 [nq]
-    size_t off_qsw;       // uint8 [ntiles][m*256*fqt]
+    size_t off_qsw;       // uint8 [ntiles][fast_table_bytes(m, fqt)]
     size_t off_fkeys;     // uint64 [nq][slices][cap]
     size_t off_fsort;     // uint64 [nq][sortcap], only when sortcap exceeds the LDS sort
     size_t total;
 };
-ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r);
+// mode: DCPQ_SCAN_AUTO picks the single-pass query tile from the batch size; DCPQ_SCAN_TILE16/32/64 force it
+ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode = 0);
 
-int fast_query_tile(int m);   // 0 when the single-pass path does not exist for this m
+int fast_query_tile(int m, int nq, int mode);   // 0 when the single-pass path does not exist for this m (and tile)
+size_t fast_table_bytes(int m, int qt);
 int launch_sample_hist(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                        uint32_t r, uint32_t *shist, const ScanPlan &p, hipStream_t st);
 int launch_scan_fast(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,

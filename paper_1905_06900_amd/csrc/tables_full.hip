@@ -12,7 +12,7 @@ namespace dcpq {
 
 typedef double double4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kTileQ = 64;     // queries per workgroup   (4 row tiles of 16)
+constexpr int kTileQ = 32;     // queries per workgroup   (2 row tiles of 16)
 constexpr int kTileC = 256;    // centroids per workgroup (4 wavefronts x 64)
 
 // MFMA operand/result layout (16x16x4, fp64), lane l = 0..63:
@@ -53,9 +53,10 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
         }
     }
 
-    double4_t acc[4][4];
+    constexpr int MT = kTileQ / 16;
+    double4_t acc[MT][4];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt)
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = double4_t{0.0, 0.0, 0.0, 0.0};
 
@@ -64,9 +65,9 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
     for (int k0 = 0; k0 < dsub; k0 += 4) {
         const int k = k0 + lk;
         const bool kin = k < dsub;
-        double a[4], b[4];
+        double a[MT], b[4];
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
+        for (int mt = 0; mt < MT; ++mt) {
             const int q = q0 + mt * 16 + lr;
             a[mt] = (kin && q < nq) ? static_cast<double>(queries[static_cast<size_t>(q) * D + j * dsub + k]) : 0.0;
         }
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
             b[nt] = (kin && c < ncent) ? static_cast<double>(cbj[static_cast<size_t>(c) * dsub + k]) : 0.0;
         }
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
                 acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
@@ -86,7 +87,7 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
     const int cl = wave * 64 + lr * 4;                 // this lane's 4 centroids within the tile
     const double n0 = nc[cl], n1 = nc[cl + 1], n2 = nc[cl + 2], n3 = nc[cl + 3];
 #pragma unroll
-    for (int mt = 0; mt < 4; ++mt) {
+    for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
             const int ql = mt * 16 + v * 4 + lk;

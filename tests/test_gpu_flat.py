@@ -82,7 +82,7 @@ def test_sift_recipe_scaled_with_encoded_codes():
 # ------------------------------------------------------------------------------------------------
 # edge cases of the scan / select
 # ------------------------------------------------------------------------------------------------
-def scan_vs_oracle(codes_np, qtab_np, r):
+def scan_vs_oracle(codes_np, qtab_np, r, modes=(binding.SCAN_AUTO, binding.SCAN_THREE_PASS)):
     """Both scan algorithms (single pass with redo, and three-pass) against the oracle."""
     codes = torch.from_numpy(codes_np.view(np.int16)).to(DEV).view(torch.uint16)
     qtab = torch.from_numpy(qtab_np).to(DEV)
@@ -90,7 +90,7 @@ def scan_vs_oracle(codes_np, qtab_np, r):
     for q in range(qtab_np.shape[0]):
         qd = oracle.adc_low_bits(codes_np, qtab_np[q])
         want.append(oracle.select(qd, r))
-    for mode in (binding.SCAN_AUTO, binding.SCAN_THREE_PASS):
+    for mode in modes:
         cid, cqd = binding.scan_candidates(codes, qtab, r, mode=mode)
         torch.cuda.synchronize()
         cid, cqd = to_np(cid), to_np(cqd)
@@ -107,6 +107,20 @@ def test_scan_every_supported_m(m):
     qtab = rng.integers(0, 256 // m + 8, size=(Q, m, 256)).astype(np.uint8)
     print("scan m=%d N=%d" % (m, N), flush=True)
     scan_vs_oracle(codes, qtab, r)
+
+
+@pytest.mark.parametrize("Q", [1, 16, 17, 37, 70])
+def test_scan_every_query_tile_size(Q):
+    """m = 8 has single-pass kernels for tiles of 16, 32 and 64 queries (the smaller tiles keep repeated
+    copies of the tables in LDS); each must give the oracle's candidates for full, ragged and absent
+    tiles.  AUTO picks the tile from the batch size."""
+    rng = np.random.default_rng(1000 + Q)
+    N, r = 90_003, 500
+    codes = rng.integers(0, 65536, size=(N, 8)).astype(np.uint16)
+    qtab = rng.integers(0, 40, size=(Q, 8, 256)).astype(np.uint8)
+    print("scan tiles Q=%d" % Q, flush=True)
+    scan_vs_oracle(codes, qtab, r, modes=(binding.SCAN_TILE16, binding.SCAN_TILE32, binding.SCAN_TILE64,
+                                          binding.SCAN_AUTO))
 
 
 @pytest.mark.parametrize("N,r", [(1, 1), (63, 63), (64, 1), (65, 65), (1000, 1000), (5000, 4097), (20000, 9000)])
@@ -177,6 +191,11 @@ def test_argument_errors_are_reported_not_launched():
     qtab3 = torch.zeros((2, 3, 256), dtype=torch.uint8, device=DEV)
     with pytest.raises(binding.DcpqError) as e:
         binding.scan_candidates(codes3, qtab3, 10)            # m = 3 not built
+    assert e.value.code == binding.EUNSUPPORTED
+    codes4 = torch.zeros((100, 4), dtype=torch.int16, device=DEV).view(torch.uint16)
+    qtab4 = torch.zeros((2, 4, 256), dtype=torch.uint8, device=DEV)
+    with pytest.raises(binding.DcpqError) as e:
+        binding.scan_candidates(codes4, qtab4, 10, mode=binding.SCAN_TILE16)   # no 16-query tile for m = 4
     assert e.value.code == binding.EUNSUPPORTED
     tables = torch.zeros((2, 8, 65536), dtype=torch.float32, device=DEV)
     cand = torch.zeros((2, 10), dtype=torch.int32, device=DEV).view(torch.uint32)
