@@ -354,18 +354,44 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode)
     p.fast = p.fqt != 0;
     if (p.fast) {
         p.ntiles = static_cast<uint32_t>((Q + p.fqt - 1) / p.fqt);
-        // workgroups along the codes: about 8 rounds of the 256 CUs in total, at least 16 Ki codes each
+        // Every wavefront starts from the bound of the sample and only sees lower bounds a few groups
+        // later, so the more wavefronts start at once, the more candidates above the final bound get
+        // appended.  A first launch with at most 16 workgroups per tile therefore scans a small head of
+        // the array (1/64 of it, at least 256 Ki codes) and leaves a bound that is already tight for
+        // the main launch, whose thousands of wavefronts would otherwise each repeat that start-up.
+        p.warm_codes = 0;
+        if (n_codes >= (1ull << 22)) {
+            uint64_t w = n_codes / 64;
+            if (w < (1ull << 18)) w = 1ull << 18;
+            p.warm_blocks = 16;
+            uint64_t wc = (w + p.warm_blocks - 1) / p.warm_blocks;
+            wc = (wc + 1023) / 1024 * 1024;
+            p.warm_codes_per_block = static_cast<uint32_t>(wc);
+            p.warm_codes = wc * p.warm_blocks;
+        }
+        // main launch: workgroups along the codes, about 8 rounds of the 256 CUs in total, at least 16 Ki codes each
+        const uint64_t rest = n_codes - p.warm_codes;
         const uint64_t want = (2048 + p.ntiles - 1) / p.ntiles;
-        const uint64_t most = (n_codes + 16383) / 16384;
+        const uint64_t most = (rest + 16383) / 16384;
         uint64_t fb = want < most ? want : most;
         if (fb < 1) fb = 1;
-        uint64_t cpb = (n_codes + fb - 1) / fb;
+        uint64_t cpb = (rest + fb - 1) / fb;
         cpb = (cpb + 1023) / 1024 * 1024;
         p.codes_per_block = static_cast<uint32_t>(cpb);
-        p.fblocks = static_cast<uint32_t>((n_codes + cpb - 1) / cpb);
+        p.fblocks = static_cast<uint32_t>((rest + cpb - 1) / cpb);
         p.slices = p.fblocks < static_cast<uint32_t>(kFastSlices) ? p.fblocks : kFastSlices;
         p.cap = 32 * r / p.slices < 1024 ? 1024 : 32 * r / p.slices;   // 32 r per query in all: twice the even share
         p.upd = r / 16 < 16 ? 16 : r / 16;                   // appends to one slice between bound updates
+        // Candidates waiting in the wavefronts' queues are invisible to the bound.  With few queries and
+        // thousands of wavefronts they would outnumber r, so a wavefront hands its queue over as soon as
+        // it holds its share of r / 4 waiting candidates per query (between 4 and a full queue of 64).
+        {
+            const uint64_t conc = 256 / p.ntiles ? 256 / p.ntiles : 1;             // workgroups of a tile at a time
+            const uint64_t blocks = conc < p.fblocks ? conc : p.fblocks;
+            const uint64_t tile_q = Q < p.fqt ? Q : p.fqt;
+            uint64_t lim = static_cast<uint64_t>(r / 4) * tile_q / (blocks * 16);
+            p.qflush = static_cast<uint32_t>(lim < 4 ? 4 : lim > 64 ? 64 : lim);
+        }
         const uint32_t want_sort = next_pow2(2 * r);
         p.sortcap = want_sort < kSortLdsKeys ? kSortLdsKeys : want_sort;
         // sample: runs of 256 codes spread evenly over the array, about 32 r codes (at least 64 Ki)

@@ -209,9 +209,9 @@ __device__ __noinline__ void lower_bound_of(int q, uint32_t r, int *t_cur, const
 
 template <int M, int QT, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
-    const uint16_t *__restrict__ codes, uint64_t n_codes, uint32_t codes_per_block,
+    const uint16_t *__restrict__ codes, uint64_t code_begin, uint64_t code_end, uint32_t codes_per_block,
     const uint8_t *__restrict__ qsw, int nq, uint32_t r, uint32_t nslices, uint32_t cap, uint32_t upd,
-    int *t_cur, uint32_t *count, uint32_t *chist, uint64_t *__restrict__ keys)
+    uint32_t qflush, int *t_cur, uint32_t *count, uint32_t *chist, uint64_t *__restrict__ keys)
 {
     using C = FastCfg<M, QT, WAVES>;
     extern __shared__ __align__(16) uint8_t smem[];
@@ -260,8 +260,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
         ql[v] = (C::ADJ ? row % C::NQB : row / C::CPS) * 16 + i;
     }
 
-    const uint64_t cbeg = static_cast<uint64_t>(blockIdx.y) * codes_per_block;
-    const uint64_t cend = min(n_codes, cbeg + codes_per_block);
+    // this workgroup's codes: a stretch of codes_per_block out of code_begin .. code_end
+    const uint64_t cbeg = code_begin + static_cast<uint64_t>(blockIdx.y) * codes_per_block;
+    const uint64_t cend = min(code_end, cbeg + codes_per_block);
     const uint32_t ngroups = cbeg < cend ? static_cast<uint32_t>((cend - cbeg + 63) / 64) : 0u;
 
     // Pending candidates of this wavefront: records wq[0 .. qlen), qlen <= QCAP = 64.  qlen is
@@ -320,18 +321,27 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
         for (int pf = 0; pf < PF; ++pf) load_group(g0 + pf * WAVES, wb[pf]);
     };
     load_batch(wave);
-    // bucket bounds of this lane's four (code, query) outputs, re-read once per batch and one
-    // batch ahead of their use; absent queries never match
-    auto load_bounds = [&](int (&dst)[4]) {
+    // Bucket bounds of the queries of this lane's four outputs, re-read once per batch and one batch
+    // ahead of their use; absent queries never match.  The four outputs are NB different queries
+    // (output v belongs to query v mod NB).  A stale bound is still a valid one (bounds only go down), so
+    // most reads may be served by the CU's vector cache; the first batches of a workgroup (when the
+    // bound moves fastest) and every 4th one after them read past it.  This keeps the thousands of
+    // wavefronts of a tile from queueing on the one cache line that holds its bounds.
+    constexpr int NB = (C::ADJ && C::NQB == 2) ? 2 : 1;
+    auto load_bounds = [&](int (&dst)[NB], bool fresh) {
 #pragma unroll
-        for (int v = 0; v < 4; ++v) {
-            const int q = q0 + ql[v];
-            const int t = q < nq ? __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : -1;
-            dst[v] = t >= 255 ? 0x7fffffff : t;
+        for (int b = 0; b < NB; ++b) {
+            const int q = q0 + ql[b];
+            int t = -1;
+            if (q < nq)
+                t = fresh ? __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                          : __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            dst[b] = t >= 255 ? 0x7fffffff : t;
         }
     };
-    int tl_next[4];
-    load_bounds(tl_next);
+    int tb_next[NB];
+    load_bounds(tb_next, true);
+    uint32_t batch = 0;
 
     for (uint32_t g0 = wave; g0 < ngroups; g0 += PF * WAVES) {
         uint32_t tbp[PF][M / 4];
@@ -340,8 +350,9 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
         load_batch(g0 + PF * WAVES);                                 // prefetch the next batch
         int tl[4];
 #pragma unroll
-        for (int v = 0; v < 4; ++v) tl[v] = tl_next[v];
-        load_bounds(tl_next);
+        for (int v = 0; v < 4; ++v) tl[v] = tb_next[v % NB];
+        ++batch;
+        load_bounds(tb_next, batch < 4 || (batch & 3u) == 0);
         v4i acc0;
 #pragma unroll
         for (int v = 0; v < 4; ++v)
@@ -444,6 +455,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
                 };
                 if (nlive == 64) decode(std::false_type{});
                 else decode(std::true_type{});
+                if (qlen >= qflush) flush();                       // uniform: keep the invisible backlog small
             }
         }
       }
@@ -582,9 +594,15 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     DCPQ_LAUNCH(kStageSelect, st, sample_threshold_kernel, dim3(nq), dim3(256), 0, shist, r, t_cur);
     DCPQ_CHECK_LAUNCH("sample_threshold_kernel");
     // the scan
+    if (p.warm_codes) {
+        DCPQ_LAUNCH(kStageScanFast, st, (scan_fast_kernel<M, QT, WAVES>), dim3(p.ntiles, p.warm_blocks),
+                    dim3(WAVES * 64), C::LDS_BYTES, codes, static_cast<uint64_t>(0), p.warm_codes,
+                    p.warm_codes_per_block, qsw, nq, r, p.slices, p.cap, p.upd, p.qflush, t_cur, fcount, chist, fkeys);
+        DCPQ_CHECK_LAUNCH("scan_fast_kernel");
+    }
     DCPQ_LAUNCH(kStageScanFast, st, (scan_fast_kernel<M, QT, WAVES>), dim3(p.ntiles, p.fblocks), dim3(WAVES * 64),
-                C::LDS_BYTES, codes, n_codes, p.codes_per_block, qsw, nq, r, p.slices, p.cap, p.upd, t_cur, fcount, chist,
-                fkeys);
+                C::LDS_BYTES, codes, p.warm_codes, n_codes, p.codes_per_block, qsw, nq, r, p.slices, p.cap, p.upd,
+                p.qflush, t_cur, fcount, chist, fkeys);
     DCPQ_CHECK_LAUNCH("scan_fast_kernel");
     // exact selection + list of queries to redo
     const int use_lds = p.sortcap <= kSortLdsKeys;

@@ -37,11 +37,14 @@ struct ScanPlan {
     bool fast;
     uint32_t fqt;             // queries per tile
     uint32_t ntiles;
-    uint32_t fblocks;         // workgroups along the code axis
+    uint32_t fblocks;         // workgroups along the code axis (main launch: codes warm_codes .. n_codes)
     uint32_t codes_per_block;
+    uint64_t warm_codes;      // codes 0 .. warm_codes go first, in a launch of their own (0: no such launch)
+    uint32_t warm_blocks, warm_codes_per_block;
     uint32_t slices;          // slices per query: min(kFastSlices, fblocks)
     uint32_t cap;             // candidate-buffer entries per query and slice
     uint32_t upd;             // appended candidates between two bound updates
+    uint32_t qflush;          // a wavefront appends its pending candidates once it holds this many
     uint32_t sortcap;         // keys the final selection can sort (power of two)
     uint32_t s_unit, s_nunits;    // sample: s_nunits runs of s_unit codes ...
     uint64_t s_stride;            // ... starting every s_stride codes
