@@ -38,6 +38,7 @@ _SIGNATURES = {
     "dcpq_scan_workspace_bytes": (_sz, [_u64, _i, _i, _u32]),
     "dcpq_scan_candidates": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_scan_query_tile": (_i, [_i]),
+    "dcpq_scan_plan": (_i, [_u64, _i, _i, _u32, _i, _vp, _i]),
     "dcpq_search_chunk": (_i, [_i, _i, _i]),
     "dcpq_scan_candidates_mode": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp, _sz, _i, _vp]),
     "dcpq_refine_workspace_bytes": (_sz, [_i, _u32]),
@@ -154,6 +155,14 @@ def search_chunk(m: int, nq: int, chunk_queries: int = 0) -> int:
 
 
 SCAN_AUTO, SCAN_THREE_PASS, SCAN_TILE16, SCAN_TILE32, SCAN_TILE64 = 0, 1, 2, 3, 4
+
+
+def scan_plan(n_codes: int, m: int, nq: int, r: int, mode: int = SCAN_AUTO) -> dict:
+    """How the scan lays out its work for this problem (see dcpq_scan_plan)."""
+    info = (C.c_uint64 * 8)()
+    _check(lib().dcpq_scan_plan(n_codes, m, nq, r, mode, C.cast(info, C.c_void_p), 8))
+    keys = ("query_tile", "tiles", "warm_codes", "warm_blocks", "blocks", "codes_per_block", "slices", "slice_cap")
+    return dict(zip(keys, (int(v) for v in info)))
 
 
 def scan_candidates(codes: torch.Tensor, qtab: torch.Tensor, r: int, workspace: torch.Tensor | None = None,

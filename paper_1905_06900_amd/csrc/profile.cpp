@@ -10,7 +10,8 @@ namespace dcpq {
 namespace prof {
 
 static const char *const kNames[kNumStages] = {
-    "small_tables", "scan_hist", "scan_tiecount", "scan_collect", "scan_fast", "select", "full_tables",
+    "small_tables", "scan_hist", "scan_tiecount", "scan_collect", "scan_fast", "scan_fast_warm", "select",
+    "full_tables",
     "refine_topk", "ivf", "misc",
 };
 

@@ -394,8 +394,8 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode)
         }
         const uint32_t want_sort = next_pow2(2 * r);
         p.sortcap = want_sort < kSortLdsKeys ? kSortLdsKeys : want_sort;
-        // sample: runs of 256 codes spread evenly over the array, about 32 r codes (at least 64 Ki)
-        uint64_t s_codes = 32ull * r < 65536 ? 65536 : 32ull * r;
+        // sample: runs of 256 codes spread evenly over the array, about 64 r codes (at least 64 Ki)
+        uint64_t s_codes = 64ull * r < 65536 ? 65536 : 64ull * r;
         if (s_codes > n_codes) s_codes = n_codes;
         p.s_unit = 256;
         p.s_nunits = static_cast<uint32_t>((s_codes + 255) / 256);
@@ -542,6 +542,24 @@ extern "C" int dcpq_scan_query_tile(int m)
     if (!m_supported(m)) return 0;
     const int f = fast_query_tile(m, 1 << 30, DCPQ_SCAN_AUTO);
     return f ? f : scan_qt(m);
+}
+
+extern "C" int dcpq_scan_plan(uint64_t n_codes, int m, int nq, uint32_t r, int mode, uint64_t *info, int ninfo)
+{
+    clear_error();
+    DCPQ_REQUIRE(info && ninfo >= 8, "scan_plan: info must hold 8 values");
+    DCPQ_REQUIRE(nq >= 1 && n_codes >= 1 && r >= 1, "scan_plan: empty problem");
+    if (!m_supported(m)) return fail(DCPQ_EUNSUPPORTED, "scan_plan: m=%d not supported", m);
+    const ScanPlan p = plan_scan(n_codes, m, nq, r, mode);
+    info[0] = p.fast ? p.fqt : p.qt;
+    info[1] = p.fast ? p.ntiles : (static_cast<uint64_t>(nq) + p.qt - 1) / p.qt;
+    info[2] = p.fast ? p.warm_codes : 0;
+    info[3] = p.fast && p.warm_codes ? p.warm_blocks : 0;
+    info[4] = p.fast ? p.fblocks : 0;
+    info[5] = p.fast ? p.codes_per_block : p.unit;
+    info[6] = p.fast ? p.slices : 0;
+    info[7] = p.fast ? p.cap : 0;
+    return DCPQ_OK;
 }
 
 extern "C" size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r)

@@ -595,7 +595,7 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     DCPQ_CHECK_LAUNCH("sample_threshold_kernel");
     // the scan
     if (p.warm_codes) {
-        DCPQ_LAUNCH(kStageScanFast, st, (scan_fast_kernel<M, QT, WAVES>), dim3(p.ntiles, p.warm_blocks),
+        DCPQ_LAUNCH(kStageScanFastWarm, st, (scan_fast_kernel<M, QT, WAVES>), dim3(p.ntiles, p.warm_blocks),
                     dim3(WAVES * 64), C::LDS_BYTES, codes, static_cast<uint64_t>(0), p.warm_codes,
                     p.warm_codes_per_block, qsw, nq, r, p.slices, p.cap, p.upd, p.qflush, t_cur, fcount, chist, fkeys);
         DCPQ_CHECK_LAUNCH("scan_fast_kernel");

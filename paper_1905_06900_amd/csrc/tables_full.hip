@@ -111,12 +111,120 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
     }
 }
 
+// Same computation for sub-spaces of at most 64 dimensions, laid out for the store stream: a workgroup
+// keeps its 256 centroids (as MFMA B operands, 4 * KS doubles per lane, KS = ceil(dsub / 4)) and their
+// norms in registers and walks kBigTileQ queries in sub-tiles of 16, so the codebook is read once per
+// 128 queries and every wavefront alternates a few MFMAs with 16 KiB of table stores.
+constexpr int kBigTileQ = 128;
+
+template <int KS>
+__global__ __launch_bounds__(256) void full_tables_stream_kernel(const float *__restrict__ queries, int nq,
+                                                                 const float *__restrict__ cb, int m, int dsub,
+                                                                 int ncent, float *__restrict__ tables)
+{
+    __shared__ double ny[kBigTileQ];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int j = blockIdx.z;
+    const int q0 = blockIdx.y * kBigTileQ;
+    const int c0 = blockIdx.x * kTileC;
+    const int D = m * dsub;
+    const float *cbj = cb + static_cast<size_t>(j) * ncent * dsub;
+    const int lr = lane & 15, lk = lane >> 4;
+
+    if (tid < kBigTileQ) {                               // query norms in fp64
+        double sy = 0.0;
+        if (q0 + tid < nq) {
+            const float *y = queries + static_cast<size_t>(q0 + tid) * D + j * dsub;
+            for (int t = 0; t < dsub; ++t) { const double v = y[t]; sy += v * v; }
+        }
+        ny[tid] = sy;
+    }
+
+    // B operands: lane (lr, lk) holds components 4 * ks + lk of centroids cw + 4 * lr + nt
+    const int cw = c0 + wave * 64;
+    double b[KS][4];
+    double nc[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        const int k = 4 * ks + lk;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) {
+            const int c = cw + lr * 4 + nt;
+            b[ks][nt] = (k < dsub && c < ncent) ? static_cast<double>(cbj[static_cast<size_t>(c) * dsub + k]) : 0.0;
+            nc[nt] += b[ks][nt] * b[ks][nt];
+        }
+    }
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {                     // sum the four component residues: full squared norms
+        nc[nt] += __shfl_xor(nc[nt], 16);
+        nc[nt] += __shfl_xor(nc[nt], 32);
+    }
+    __syncthreads();                                     // query norms visible
+
+    const int cl = wave * 64 + lr * 4;                   // this lane's 4 centroids within the tile
+    const bool vec_ok = c0 + cl + 3 < ncent && (ncent & 3) == 0;
+    for (int mt = 0; mt < kBigTileQ / 16; ++mt) {
+        if (q0 + mt * 16 >= nq) break;                   // uniform
+        const int qa = q0 + mt * 16 + lr;
+        double4_t acc[4];
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[nt] = double4_t{0.0, 0.0, 0.0, 0.0};
+        double a[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const int k = 4 * ks + lk;
+            a[ks] = (k < dsub && qa < nq) ? static_cast<double>(queries[static_cast<size_t>(qa) * D + j * dsub + k]) : 0.0;
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt)
+                acc[nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ks], b[ks][nt], acc[nt], 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int ql = mt * 16 + v * 4 + lk;
+            const int q = q0 + ql;
+            if (q >= nq) continue;
+            const double yy = ny[ql];
+            float4 o;
+            o.x = static_cast<float>(fmax(0.0, (yy + nc[0]) - 2.0 * acc[0][v]));
+            o.y = static_cast<float>(fmax(0.0, (yy + nc[1]) - 2.0 * acc[1][v]));
+            o.z = static_cast<float>(fmax(0.0, (yy + nc[2]) - 2.0 * acc[2][v]));
+            o.w = static_cast<float>(fmax(0.0, (yy + nc[3]) - 2.0 * acc[3][v]));
+            float *dst = tables + (static_cast<size_t>(q) * m + j) * ncent + c0 + cl;
+            if (vec_ok) {
+                *reinterpret_cast<float4 *>(dst) = o;
+            } else {
+                const float ov[4] = {o.x, o.y, o.z, o.w};
+                for (int z = 0; z < 4; ++z)
+                    if (c0 + cl + z < ncent) dst[z] = ov[z];
+            }
+        }
+    }
+}
+
+template <int KS>
+static void launch_stream(const float *queries, int nq, const float *codebooks, int m, int dsub, int ncent,
+                          float *tables, int stage, hipStream_t st)
+{
+    const dim3 grid((ncent + kTileC - 1) / kTileC, (nq + kBigTileQ - 1) / kBigTileQ, m);
+    DCPQ_LAUNCH(stage, st, (full_tables_stream_kernel<KS>), grid, dim3(256), 0, queries, nq, codebooks, m, dsub, ncent,
+                tables);
+}
+
 int launch_distance_tables(const float *queries, int nq, const float *codebooks, int m, int dsub, int ncent,
                            float *tables, int stage, hipStream_t st)
 {
     if (nq == 0) return DCPQ_OK;
-    const dim3 grid((ncent + kTileC - 1) / kTileC, (nq + kTileQ - 1) / kTileQ, m);
-    DCPQ_LAUNCH(stage, st, full_tables_kernel, grid, dim3(256), 0, queries, nq, codebooks, m, dsub, ncent, tables);
+    const int ks = (dsub + 3) / 4;
+    if (ks <= 3) launch_stream<3>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
+    else if (ks <= 4) launch_stream<4>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
+    else if (ks <= 8) launch_stream<8>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
+    else if (ks <= 16) launch_stream<16>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
+    else {
+        const dim3 grid((ncent + kTileC - 1) / kTileC, (nq + kTileQ - 1) / kTileQ, m);
+        DCPQ_LAUNCH(stage, st, full_tables_kernel, grid, dim3(256), 0, queries, nq, codebooks, m, dsub, ncent, tables);
+    }
     DCPQ_CHECK_LAUNCH("full_tables_kernel");
     return DCPQ_OK;
 }
