@@ -35,6 +35,13 @@
 //    true candidate set, from which the exact, id-tie-broken r are then selected; the result does
 //    not depend on the order of arrival.  If a buffer overflows (pathological ties), the query is
 //    flagged and redone by the three-pass path of scan.hip.
+//
+// 4. Appends stay off the critical path.  A query's buffer and append cursor are split into slices by
+//    the workgroup's position along the codes (same-address returning atomics serialize in the L2);
+//    a first, narrow launch over a small head of the array settles the bounds before the main launch
+//    starts thousands of wavefronts from the sample's loose bound; and a wavefront hands its pending
+//    candidates over early when few queries face many wavefronts, so that candidates waiting in
+//    queues never outnumber r.
 #include <type_traits>
 
 #include "common.h"
