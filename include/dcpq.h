@@ -94,7 +94,7 @@ int dcpq_build_tables(const float *queries, int nq, const float *codebooks, int 
  *   codes   : const uint16_t [n_codes][m]     qtab : const uint8_t [nq][m][256]
  *   cand_id : uint32_t [nq][r] (output)       cand_qd : uint8_t [nq][r] (output)
  *   workspace : at least dcpq_scan_workspace_bytes(n_codes, m, nq, r) bytes, 256-byte aligned
- * Requires 1 <= r <= n_codes < 2^32.
+ * Requires 1 <= r <= n_codes < 2^32; codes and qtab 16-byte aligned.
  * ------------------------------------------------------------------------------------------- */
 size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r);
 /* Queries that share one pass over the codes inside the scan kernels for a large batch (their tables
@@ -196,7 +196,7 @@ int dcpq_ivf_build_small_tables(const float *queries, int nq, const float *coars
  * the tables of the list the code lies in.  If the probed lists hold fewer than r codes the tail
  * is padded with id DCPQ_PAD_ID and qd 255; count[q] = number of valid candidates.
  *   cand_id : uint32_t [nq][r]  cand_qd : uint8_t [nq][r]  count : uint32_t [nq]  (outputs)
- *   workspace : dcpq_ivf_scan_workspace_bytes(nq, r), 256-byte aligned */
+ *   workspace : dcpq_ivf_scan_workspace_bytes(nq, r), 256-byte aligned; codes and qtab 16-byte aligned */
 size_t dcpq_ivf_scan_workspace_bytes(int nq, uint32_t r);
 int dcpq_ivf_scan_candidates(const uint16_t *codes, const int64_t *offsets, int nlist, int m,
                              const int32_t *probe, int nprobe, const uint8_t *qtab, int nq, uint32_t r,

@@ -283,13 +283,15 @@ __global__ __launch_bounds__(256) void ivf_plan_kernel(const int32_t *__restrict
 }
 
 enum IvfMode { kIvfHist = 0, kIvfTieCount = 1, kIvfCollect = 2 };
+constexpr int kIvfAhead = 4;     // 64-code groups whose codes a wavefront loads together
 
 // One wavefront per unit; grid (kIvfUnitsPerQuery / 4, nq), 256 threads.  The wavefront keeps the
 // 8-bit tables of its (query, list) in its own LDS slot and walks the unit 64 codes at a time.
 template <int M, int MODE>
 __global__ __launch_bounds__(256) void ivf_scan_kernel(const uint16_t *__restrict__ codes, const IvfUnit *__restrict__ units,
                                                       const uint32_t *__restrict__ nunits, const uint8_t *__restrict__ qtab,
-                                                      int nprobe, uint32_t r, uint32_t *__restrict__ hist,
+                                                      int nprobe, uint32_t r, uint32_t unit_step,
+                                                      const uint32_t *__restrict__ flags, uint32_t *__restrict__ hist,
                                                       const uint32_t *__restrict__ thr, uint32_t *__restrict__ tie,
                                                       uint32_t *__restrict__ counter, uint64_t *__restrict__ keys)
 {
@@ -299,7 +301,8 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const uint16_t *__restric
     const uint32_t u = blockIdx.x * 4 + wave;
     uint8_t *tab = smem + wave * (M * 256);                                      // [M][256]
     uint32_t *lhist = reinterpret_cast<uint32_t *>(smem + 4 * M * 256) + wave * 256;   // kIvfHist only
-    const bool active = u < nunits[q];
+    // every unit_step-th unit only (sampling), and only the queries with a flag when flags are given
+    const bool active = u < nunits[q] && u % unit_step == 0 && (!flags || flags[q] != 0);
     IvfUnit un{0, 0, 0};
     if (active) un = units[static_cast<size_t>(q) * kIvfUnitsPerQuery + u];
     if (active) {
@@ -317,16 +320,30 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const uint16_t *__restric
         T = thr[2 * q];
         if (MODE == kIvfCollect) aux = tie[static_cast<size_t>(q) * kIvfUnitsPerQuery + u];
     }
-    for (uint32_t base = 0; base < un.count; base += 64) {
+    // The unit is walked 64 codes at a time, in id order; the codes of kIvfAhead such groups are loaded
+    // together, so that one memory latency covers all of them.
+    for (uint32_t base0 = 0; base0 < un.count; base0 += 64 * kIvfAhead) {
+        uint32_t low[kIvfAhead][M];
+#pragma unroll
+        for (int g = 0; g < kIvfAhead; ++g) {
+            const uint32_t k = base0 + g * 64 + lane;
+            if (k < un.count) {
+                load_low_bytes<M>(codes, un.begin + k, low[g]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < M; ++j) low[g][j] = 0;
+            }
+        }
+#pragma unroll
+      for (int g = 0; g < kIvfAhead; ++g) {
+        const uint32_t base = base0 + g * 64;
+        if (base >= un.count) break;                                  // uniform
         const uint32_t k = base + lane;
         const bool live = k < un.count;
         const uint64_t id = un.begin + k;
         uint32_t s = 0;
-        if (live) {
-            const uint16_t *c = codes + id * M;
 #pragma unroll
-            for (int j = 0; j < M; ++j) s += tab[j * 256 + (c[j] & 255)];
-        }
+        for (int j = 0; j < M; ++j) s += tab[j * 256 + low[g][j]];
         const uint32_t qd = min(s, 255u);
         if (MODE == kIvfHist) {
             if (live) atomicAdd(&lhist[qd], 1u);
@@ -354,6 +371,7 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const uint16_t *__restric
                 }
             }
         }
+      }
     }
     if (MODE == kIvfHist) {
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -366,6 +384,104 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const uint16_t *__restric
     } else if (MODE == kIvfTieCount) {
         if (lane == 0) tie[static_cast<size_t>(q) * kIvfUnitsPerQuery + u] = aux;
     }
+}
+
+// The same scan in ONE pass over the probed lists (each pass reads every probed code from HBM, and no
+// two queries share them, so passes are what the scan costs).  As in the flat single pass, a query has
+// a running bucket bound, initialised from the histogram of a sample (every kIvfSampleStep-th unit) and
+// lowered as exact per-bucket counts of appended candidates accumulate; pairs at or below the bound are
+// appended to the query's sliced buffer, the exact r are selected afterwards, and a query whose buffer
+// overflows (or whose lists hold fewer than r codes) is redone by the three passes above.
+// Grid (nq, kIvfUnitsPerQuery / 4): the query index varies fastest, so only a few wavefronts of one
+// query run at a time and the candidates waiting in their queues stay few against r.
+constexpr uint32_t kIvfSampleStep = 16;
+
+template <int M>
+__global__ __launch_bounds__(256) void ivf_scan_single_kernel(const uint16_t *__restrict__ codes,
+                                                             const IvfUnit *__restrict__ units,
+                                                             const uint32_t *__restrict__ nunits,
+                                                             const uint8_t *__restrict__ qtab, int nprobe, uint32_t r,
+                                                             uint32_t cap, uint32_t upd, uint32_t qflush, int *t_cur,
+                                                             uint32_t *count, uint32_t *chist, uint64_t *__restrict__ keys)
+{
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int q = blockIdx.x;
+    const uint32_t u = blockIdx.y * 4 + wave;
+    uint8_t *tab = smem + wave * (M * 256);                                           // [M][256]
+    uint64_t *wq = reinterpret_cast<uint64_t *>(smem + 4 * M * 256) + wave * 64;      // pending candidates
+    const bool active = u < nunits[q];
+    IvfUnit un{0, 0, 0};
+    if (active) un = units[static_cast<size_t>(q) * kIvfUnitsPerQuery + u];
+    if (active) {
+        const uint4 *src = reinterpret_cast<const uint4 *>(qtab + (static_cast<size_t>(q) * nprobe + un.p) * M * 256);
+        uint4 *dst = reinterpret_cast<uint4 *>(tab);
+        for (int v = lane; v < M * 256 / 16; v += 64) dst[v] = src[v];
+    }
+    __syncthreads();
+    if (!active) return;
+
+    const size_t cell = static_cast<size_t>(q) * kFastSlices + u % kFastSlices;
+    uint32_t qlen = 0;                                   // wave-uniform
+    auto flush = [&]() {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        uint32_t first = 0;
+        if (lane == 0) first = atomicAdd(&count[cell], qlen);
+        first = __builtin_amdgcn_readfirstlane(__shfl(first, 0, kWave));
+        if (static_cast<uint32_t>(lane) < qlen) {
+            const uint64_t key = wq[lane];
+            if (first + lane < cap) keys[cell * cap + first + lane] = key;
+            else atomicMin(&t_cur[q], -1);               // slice full: stop appending, the query is redone
+            atomicAdd(&chist[static_cast<size_t>(q) * 256 + static_cast<uint32_t>(key >> 32)], 1u);
+        }
+        if (first / upd != (first + qlen) / upd) lower_bound_of(q, r, t_cur, chist);   // uniform
+        qlen = 0;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
+
+    for (uint32_t base0 = 0; base0 < un.count; base0 += 64 * kIvfAhead) {
+        int T = __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (T >= 255) T = 0x7fffffff;
+        uint32_t low[kIvfAhead][M];
+#pragma unroll
+        for (int g = 0; g < kIvfAhead; ++g) {
+            const uint32_t k = base0 + g * 64 + lane;
+            if (k < un.count) {
+                load_low_bytes<M>(codes, un.begin + k, low[g]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < M; ++j) low[g][j] = 0;
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < kIvfAhead; ++g) {
+            const uint32_t base = base0 + g * 64;
+            if (base >= un.count) break;                              // uniform
+            const uint32_t k = base + lane;
+            uint32_t s = 0;
+#pragma unroll
+            for (int j = 0; j < M; ++j) s += tab[j * 256 + low[g][j]];
+            const uint32_t qd = min(s, 255u);
+            const bool h = k < un.count && static_cast<int>(qd) <= T;
+            const uint64_t mask = __builtin_amdgcn_ballot_w64(h);
+            if (!mask) continue;                                      // uniform
+            const uint32_t cnt = __popcll(mask);
+            if (qlen + cnt > 64) flush();                             // uniform
+            if (h) {
+                const uint32_t rank = __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                                                __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+                wq[qlen + rank] = make_key(qd, static_cast<uint32_t>(un.begin + k));
+            }
+            qlen = __builtin_amdgcn_readfirstlane(qlen + cnt);
+            if (qlen >= qflush) flush();                              // uniform
+        }
+    }
+    if (qlen) flush();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -433,6 +549,9 @@ __global__ __launch_bounds__(1024) void ivf_refine_kernel(const float *__restric
 // ------------------------------------------------------------------------------------------------
 struct IvfScanPlan {
     size_t off_hist, off_thr, off_counter, off_nunits, zero_bytes, off_tie, off_units, off_keys, off_spill, total;
+    // single pass: sample histogram, cursors, appended histogram (cleared with the rest); bounds, flags, buffers
+    size_t off_shist, off_fcount, off_chist, off_tcur, off_flags, off_fkeys, off_fsort;
+    uint32_t cap, upd, qflush, sortcap;
 };
 
 static IvfScanPlan plan_ivf_scan(int nq, uint32_t r)
@@ -445,11 +564,31 @@ static IvfScanPlan plan_ivf_scan(int nq, uint32_t r)
     p.off_counter = off; off = align_up(off + sizeof(uint32_t) * Q, 256);
     p.off_nunits = off;  off = align_up(off + sizeof(uint32_t) * Q, 256);
     p.off_tie = off;     off = align_up(off + sizeof(uint32_t) * Q * kIvfUnitsPerQuery, 256);
+    p.off_shist = off;   off = align_up(off + sizeof(uint32_t) * 256 * Q, 256);
+    p.off_fcount = off;  off = align_up(off + sizeof(uint32_t) * Q * kFastSlices, 256);
+    p.off_chist = off;   off = align_up(off + sizeof(uint32_t) * 256 * Q, 256);
     p.zero_bytes = off;  // everything above is cleared together
     p.off_units = off;   off = align_up(off + sizeof(IvfUnit) * Q * kIvfUnitsPerQuery, 256);
     p.off_keys = off;    off = align_up(off + sizeof(uint64_t) * Q * r, 256);
     p.off_spill = off;
     if (next_pow2(r) > kSortLdsKeys) off = align_up(off + sizeof(uint64_t) * Q * next_pow2(r), 256);
+    p.cap = 2 * r < 1024 ? 1024 : 2 * r;                 // per slice; 32 r per query in all
+    p.upd = r / 16 < 16 ? 16 : r / 16;                   // appends to one slice between bound updates
+    // Pending candidates a wavefront may hold: the wavefronts of one query that run at the same time
+    // (about 2048 workgroups of 4 are resident, the query index varies fastest) together keep at most r / 4
+    // candidates away from the bound.
+    {
+        const size_t resident = 2048 / Q ? 2048 / Q : 1;
+        const size_t waves = 4 * resident < static_cast<size_t>(kIvfUnitsPerQuery) ? 4 * resident : kIvfUnitsPerQuery;
+        const size_t lim = r / 4 / waves;
+        p.qflush = static_cast<uint32_t>(lim < 1 ? 1 : lim > 64 ? 64 : lim);
+    }
+    p.sortcap = next_pow2(2 * r) < kSortLdsKeys ? kSortLdsKeys : next_pow2(2 * r);
+    p.off_tcur = off;    off = align_up(off + sizeof(int32_t) * Q, 256);
+    p.off_flags = off;   off = align_up(off + sizeof(uint32_t) * Q, 256);
+    p.off_fkeys = off;   off = align_up(off + sizeof(uint64_t) * Q * kFastSlices * p.cap, 256);
+    p.off_fsort = off;
+    if (p.sortcap > kSortLdsKeys) off = align_up(off + sizeof(uint64_t) * Q * p.sortcap, 256);
     p.total = off;
     return p;
 }
@@ -476,20 +615,40 @@ static int ivf_scan_m(const uint16_t *codes, const int64_t *offsets, const int32
     DCPQ_CHECK_LAUNCH("ivf_plan_kernel");
     const dim3 grid(kIvfUnitsPerQuery / 4, nq);
     const size_t lds_tab = 4 * M * 256;
+    uint32_t *shist = reinterpret_cast<uint32_t *>(base + p.off_shist);
+    uint32_t *fcount = reinterpret_cast<uint32_t *>(base + p.off_fcount);
+    uint32_t *chist = reinterpret_cast<uint32_t *>(base + p.off_chist);
+    int *t_cur = reinterpret_cast<int *>(base + p.off_tcur);
+    uint32_t *flags = reinterpret_cast<uint32_t *>(base + p.off_flags);
+    uint64_t *fkeys = reinterpret_cast<uint64_t *>(base + p.off_fkeys);
+    uint64_t *fsort = reinterpret_cast<uint64_t *>(base + p.off_fsort);
+    // single pass: bounds from a sample of the units, one pass over all of them, exact selection
     DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
-                nunits, qtab, nprobe, r, hist, thr, tie, counter, keys);
+                nunits, qtab, nprobe, r, kIvfSampleStep, nullptr, shist, thr, tie, counter, keys);
+    DCPQ_CHECK_LAUNCH("ivf_scan_kernel<sample>");
+    rc = launch_sample_threshold(shist, nq, r, t_cur, st);
+    if (rc) return rc;
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_single_kernel<M>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
+                lds_tab + 4 * 64 * 8, codes, units, nunits, qtab, nprobe, r, p.cap, p.upd, p.qflush, t_cur, fcount, chist,
+                fkeys);
+    DCPQ_CHECK_LAUNCH("ivf_scan_single_kernel");
+    rc = launch_fast_select(fkeys, fcount, chist, nq, r, kFastSlices, p.cap, p.sortcap, fsort, cand_id, cand_qd, flags, st);
+    if (rc) return rc;
+    // the queries it flagged (a full slice, or fewer than r codes in the probed lists): three passes
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
+                nunits, qtab, nprobe, r, 1u, flags, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<hist>");
     rc = launch_threshold(hist, nq, r, thr, st);
     if (rc) return rc;
     DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfTieCount>), grid, dim3(256), lds_tab, codes, units, nunits, qtab,
-                nprobe, r, hist, thr, tie, counter, keys);
+                nprobe, r, 1u, flags, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<tiecount>");
     rc = launch_tie_quota(tie, kIvfUnitsPerQuery, nq, thr, st);
     if (rc) return rc;
     DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfCollect>), grid, dim3(256), lds_tab, codes, units, nunits, qtab,
-                nprobe, r, hist, thr, tie, counter, keys);
+                nprobe, r, 1u, flags, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<collect>");
-    return launch_sort_candidates(keys, nq, r, spill, cand_id, cand_qd, st);
+    return launch_sort_candidates(keys, nq, r, spill, cand_id, cand_qd, st, flags);
 }
 
 static int ivf_check_common(const char *what, int nq, int m, int dsub, int nlist, int nprobe)
@@ -584,7 +743,8 @@ extern "C" int dcpq_ivf_scan_candidates(const uint16_t *codes, const int64_t *of
     if (nq == 0) return DCPQ_OK;
     DCPQ_REQUIRE(codes && offsets && probe && qtab && cand_id && cand_qd && count && workspace, "ivf_scan_candidates: null pointer");
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "ivf_scan_candidates: workspace must be 256-byte aligned");
-    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(qtab) & 15) == 0, "ivf_scan_candidates: qtab must be 16-byte aligned");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(qtab) & 15) == 0 && (reinterpret_cast<uintptr_t>(codes) & 15) == 0,
+                 "ivf_scan_candidates: codes and qtab must be 16-byte aligned");
     if (workspace_bytes < dcpq_ivf_scan_workspace_bytes(nq, r))
         return fail(DCPQ_EWORKSPACE, "ivf_scan_candidates: workspace %zu < %zu bytes", workspace_bytes, dcpq_ivf_scan_workspace_bytes(nq, r));
     hipStream_t st = as_stream(stream);

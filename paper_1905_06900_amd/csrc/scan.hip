@@ -30,32 +30,6 @@ constexpr int kScanWaves = kScanThreads / kWave;
 
 enum ScanMode { kHist = 0, kTieCount = 1, kCollect = 2 };
 
-// Low bytes of the m sub-codes of code i (property P1: the derived index is the low 8 bits).
-template <int M>
-__device__ inline void load_low_bytes(const uint16_t *__restrict__ codes, uint64_t i, uint32_t (&low)[M])
-{
-    if constexpr (M % 8 == 0) {
-        const uint4 *p = reinterpret_cast<const uint4 *>(codes + i * M);
-#pragma unroll
-        for (int v = 0; v < M / 8; ++v) {
-            const uint4 x = p[v];
-            low[8 * v + 0] = x.x & 255u; low[8 * v + 1] = (x.x >> 16) & 255u;
-            low[8 * v + 2] = x.y & 255u; low[8 * v + 3] = (x.y >> 16) & 255u;
-            low[8 * v + 4] = x.z & 255u; low[8 * v + 5] = (x.z >> 16) & 255u;
-            low[8 * v + 6] = x.w & 255u; low[8 * v + 7] = (x.w >> 16) & 255u;
-        }
-    } else if constexpr (M == 4) {
-        const uint2 x = *reinterpret_cast<const uint2 *>(codes + i * 4);
-        low[0] = x.x & 255u; low[1] = (x.x >> 16) & 255u;
-        low[2] = x.y & 255u; low[3] = (x.y >> 16) & 255u;
-    } else if constexpr (M == 2) {
-        const uint32_t x = *reinterpret_cast<const uint32_t *>(codes + i * 2);
-        low[0] = x & 255u; low[1] = (x >> 16) & 255u;
-    } else {
-        low[0] = codes[i] & 255u;
-    }
-}
-
 // Queries are addressed by their position p in the active list: query id = qlist ? qlist[p] : p.
 // Workspace arrays (hist, thr, tie, counter, keys) are indexed by p; qtab by the query id.
 template <int M, int QT, int MODE>
@@ -235,6 +209,7 @@ __global__ __launch_bounds__(1024) void sort_candidates_kernel(const uint64_t *_
                                                               uint64_t *__restrict__ spill,
                                                               const int *__restrict__ qlist,
                                                               const uint32_t *__restrict__ nq_dev,
+                                                              const uint32_t *__restrict__ flags,
                                                               uint32_t *__restrict__ cand_id,
                                                               uint8_t *__restrict__ cand_qd)
 {
@@ -242,6 +217,7 @@ __global__ __launch_bounds__(1024) void sort_candidates_kernel(const uint64_t *_
     const int p = blockIdx.x;
     if (nq_dev && p >= static_cast<int>(*nq_dev)) return;
     const int qid = qlist ? qlist[p] : p;
+    if (flags && flags[qid] == 0) return;
     uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(p) * n_pow2;
     for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x)
         a[t] = t < r ? keys[static_cast<size_t>(p) * r + t] : ~0ull;
@@ -298,12 +274,12 @@ int launch_tie_quota(uint32_t *tie, uint32_t nunits, int nq, const uint32_t *thr
 }
 
 int launch_sort_candidates(const uint64_t *keys, int nq, uint32_t r, uint64_t *spill, uint32_t *cand_id,
-                           uint8_t *cand_qd, hipStream_t st)
+                           uint8_t *cand_qd, hipStream_t st, const uint32_t *flags)
 {
     const uint32_t np2 = next_pow2(r);
     const bool use_spill = np2 > kSortLdsKeys;
     DCPQ_LAUNCH(kStageSelect, st, sort_candidates_kernel, dim3(nq), dim3(1024), use_spill ? 0 : sizeof(uint64_t) * np2,
-                keys, r, np2, use_spill ? 0 : 1, spill, nullptr, nullptr, cand_id, cand_qd);
+                keys, r, np2, use_spill ? 0 : 1, spill, nullptr, nullptr, flags, cand_id, cand_qd);
     DCPQ_CHECK_LAUNCH("sort_candidates_kernel");
     return DCPQ_OK;
 }
@@ -470,7 +446,7 @@ static int launch_three_pass(const uint16_t *codes, uint64_t n_codes, const uint
     DCPQ_CHECK_LAUNCH("scan_kernel<collect>");
     const uint32_t np2 = next_pow2(r);
     DCPQ_LAUNCH(kStageSelect, st, sort_candidates_kernel, dim3(nq), dim3(1024), spill ? 0 : sizeof(uint64_t) * np2,
-                keys, r, np2, spill ? 0 : 1, sorted, qlist, nq_dev, cand_id, cand_qd);
+                keys, r, np2, spill ? 0 : 1, sorted, qlist, nq_dev, nullptr, cand_id, cand_qd);
     DCPQ_CHECK_LAUNCH("sort_candidates_kernel");
     return DCPQ_OK;
 }

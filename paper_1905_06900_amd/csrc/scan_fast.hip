@@ -183,37 +183,6 @@ __device__ __noinline__ int append_candidate(uint64_t rec, int q0, uint32_t slic
     return (pos + 1) % upd == 0 ? static_cast<int>(q) : -1;
 }
 
-// Lowers query q's bucket bound to the bucket that holds its r-th best appended candidate (nothing
-// happens while fewer than r are appended).  Called by
-// a whole wavefront: lane l reads the counts of buckets 4l .. 4l+3, a wavefront prefix sum locates the
-// bucket.  The counts only grow, so any snapshot of them gives a bound that is still valid later.
-__device__ __noinline__ void lower_bound_of(int q, uint32_t r, int *t_cur, const uint32_t *chist)
-{
-    const int lane = threadIdx.x & 63;
-    uint32_t c[4];
-#pragma unroll
-    for (int z = 0; z < 4; ++z)
-        c[z] = __hip_atomic_load(&chist[static_cast<size_t>(q) * 256 + 4 * lane + z], __ATOMIC_RELAXED,
-                                 __HIP_MEMORY_SCOPE_AGENT);
-    const uint32_t mine = c[0] + c[1] + c[2] + c[3];
-    uint32_t incl = mine;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t other = __shfl(incl, lane >= d ? lane - d : lane);
-        if (lane >= d) incl += other;
-    }
-    uint32_t cum = incl - mine;                          // appended candidates in buckets below 4 * lane
-    if (cum < r && incl >= r) {                          // at most one lane
-        int tn = 4 * lane;
-#pragma unroll
-        for (int z = 0; z < 3; ++z) {
-            cum += c[z];
-            if (cum < r) tn = 4 * lane + z + 1;
-        }
-        atomicMin(&t_cur[q], tn);
-    }
-}
-
 template <int M, int QT, int WAVES>
 __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     const uint16_t *__restrict__ codes, uint64_t code_begin, uint64_t code_end, uint32_t codes_per_block,
@@ -585,9 +554,6 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
                         static_cast<size_t>(fa.sharedSizeBytes));
         DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_fast_kernel<M, QT, WAVES>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_select_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           static_cast<int>(sizeof(uint64_t) * kSortLdsKeys)));
         attr_done = true;
     }
 
@@ -598,8 +564,8 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     // sample histogram -> starting bounds
     int rc = launch_sample_hist(codes, n_codes, M, qtab, nq, r, shist, p, st);
     if (rc) return rc;
-    DCPQ_LAUNCH(kStageSelect, st, sample_threshold_kernel, dim3(nq), dim3(256), 0, shist, r, t_cur);
-    DCPQ_CHECK_LAUNCH("sample_threshold_kernel");
+    rc = launch_sample_threshold(shist, nq, r, t_cur, st);
+    if (rc) return rc;
     // the scan
     if (p.warm_codes) {
         DCPQ_LAUNCH(kStageScanFastWarm, st, (scan_fast_kernel<M, QT, WAVES>), dim3(p.ntiles, p.warm_blocks),
@@ -612,12 +578,35 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
                 p.qflush, t_cur, fcount, chist, fkeys);
     DCPQ_CHECK_LAUNCH("scan_fast_kernel");
     // exact selection + list of queries to redo
-    const int use_lds = p.sortcap <= kSortLdsKeys;
-    DCPQ_LAUNCH(kStageSelect, st, fast_select_kernel, dim3(nq), dim3(1024), use_lds ? sizeof(uint64_t) * p.sortcap : 0,
-                fkeys, fcount, chist, r, p.slices, p.cap, p.sortcap, use_lds, fsort, cand_id, cand_qd, flags);
-    DCPQ_CHECK_LAUNCH("fast_select_kernel");
+    rc = launch_fast_select(fkeys, fcount, chist, nq, r, p.slices, p.cap, p.sortcap, fsort, cand_id, cand_qd, flags, st);
+    if (rc) return rc;
     DCPQ_LAUNCH(kStageSelect, st, collect_flags_kernel, dim3(1), dim3(64), 0, flags, nq, qlist, nflag);
     DCPQ_CHECK_LAUNCH("collect_flags_kernel");
+    return DCPQ_OK;
+}
+
+int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, int *t_cur, hipStream_t st)
+{
+    DCPQ_LAUNCH(kStageSelect, st, sample_threshold_kernel, dim3(nq), dim3(256), 0, shist, r, t_cur);
+    DCPQ_CHECK_LAUNCH("sample_threshold_kernel");
+    return DCPQ_OK;
+}
+
+int launch_fast_select(const uint64_t *keys, const uint32_t *count, const uint32_t *chist, int nq, uint32_t r,
+                       uint32_t nslices, uint32_t cap, uint32_t sortcap, uint64_t *spill, uint32_t *cand_id,
+                       uint8_t *cand_qd, uint32_t *flags, hipStream_t st)
+{
+    static bool attr_done = false;          // LDS above 64 KiB must be requested once per kernel
+    if (!attr_done) {
+        DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_select_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           static_cast<int>(sizeof(uint64_t) * kSortLdsKeys)));
+        attr_done = true;
+    }
+    const int use_lds = sortcap <= kSortLdsKeys;
+    DCPQ_LAUNCH(kStageSelect, st, fast_select_kernel, dim3(nq), dim3(1024), use_lds ? sizeof(uint64_t) * sortcap : 0,
+                keys, count, chist, r, nslices, cap, sortcap, use_lds, spill, cand_id, cand_qd, flags);
+    DCPQ_CHECK_LAUNCH("fast_select_kernel");
     return DCPQ_OK;
 }
 

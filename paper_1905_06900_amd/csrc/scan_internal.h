@@ -72,15 +72,79 @@ int launch_scan_fast(const uint16_t *codes, uint64_t n_codes, int m, const uint8
                      uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, uint8_t *base, const ScanPlan &p,
                      hipStream_t st);
 
+// Steps of the single-pass selection that the inverted-list variant reuses.
+int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, int *t_cur, hipStream_t st);
+int launch_fast_select(const uint64_t *keys, const uint32_t *count, const uint32_t *chist, int nq, uint32_t r,
+                       uint32_t nslices, uint32_t cap, uint32_t sortcap, uint64_t *spill, uint32_t *cand_id,
+                       uint8_t *cand_qd, uint32_t *flags, hipStream_t st);
+
 // Small shared steps of the three-pass selection, reused by the inverted-list variant.
 int launch_zero_words(uint32_t *p, size_t nwords, hipStream_t st);
 int launch_fill_u64(uint64_t *p, size_t n, uint64_t v, hipStream_t st);
 int launch_threshold(const uint32_t *hist, int nq, uint32_t r, uint32_t *thr, hipStream_t st);
 int launch_tie_quota(uint32_t *tie, uint32_t nunits, int nq, const uint32_t *thr, hipStream_t st);
+// flags (may be null): only queries with a non-zero flag are sorted and written
 int launch_sort_candidates(const uint64_t *keys, int nq, uint32_t r, uint64_t *spill, uint32_t *cand_id,
-                           uint8_t *cand_qd, hipStream_t st);
+                           uint8_t *cand_qd, hipStream_t st, const uint32_t *flags = nullptr);
 
 #ifdef __HIPCC__
+// Low bytes of the m sub-codes of code i (property P1: the derived index is the low 8 bits).
+template <int M>
+__device__ inline void load_low_bytes(const uint16_t *__restrict__ codes, uint64_t i, uint32_t (&low)[M])
+{
+    if constexpr (M % 8 == 0) {
+        const uint4 *p = reinterpret_cast<const uint4 *>(codes + i * M);
+#pragma unroll
+        for (int v = 0; v < M / 8; ++v) {
+            const uint4 x = p[v];
+            low[8 * v + 0] = x.x & 255u; low[8 * v + 1] = (x.x >> 16) & 255u;
+            low[8 * v + 2] = x.y & 255u; low[8 * v + 3] = (x.y >> 16) & 255u;
+            low[8 * v + 4] = x.z & 255u; low[8 * v + 5] = (x.z >> 16) & 255u;
+            low[8 * v + 6] = x.w & 255u; low[8 * v + 7] = (x.w >> 16) & 255u;
+        }
+    } else if constexpr (M == 4) {
+        const uint2 x = *reinterpret_cast<const uint2 *>(codes + i * 4);
+        low[0] = x.x & 255u; low[1] = (x.x >> 16) & 255u;
+        low[2] = x.y & 255u; low[3] = (x.y >> 16) & 255u;
+    } else if constexpr (M == 2) {
+        const uint32_t x = *reinterpret_cast<const uint32_t *>(codes + i * 2);
+        low[0] = x & 255u; low[1] = (x >> 16) & 255u;
+    } else {
+        low[0] = codes[i] & 255u;
+    }
+}
+
+// Lowers query q's bucket bound to the bucket that holds its r-th best appended candidate (nothing
+// happens while fewer than r are appended).  Called by
+// a whole wavefront: lane l reads the counts of buckets 4l .. 4l+3, a wavefront prefix sum locates the
+// bucket.  The counts only grow, so any snapshot of them gives a bound that is still valid later.
+static __device__ __noinline__ void lower_bound_of(int q, uint32_t r, int *t_cur, const uint32_t *chist)
+{
+    const int lane = threadIdx.x & 63;
+    uint32_t c[4];
+#pragma unroll
+    for (int z = 0; z < 4; ++z)
+        c[z] = __hip_atomic_load(&chist[static_cast<size_t>(q) * 256 + 4 * lane + z], __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+    uint32_t incl = mine;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const uint32_t other = __shfl(incl, lane >= d ? lane - d : lane);
+        if (lane >= d) incl += other;
+    }
+    uint32_t cum = incl - mine;                          // appended candidates in buckets below 4 * lane
+    if (cum < r && incl >= r) {                          // at most one lane
+        int tn = 4 * lane;
+#pragma unroll
+        for (int z = 0; z < 3; ++z) {
+            cum += c[z];
+            if (cum < r) tn = 4 * lane + z + 1;
+        }
+        atomicMin(&t_cur[q], tn);
+    }
+}
+
 // In-place bitonic sort of n_pow2 64-bit keys by one workgroup (array in LDS or global memory).
 __device__ inline void bitonic_sort(uint64_t *a, uint32_t n_pow2)
 {
