@@ -2,7 +2,7 @@
 //
 // What is computed is the same as in scan.hip: qd = min(255, sum_j Q_j[low8(c[j])]) for every
 // (query, code) and the r smallest by (qd, id).  How it is computed differs from the paper's CPU
-// loop in three ways that matter on this chip:
+// loop in four ways that matter on this chip:
 //
 // 1. Row lookups instead of byte lookups.  A tile of QT queries keeps its tables in LDS
 //    transposed, T[j][e][q] with the query fastest, so that the table entries of one (code, j)
@@ -21,10 +21,10 @@
 //    D[row][n] = sum over the 4 sub-quantizers of T[j][e][16 * qb + n], and chaining M/4 of them
 //    through the accumulator gives the unsaturated integer distance.  The instruction multiplies
 //    SIGNED bytes, so the LDS copy of the tables holds x - 128 (the byte with its top bit flipped)
-//    and the accumulator starts at 128 * M instead of 0, which restores the unsigned sum exactly.  This is not a reshaping of
-//    the scan into a dense product (no one-hot expansion: every byte multiplied is a byte the
-//    method looks up); the matrix unit only replaces the byte unpack-and-add that the vector ALU
-//    would otherwise spend three instructions per four lookups on.
+//    and the accumulator starts at 128 * M instead of 0, which restores the unsigned sum exactly.
+//    This is not a reshaping of the scan into a dense product (no one-hot expansion: every byte
+//    multiplied is a byte the method looks up); the matrix unit only replaces the byte
+//    unpack-and-add that the vector ALU would otherwise spend three instructions per four lookups on.
 //
 // 3. Capped buckets become a running threshold.  Each query has a bucket bound T_cur that is
 //    never below the bucket of its r-th best candidate: it starts as the exact r-th smallest qd
