@@ -203,6 +203,17 @@ int dcpq_ivf_scan_candidates(const uint16_t *codes, const int64_t *offsets, int 
                              uint32_t *cand_id, uint8_t *cand_qd, uint32_t *count, void *workspace,
                              size_t workspace_bytes, void *stream);
 
+/* Low-byte plane of a code array.  Pass one consumes only the low bbar = 8 bits of every sub-code
+ * (Sec. 3.3, adc_low_bits), and the scan of probed lists is bound by the bytes it streams from HBM, so a
+ * copy of just those bytes halves its cost:  plane[i][j] = codes[i][j] & 255,  uint8_t [n_codes][m]
+ * (device, caller-owned, 16-byte aligned like codes).  An index-build step, like derive_codebooks. */
+int dcpq_pack_low_bytes(const uint16_t *codes, uint64_t n_codes, int m, uint8_t *plane, void *stream);
+/* dcpq_ivf_scan_candidates reading the plane instead of the codes: same arguments otherwise, same outputs. */
+int dcpq_ivf_scan_candidates_packed(const uint8_t *plane, const int64_t *offsets, int nlist, int m,
+                                    const int32_t *probe, int nprobe, const uint8_t *qtab, int nq, uint32_t r,
+                                    uint32_t *cand_id, uint8_t *cand_qd, uint32_t *count, void *workspace,
+                                    size_t workspace_bytes, void *stream);
+
 /* Refine step: d(q, i) = sum_j || (y_q - coarse[l(i)])^j - codebooks[j][codes[i][j]] ||^2 with l(i)
  * the probed list holding i, computed directly in double precision (Eq. 3 on the residual) and
  * rounded to fp32; the k smallest by (d, i), ascending; padded candidates give id DCPQ_PAD_ID and

@@ -65,11 +65,12 @@ def main() -> int:
             cb, coarse, offsets = d["codebooks"], d["coarse"], d["offsets"]
             codes, queries = d["codes"], d["queries"]
             derived = binding.derive_codebooks(cb)
+            plane = binding.pack_low_bytes(codes)                # index build: the bytes pass one reads
 
             def step():
                 probe = binding.ivf_probe(queries, coarse, w.nprobe)
                 qtab, _ = binding.ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, w.r)
-                cand_id, _, _ = binding.ivf_scan_candidates(codes, offsets, probe, qtab, w.r)
+                cand_id, _, _ = binding.ivf_scan_candidates(plane, offsets, probe, qtab, w.r)
                 binding.ivf_refine_topk(queries, coarse, cb, codes, offsets, probe, cand_id, w.k)
         sec, stages = time_steps(step, args.steps)
         print(json.dumps({

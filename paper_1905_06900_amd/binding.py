@@ -50,6 +50,8 @@ _SIGNATURES = {
     "dcpq_ivf_build_small_tables": (_i, [_vp, _i, _vp, _i, _vp, _i, _vp, _i, _i, _vp, _vp, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_ivf_scan_workspace_bytes": (_sz, [_i, _u32]),
     "dcpq_ivf_scan_candidates": (_i, [_vp, _vp, _i, _i, _vp, _i, _vp, _i, _u32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_ivf_scan_candidates_packed": (_i, [_vp, _vp, _i, _i, _vp, _i, _vp, _i, _u32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_pack_low_bytes": (_i, [_vp, _u64, _i, _vp, _vp]),
     "dcpq_ivf_refine_workspace_bytes": (_sz, [_i, _u32]),
     "dcpq_ivf_refine_topk": (_i, [_vp, _vp, _i, _vp, _i, _i, _vp, _vp, _vp, _i, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_profile_enable": (_i, [_i]),
@@ -276,8 +278,16 @@ def ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r: i
     return qtab, bounds
 
 
+def pack_low_bytes(codes: torch.Tensor) -> torch.Tensor:
+    """-> plane u8 [n][m], plane[i][j] = codes[i][j] & 255"""
+    n, m = codes.shape
+    plane = torch.empty((n, m), dtype=torch.uint8, device=codes.device)
+    _check(lib().dcpq_pack_low_bytes(_dev(codes, torch.uint16, "codes"), n, m, plane.data_ptr(), _stream()))
+    return plane
+
+
 def ivf_scan_candidates(codes, offsets, probe, qtab, r: int):
-    """-> (cand_id u32 [nq][r], cand_qd u8 [nq][r], count u32 [nq])"""
+    """-> (cand_id u32 [nq][r], cand_qd u8 [nq][r], count u32 [nq]); codes: the u16 codes or their u8 low-byte plane"""
     m = codes.shape[1]
     nq, nprobe = probe.shape
     nlist = offsets.shape[0] - 1
@@ -286,8 +296,10 @@ def ivf_scan_candidates(codes, offsets, probe, qtab, r: int):
     cand_qd = torch.empty((nq, r), dtype=torch.uint8, device=dev)
     count = torch.empty((nq,), dtype=torch.uint32, device=dev)
     ws = _workspace(lib().dcpq_ivf_scan_workspace_bytes(nq, r), dev)
-    _check(lib().dcpq_ivf_scan_candidates(
-        _dev(codes, torch.uint16, "codes"), _dev(offsets, torch.int64, "offsets"), nlist, m,
+    packed = codes.dtype == torch.uint8
+    fn = lib().dcpq_ivf_scan_candidates_packed if packed else lib().dcpq_ivf_scan_candidates
+    _check(fn(
+        _dev(codes, torch.uint8 if packed else torch.uint16, "codes"), _dev(offsets, torch.int64, "offsets"), nlist, m,
         _dev(probe, torch.int32, "probe"), nprobe, _dev(qtab, torch.uint8, "qtab"), nq, r, cand_id.data_ptr(),
         cand_qd.data_ptr(), count.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
     return cand_id, cand_qd, count

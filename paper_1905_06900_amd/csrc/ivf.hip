@@ -287,8 +287,9 @@ constexpr int kIvfAhead = 4;     // 64-code groups whose codes a wavefront loads
 
 // One wavefront per unit; grid (kIvfUnitsPerQuery / 4, nq), 256 threads.  The wavefront keeps the
 // 8-bit tables of its (query, list) in its own LDS slot and walks the unit 64 codes at a time.
-template <int M, int MODE>
-__global__ __launch_bounds__(256) void ivf_scan_kernel(const uint16_t *__restrict__ codes, const IvfUnit *__restrict__ units,
+// CodeT: uint16_t (the codes as stored) or uint8_t (their low-byte plane).
+template <int M, int MODE, typename CodeT>
+__global__ __launch_bounds__(256) void ivf_scan_kernel(const CodeT *__restrict__ codes, const IvfUnit *__restrict__ units,
                                                       const uint32_t *__restrict__ nunits, const uint8_t *__restrict__ qtab,
                                                       int nprobe, uint32_t r, uint32_t unit_step,
                                                       const uint32_t *__restrict__ flags, uint32_t *__restrict__ hist,
@@ -396,8 +397,8 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const uint16_t *__restric
 // query run at a time and the candidates waiting in their queues stay few against r.
 constexpr uint32_t kIvfSampleStep = 16;
 
-template <int M>
-__global__ __launch_bounds__(256) void ivf_scan_single_kernel(const uint16_t *__restrict__ codes,
+template <int M, typename CodeT>
+__global__ __launch_bounds__(256) void ivf_scan_single_kernel(const CodeT *__restrict__ codes,
                                                              const IvfUnit *__restrict__ units,
                                                              const uint32_t *__restrict__ nunits,
                                                              const uint8_t *__restrict__ qtab, int nprobe, uint32_t r,
@@ -593,8 +594,8 @@ static IvfScanPlan plan_ivf_scan(int nq, uint32_t r)
     return p;
 }
 
-template <int M>
-static int ivf_scan_m(const uint16_t *codes, const int64_t *offsets, const int32_t *probe, int nprobe,
+template <int M, typename CodeT>
+static int ivf_scan_m(const CodeT *codes, const int64_t *offsets, const int32_t *probe, int nprobe,
                       const uint8_t *qtab, int nq, uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, uint32_t *count,
                       uint8_t *base, hipStream_t st)
 {
@@ -623,29 +624,29 @@ static int ivf_scan_m(const uint16_t *codes, const int64_t *offsets, const int32
     uint64_t *fkeys = reinterpret_cast<uint64_t *>(base + p.off_fkeys);
     uint64_t *fsort = reinterpret_cast<uint64_t *>(base + p.off_fsort);
     // single pass: bounds from a sample of the units, one pass over all of them, exact selection
-    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist, CodeT>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
                 nunits, qtab, nprobe, r, kIvfSampleStep, nullptr, shist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<sample>");
     rc = launch_sample_threshold(shist, nq, r, t_cur, st);
     if (rc) return rc;
-    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_single_kernel<M>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_single_kernel<M, CodeT>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
                 lds_tab + 4 * 64 * 8, codes, units, nunits, qtab, nprobe, r, p.cap, p.upd, p.qflush, t_cur, fcount, chist,
                 fkeys);
     DCPQ_CHECK_LAUNCH("ivf_scan_single_kernel");
     rc = launch_fast_select(fkeys, fcount, chist, nq, r, kFastSlices, p.cap, p.sortcap, fsort, cand_id, cand_qd, flags, st);
     if (rc) return rc;
     // the queries it flagged (a full slice, or fewer than r codes in the probed lists): three passes
-    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist, CodeT>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
                 nunits, qtab, nprobe, r, 1u, flags, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<hist>");
     rc = launch_threshold(hist, nq, r, thr, st);
     if (rc) return rc;
-    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfTieCount>), grid, dim3(256), lds_tab, codes, units, nunits, qtab,
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfTieCount, CodeT>), grid, dim3(256), lds_tab, codes, units, nunits, qtab,
                 nprobe, r, 1u, flags, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<tiecount>");
     rc = launch_tie_quota(tie, kIvfUnitsPerQuery, nq, thr, st);
     if (rc) return rc;
-    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfCollect>), grid, dim3(256), lds_tab, codes, units, nunits, qtab,
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfCollect, CodeT>), grid, dim3(256), lds_tab, codes, units, nunits, qtab,
                 nprobe, r, 1u, flags, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<collect>");
     return launch_sort_candidates(keys, nq, r, spill, cand_id, cand_qd, st, flags);
@@ -731,22 +732,23 @@ extern "C" size_t dcpq_ivf_scan_workspace_bytes(int nq, uint32_t r)
     return plan_ivf_scan(nq, r).total;
 }
 
-extern "C" int dcpq_ivf_scan_candidates(const uint16_t *codes, const int64_t *offsets, int nlist, int m,
-                                        const int32_t *probe, int nprobe, const uint8_t *qtab, int nq, uint32_t r,
-                                        uint32_t *cand_id, uint8_t *cand_qd, uint32_t *count, void *workspace,
-                                        size_t workspace_bytes, void *stream)
+template <typename CodeT>
+static int ivf_scan_checked(const char *what, const CodeT *codes, const int64_t *offsets, int nlist, int m,
+                            const int32_t *probe, int nprobe, const uint8_t *qtab, int nq, uint32_t r,
+                            uint32_t *cand_id, uint8_t *cand_qd, uint32_t *count, void *workspace,
+                            size_t workspace_bytes, void *stream)
 {
     clear_error();
-    int rc = ivf_check_common("ivf_scan_candidates", nq, m, 1, nlist, nprobe);
+    int rc = ivf_check_common(what, nq, m, 1, nlist, nprobe);
     if (rc) return rc;
-    DCPQ_REQUIRE(r >= 1 && r <= (1u << 26), "ivf_scan_candidates: r=%u out of range", r);
+    DCPQ_REQUIRE(r >= 1 && r <= (1u << 26), "%s: r=%u out of range", what, r);
     if (nq == 0) return DCPQ_OK;
-    DCPQ_REQUIRE(codes && offsets && probe && qtab && cand_id && cand_qd && count && workspace, "ivf_scan_candidates: null pointer");
-    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "ivf_scan_candidates: workspace must be 256-byte aligned");
+    DCPQ_REQUIRE(codes && offsets && probe && qtab && cand_id && cand_qd && count && workspace, "%s: null pointer", what);
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "%s: workspace must be 256-byte aligned", what);
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(qtab) & 15) == 0 && (reinterpret_cast<uintptr_t>(codes) & 15) == 0,
-                 "ivf_scan_candidates: codes and qtab must be 16-byte aligned");
+                 "%s: codes and qtab must be 16-byte aligned", what);
     if (workspace_bytes < dcpq_ivf_scan_workspace_bytes(nq, r))
-        return fail(DCPQ_EWORKSPACE, "ivf_scan_candidates: workspace %zu < %zu bytes", workspace_bytes, dcpq_ivf_scan_workspace_bytes(nq, r));
+        return fail(DCPQ_EWORKSPACE, "%s: workspace %zu < %zu bytes", what, workspace_bytes, dcpq_ivf_scan_workspace_bytes(nq, r));
     hipStream_t st = as_stream(stream);
     uint8_t *base = static_cast<uint8_t *>(workspace);
     switch (m) {
@@ -758,6 +760,60 @@ extern "C" int dcpq_ivf_scan_candidates(const uint16_t *codes, const int64_t *of
         case 32: return ivf_scan_m<32>(codes, offsets, probe, nprobe, qtab, nq, r, cand_id, cand_qd, count, base, st);
         default: return fail(DCPQ_EUNSUPPORTED, "m=%d not supported", m);
     }
+}
+
+extern "C" int dcpq_ivf_scan_candidates(const uint16_t *codes, const int64_t *offsets, int nlist, int m,
+                                        const int32_t *probe, int nprobe, const uint8_t *qtab, int nq, uint32_t r,
+                                        uint32_t *cand_id, uint8_t *cand_qd, uint32_t *count, void *workspace,
+                                        size_t workspace_bytes, void *stream)
+{
+    return ivf_scan_checked("ivf_scan_candidates", codes, offsets, nlist, m, probe, nprobe, qtab, nq, r, cand_id, cand_qd,
+                            count, workspace, workspace_bytes, stream);
+}
+
+extern "C" int dcpq_ivf_scan_candidates_packed(const uint8_t *plane, const int64_t *offsets, int nlist, int m,
+                                               const int32_t *probe, int nprobe, const uint8_t *qtab, int nq,
+                                               uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, uint32_t *count,
+                                               void *workspace, size_t workspace_bytes, void *stream)
+{
+    return ivf_scan_checked("ivf_scan_candidates_packed", plane, offsets, nlist, m, probe, nprobe, qtab, nq, r, cand_id,
+                            cand_qd, count, workspace, workspace_bytes, stream);
+}
+
+namespace dcpq {
+// plane[i][j] = codes[i][j] & 255, eight sub-codes per thread
+__global__ __launch_bounds__(256) void pack_low_bytes_kernel(const uint16_t *__restrict__ codes, uint64_t nsub,
+                                                            uint8_t *__restrict__ plane)
+{
+    const uint64_t t = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x;     // 8 sub-codes per thread
+    const uint64_t i = t * 8;
+    if (i + 8 <= nsub) {
+        const uint4 x = *reinterpret_cast<const uint4 *>(codes + i);
+        uint2 o;
+        o.x = (x.x & 255u) | ((x.x >> 8) & 0xff00u) | ((x.y & 255u) << 16) | ((x.y << 8) & 0xff000000u);
+        o.y = (x.z & 255u) | ((x.z >> 8) & 0xff00u) | ((x.w & 255u) << 16) | ((x.w << 8) & 0xff000000u);
+        *reinterpret_cast<uint2 *>(plane + i) = o;
+    } else {
+        for (uint64_t k = i; k < nsub; ++k) plane[k] = static_cast<uint8_t>(codes[k] & 255u);
+    }
+}
+}  // namespace dcpq
+
+extern "C" int dcpq_pack_low_bytes(const uint16_t *codes, uint64_t n_codes, int m, uint8_t *plane, void *stream)
+{
+    clear_error();
+    DCPQ_REQUIRE(m >= 1 && m <= 64, "pack_low_bytes: m=%d", m);
+    if (n_codes == 0) return DCPQ_OK;
+    DCPQ_REQUIRE(codes && plane, "pack_low_bytes: null pointer");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(codes) & 15) == 0 && (reinterpret_cast<uintptr_t>(plane) & 15) == 0,
+                 "pack_low_bytes: codes and plane must be 16-byte aligned");
+    const uint64_t nsub = n_codes * static_cast<uint64_t>(m);
+    const uint64_t nthreads = (nsub + 7) / 8;
+    hipStream_t st = as_stream(stream);
+    DCPQ_LAUNCH(kStageMisc, st, pack_low_bytes_kernel, dim3(static_cast<unsigned>((nthreads + 255) / 256)), dim3(256), 0,
+                codes, nsub, plane);
+    DCPQ_CHECK_LAUNCH("pack_low_bytes_kernel");
+    return DCPQ_OK;
 }
 
 extern "C" size_t dcpq_ivf_refine_workspace_bytes(int nq, uint32_t r)

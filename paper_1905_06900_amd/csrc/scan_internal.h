@@ -145,6 +145,33 @@ static __device__ __noinline__ void lower_bound_of(int q, uint32_t r, int *t_cur
     }
 }
 
+// The same from the low-byte plane of the codes (uint8 [n][m], the bytes pass one consumes).
+template <int M>
+__device__ inline void load_low_bytes(const uint8_t *__restrict__ plane, uint64_t i, uint32_t (&low)[M])
+{
+    if constexpr (M % 8 == 0) {
+        const uint2 *p = reinterpret_cast<const uint2 *>(plane + i * M);
+#pragma unroll
+        for (int v = 0; v < M / 8; ++v) {
+            const uint2 x = p[v];
+#pragma unroll
+            for (int z = 0; z < 4; ++z) {
+                low[8 * v + z] = (x.x >> (8 * z)) & 255u;
+                low[8 * v + 4 + z] = (x.y >> (8 * z)) & 255u;
+            }
+        }
+    } else if constexpr (M == 4) {
+        const uint32_t x = *reinterpret_cast<const uint32_t *>(plane + i * 4);
+#pragma unroll
+        for (int z = 0; z < 4; ++z) low[z] = (x >> (8 * z)) & 255u;
+    } else if constexpr (M == 2) {
+        const uint32_t x = *reinterpret_cast<const uint16_t *>(plane + i * 2);
+        low[0] = x & 255u; low[1] = (x >> 8) & 255u;
+    } else {
+        low[0] = plane[i];
+    }
+}
+
 // In-place bitonic sort of n_pow2 64-bit keys by one workgroup (array in LDS or global memory).
 __device__ inline void bitonic_sort(uint64_t *a, uint32_t n_pow2)
 {

@@ -109,3 +109,34 @@ def test_ivf_argument_errors():
     with pytest.raises(binding.DcpqError) as e:
         binding.ivf_probe(q, coarse, 600)                # above the supported nprobe
     assert e.value.code == binding.EUNSUPPORTED
+
+
+def test_low_byte_plane_gives_the_same_candidates():
+    """pack_low_bytes is the low byte of every sub-code, and the scan of probed lists returns the same
+    candidate ids / integer distances / counts from the plane as from the codes (ragged N, padded lists)."""
+    for (N, Q, r, nlist, nprobe) in [(300_007, 23, 500, 512, 16), (3001, 7, 300, 64, 5)]:
+        w = synth.scaled(synth.WORKLOADS[3], N=N, Q=Q, r=r, nlist=nlist, nprobe=nprobe)
+        print("ivf plane case: N=%d Q=%d r=%d nlist=%d nprobe=%d" % (N, Q, r, nlist, nprobe), flush=True)
+        d = synth.make_ivf(w, DEV)
+        cb, coarse, offsets, codes, queries = d["codebooks"], d["coarse"], d["offsets"], d["codes"], d["queries"]
+        plane = binding.pack_low_bytes(codes)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(to_np(plane), (to_np(codes) & 255).astype(np.uint8))
+        derived = binding.derive_codebooks(cb)
+        probe = binding.ivf_probe(queries, coarse, nprobe)
+        qtab, _ = binding.ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r)
+        a = binding.ivf_scan_candidates(codes, offsets, probe, qtab, r)
+        b = binding.ivf_scan_candidates(plane, offsets, probe, qtab, r)
+        torch.cuda.synchronize()
+        for x, y, name in zip(a, b, ("cand_id", "cand_qd", "count")):
+            np.testing.assert_array_equal(to_np(x), to_np(y), err_msg=name)
+
+
+@pytest.mark.parametrize("m", [1, 2, 4, 16, 32])
+def test_low_byte_plane_every_m(m):
+    rng = np.random.default_rng(m)
+    n = 10_003
+    codes = torch.from_numpy(rng.integers(0, 65536, size=(n, m)).astype(np.uint16).view(np.int16)).to(DEV).view(torch.uint16)
+    plane = binding.pack_low_bytes(codes)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(plane), (to_np(codes) & 255).astype(np.uint8))
