@@ -118,6 +118,33 @@ def main() -> int:
         "pairs_per_s": round(w.N * w.Q / (scan_ms * 1e-3), 1) if scan_ms > 0 else None,
     }
 
+    # The same scan with the 16-query tile on one chunk: a quarter of the lookups per byte of code stream,
+    # i.e. the configuration in which pass one is bound by the stream and not by LDS lookups.  Context for
+    # `roofline` (which describes the configuration that gives the most queries/s), not part of `value`.
+    stream_variant = None
+    if w.m == 8 and dom == "scan_fast":
+        nq_v = min(chunk, w.Q)
+        qtab_v, _, _ = binding.build_small_tables(queries[:nq_v].contiguous(), derived, codes, w.r)
+        ws_v = torch.empty(binding.scan_workspace_bytes(w.N, w.m, nq_v, w.r), dtype=torch.uint8, device=dev)
+        binding.scan_candidates(codes, qtab_v, w.r, workspace=ws_v, mode=binding.SCAN_TILE16)
+        torch.cuda.synchronize()
+        binding.profile_enable(True)
+        for _ in range(2):
+            binding.scan_candidates(codes, qtab_v, w.r, workspace=ws_v, mode=binding.SCAN_TILE16)
+        torch.cuda.synchronize()
+        st_v = binding.profile_read()
+        binding.profile_enable(False)
+        plan_v = binding.scan_plan(w.N, w.m, nq_v, w.r, binding.SCAN_TILE16)
+        ms_v = st_v["scan_fast"][0] / st_v["scan_fast"][1]
+        bytes_v = plan_v["tiles"] * (w.N - plan_v["warm_codes"]) * code_bytes
+        stream_variant = {
+            "query_tile": 16, "queries": nq_v, "bound": "hbm", "achieved": round(bytes_v / (ms_v * 1e-3) / 1e9, 1),
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(bytes_v / (ms_v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+            "avg_launch_ms": round(ms_v, 4), "bytes_per_launch": bytes_v,
+            "scan_ms_with_warmup_launch": round((st_v["scan_fast"][0] + st_v.get("scan_fast_warm", (0.0, 0))[0]) / 2, 4),
+        }
+        del ws_v, qtab_v
+
     out = {
         "metric": "queries/sec at k=100 + scan GB/s vs HBM peak (PQ 8x16, N=100M, 1 GPU)",
         "value": round(qps, 2), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -126,6 +153,7 @@ def main() -> int:
         "config": {"workload": w.name, "N": w.N, "queries": w.Q, "m": w.m, "dsub": w.dsub, "r": w.r, "k": w.k,
                    "code_bytes": code_bytes, "seed": w.seed},
         "roofline": roofline,
+        "scan_stream_variant": stream_variant,
         "stage_ms_per_step": {s: round(v[0] / args.steps, 3) for s, v in stages.items() if v[1]},
         "setup_s": round(setup_s, 2),
     }
