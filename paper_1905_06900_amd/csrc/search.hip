@@ -13,9 +13,10 @@ static SearchPlan plan_search(uint64_t n_codes, int m, int nq, uint32_t r, int c
 {
     SearchPlan p{};
     int chunk = chunk_queries;
-    if (chunk <= 0) {   // default: about 2 GiB of full tables per chunk
+    if (chunk <= 0) {   // default: about 8 GiB of full tables per chunk (sized for a 288 GB device; the larger
+                        // the chunk, the fewer launches share the scan's start-up and tail)
         const size_t per_q = sizeof(float) * static_cast<size_t>(m) * kFullSize;
-        chunk = static_cast<int>((static_cast<size_t>(2) << 30) / per_q);
+        chunk = static_cast<int>((static_cast<size_t>(8) << 30) / per_q);
         if (chunk < 64) chunk = 64;
     }
     if (chunk > nq) chunk = nq;
