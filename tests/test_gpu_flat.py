@@ -226,3 +226,36 @@ def test_scan_many_queries_ragged_tiles_and_a_few_pathological_ones():
     qtab[149] = (rng.integers(0, 2, size=(8, 256)) * 40).astype(np.uint8)
     print("scan many queries N=%d Q=%d" % (N, Q), flush=True)
     scan_vs_oracle(codes, qtab, r)
+
+
+def test_scan_random_shapes():
+    """Seeded sweep of odd shapes (sizes around the group, tile, slice and queue limits) through every scan
+    algorithm the shape has."""
+    rng = np.random.default_rng(20260101)
+    for case in range(24):
+        m = int(rng.choice([4, 8, 8, 16, 32]))
+        N = int(rng.choice([1, 63, 64, 65, 1023, 1025, 4097, 20_011, 65_537, 150_001]))
+        Q = int(rng.choice([1, 2, 15, 16, 17, 33, 64, 65, 129]))
+        r = int(min(N, rng.choice([1, 2, 63, 64, 65, 500, 3000])))
+        hi = int(rng.choice([2, 8, 256 // m + 8, 256]))
+        codes = rng.integers(0, 65536, size=(N, m)).astype(np.uint16)
+        qtab = rng.integers(0, hi, size=(Q, m, 256)).astype(np.uint8)
+        modes = [binding.SCAN_AUTO, binding.SCAN_THREE_PASS]
+        if m == 8:
+            modes += [binding.SCAN_TILE16, binding.SCAN_TILE32, binding.SCAN_TILE64]
+        print("scan random case %d: m=%d N=%d Q=%d r=%d table values < %d" % (case, m, N, Q, r, hi), flush=True)
+        scan_vs_oracle(codes, qtab, r, modes=tuple(modes))
+
+
+@pytest.mark.parametrize("Q", [5, 70])
+def test_scan_with_the_warm_up_launch(Q):
+    """From 4 Mi codes on, the single pass first scans a head of the array with few workgroups; ids must stay
+    global and every code must be scanned exactly once (all tiles, ragged last workgroup)."""
+    rng = np.random.default_rng(77 + Q)
+    N, r = 4_200_003, 700
+    codes = rng.integers(0, 65536, size=(N, 8)).astype(np.uint16)
+    qtab = rng.integers(0, 40, size=(Q, 8, 256)).astype(np.uint8)
+    plan = binding.scan_plan(N, 8, Q, r)
+    assert plan["warm_codes"] > 0
+    print("scan warm-up case N=%d Q=%d: warm-up %d codes" % (N, Q, plan["warm_codes"]), flush=True)
+    scan_vs_oracle(codes, qtab, r, modes=(binding.SCAN_AUTO, binding.SCAN_TILE16, binding.SCAN_TILE64))
