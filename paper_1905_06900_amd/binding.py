@@ -218,6 +218,7 @@ def search(queries: torch.Tensor, codebooks: torch.Tensor, derived: torch.Tensor
     m, _, dsub = codebooks.shape
     n = codes.shape[0]
     nq = queries.shape[0]
+    assert queries.shape[1] == m * dsub and codes.shape[1] == m and derived.shape == (m, 256, dsub)
     dev = queries.device
     if ids is None:
         ids = torch.empty((nq, k), dtype=torch.uint32, device=dev)
@@ -266,6 +267,7 @@ def ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r: i
     m, _, dsub = derived.shape
     nq, nprobe = probe.shape
     nlist = coarse.shape[0]
+    assert queries.shape == (nq, m * dsub) and coarse.shape[1] == m * dsub and codes.shape[1] == m
     dev = queries.device
     qtab = torch.empty((nq, nprobe, m, 256), dtype=torch.uint8, device=dev)
     bounds = torch.empty((nq, 2), dtype=torch.float32, device=dev)
@@ -311,6 +313,8 @@ def ivf_refine_topk(queries, coarse, codebooks, codes, offsets, probe, cand_id, 
     nq, r = cand_id.shape
     nprobe = probe.shape[1]
     nlist = coarse.shape[0]
+    assert queries.shape == (nq, m * dsub) and coarse.shape[1] == m * dsub and codes.shape[1] == m
+    assert probe.shape[0] == nq
     dev = queries.device
     ids = torch.empty((nq, k), dtype=torch.uint32, device=dev)
     dist = torch.empty((nq, k), dtype=torch.float32, device=dev)

@@ -100,6 +100,17 @@ def test_ivf_all_lists_probed_identical_centres_ties_by_id():
     assert (probe == np.arange(16)[None, :]).all()
 
 
+@pytest.mark.parametrize("m,dsub", [(1, 128), (2, 64), (4, 32), (16, 8), (32, 4)])
+def test_ivf_other_code_shapes(m, dsub):
+    """The inverted-index path for every supported m besides the recipe's 8 (the recipe's 128-dimensional vectors split other ways)."""
+    from dataclasses import replace
+    w = replace(synth.scaled(synth.WORKLOADS[3], N=60_013, Q=11, r=300, nlist=128, nprobe=9), m=m, dsub=dsub)
+    print("ivf case: m=%d dsub=%d N=%d Q=%d nlist=%d nprobe=%d r=%d" % (m, dsub, w.N, w.Q, w.nlist, w.nprobe, w.r),
+          flush=True)
+    d = synth.make_ivf(w, DEV)
+    run_ivf_case(d, w.nprobe, w.r, 50)
+
+
 def test_ivf_argument_errors():
     q = torch.zeros((2, 128), device=DEV); coarse = torch.zeros((8, 128), device=DEV)
     with pytest.raises(binding.DcpqError) as e:
