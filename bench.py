@@ -16,7 +16,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-SCAN_STAGES = ("scan_fast", "scan_fast_warm", "scan_hist", "scan_tiecount", "scan_collect")
+SCAN_STAGES = ("scan_fast", "scan_hist", "scan_tiecount", "scan_collect")
 
 
 def main() -> int:
@@ -92,11 +92,8 @@ def main() -> int:
     passes_per_step = sum((min(binding.search_chunk(w.m, w.Q, args.chunk), w.Q - q0) + qt - 1) // qt
                           for q0 in range(0, w.Q, binding.search_chunk(w.m, w.Q, args.chunk)))
     launches_per_step = dom_launches / args.steps
-    # the single pass gives a small head of the codes to a warm-up launch of its own (stage
-    # scan_fast_warm); the dominant launch streams the rest
     chunk = binding.search_chunk(w.m, w.Q, args.chunk)
-    warm = binding.scan_plan(w.N, w.m, min(chunk, w.Q), w.r)["warm_codes"] if dom == "scan_fast" else 0
-    bytes_per_launch = passes_per_step * (w.N - warm) * code_bytes / launches_per_step
+    bytes_per_launch = passes_per_step * w.N * code_bytes / launches_per_step
     avg_launch_s = dom_ms / dom_launches * 1e-3
     achieved = bytes_per_launch / avg_launch_s / 1e9
     scan_ms = sum(stages.get(s, (0.0, 0))[0] for s in SCAN_STAGES) / args.steps
@@ -114,7 +111,7 @@ def main() -> int:
         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
         "bytes_per_launch": bytes_per_launch, "avg_launch_ms": round(dom_ms / dom_launches, 4),
         "launches_per_step": launches_per_step, "queries_per_pass": qt,
-        "code_passes_per_step": passes_per_step, "codes_per_pass": w.N - warm,
+        "code_passes_per_step": passes_per_step, "codes_per_pass": w.N,
         "pairs_per_s": round(w.N * w.Q / (scan_ms * 1e-3), 1) if scan_ms > 0 else None,
     }
 
@@ -136,12 +133,11 @@ def main() -> int:
         binding.profile_enable(False)
         plan_v = binding.scan_plan(w.N, w.m, nq_v, w.r, binding.SCAN_TILE16)
         ms_v = st_v["scan_fast"][0] / st_v["scan_fast"][1]
-        bytes_v = plan_v["tiles"] * (w.N - plan_v["warm_codes"]) * code_bytes
+        bytes_v = plan_v["tiles"] * w.N * code_bytes
         stream_variant = {
             "query_tile": 16, "queries": nq_v, "bound": "hbm", "achieved": round(bytes_v / (ms_v * 1e-3) / 1e9, 1),
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(bytes_v / (ms_v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
             "avg_launch_ms": round(ms_v, 4), "bytes_per_launch": bytes_v,
-            "scan_ms_with_warmup_launch": round((st_v["scan_fast"][0] + st_v.get("scan_fast_warm", (0.0, 0))[0]) / 2, 4),
         }
         del ws_v, qtab_v
 

@@ -101,11 +101,10 @@ size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r);
  * sit in LDS). */
 int dcpq_scan_query_tile(int m);
 /* How scan_candidates(_mode) lays out its work for a problem, for benchmarks and reports (host only, no
- * device work).  info (host pointer, ninfo >= 8) receives: [0] queries per tile, [1] number of tiles,
- * [2] codes covered by the warm-up launch of the single pass (codes 0 .. info[2]; 0 when there is none),
- * [3] workgroups along the codes in that launch, [4] the same for the main launch, [5] codes per
- * workgroup of the main launch (for the three-pass algorithm: codes per wavefront unit), [6] slices of a
- * query's candidate buffer, [7] entries per slice.  [2]..[4], [6], [7] are 0 for the three-pass algorithm. */
+ * device work).  info (host pointer, ninfo >= 6) receives: [0] queries per tile, [1] number of tiles,
+ * [2] workgroups along the codes in the single-pass launch, [3] codes per workgroup (for the three-pass
+ * algorithm: codes per wavefront unit), [4] slices of a query's candidate buffer, [5] entries per slice.
+ * [2], [4], [5] are 0 for the three-pass algorithm. */
 int dcpq_scan_plan(uint64_t n_codes, int m, int nq, uint32_t r, int mode, uint64_t *info, int ninfo);
 int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                          uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,

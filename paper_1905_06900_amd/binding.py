@@ -161,9 +161,9 @@ SCAN_AUTO, SCAN_THREE_PASS, SCAN_TILE16, SCAN_TILE32, SCAN_TILE64 = 0, 1, 2, 3, 
 
 def scan_plan(n_codes: int, m: int, nq: int, r: int, mode: int = SCAN_AUTO) -> dict:
     """How the scan lays out its work for this problem (see dcpq_scan_plan)."""
-    info = (C.c_uint64 * 8)()
-    _check(lib().dcpq_scan_plan(n_codes, m, nq, r, mode, C.cast(info, C.c_void_p), 8))
-    keys = ("query_tile", "tiles", "warm_codes", "warm_blocks", "blocks", "codes_per_block", "slices", "slice_cap")
+    info = (C.c_uint64 * 6)()
+    _check(lib().dcpq_scan_plan(n_codes, m, nq, r, mode, C.cast(info, C.c_void_p), 6))
+    keys = ("query_tile", "tiles", "blocks", "codes_per_block", "slices", "slice_cap")
     return dict(zip(keys, (int(v) for v in info)))
 
 

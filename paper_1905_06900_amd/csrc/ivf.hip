@@ -627,7 +627,7 @@ static int ivf_scan_m(const CodeT *codes, const int64_t *offsets, const int32_t 
     DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist, CodeT>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
                 nunits, qtab, nprobe, r, kIvfSampleStep, nullptr, shist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<sample>");
-    rc = launch_sample_threshold(shist, nq, r, t_cur, st);
+    rc = launch_sample_threshold(shist, nq, r, 0, t_cur, st);     // 0: the sample's own r-th smallest
     if (rc) return rc;
     DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_single_kernel<M, CodeT>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
                 lds_tab + 4 * 64 * 8, codes, units, nunits, qtab, nprobe, r, p.cap, p.upd, p.qflush, t_cur, fcount, chist,

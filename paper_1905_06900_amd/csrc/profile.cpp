@@ -10,7 +10,7 @@ namespace dcpq {
 namespace prof {
 
 static const char *const kNames[kNumStages] = {
-    "small_tables", "scan_hist", "scan_tiecount", "scan_collect", "scan_fast", "scan_fast_warm", "select",
+    "small_tables", "scan_hist", "scan_tiecount", "scan_collect", "scan_fast", "select",
     "full_tables",
     "refine_topk", "ivf", "misc",
 };

@@ -330,23 +330,8 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode)
     p.fast = p.fqt != 0;
     if (p.fast) {
         p.ntiles = static_cast<uint32_t>((Q + p.fqt - 1) / p.fqt);
-        // Every wavefront starts from the bound of the sample and only sees lower bounds a few groups
-        // later, so the more wavefronts start at once, the more candidates above the final bound get
-        // appended.  A first launch with at most 16 workgroups per tile therefore scans a small head of
-        // the array (1/64 of it, at least 256 Ki codes) and leaves a bound that is already tight for
-        // the main launch, whose thousands of wavefronts would otherwise each repeat that start-up.
-        p.warm_codes = 0;
-        if (n_codes >= (1ull << 22)) {
-            uint64_t w = n_codes / 64;
-            if (w < (1ull << 18)) w = 1ull << 18;
-            p.warm_blocks = 16;
-            uint64_t wc = (w + p.warm_blocks - 1) / p.warm_blocks;
-            wc = (wc + 1023) / 1024 * 1024;
-            p.warm_codes_per_block = static_cast<uint32_t>(wc);
-            p.warm_codes = wc * p.warm_blocks;
-        }
-        // main launch: workgroups along the codes, about 8 rounds of the 256 CUs in total, at least 16 Ki codes each
-        const uint64_t rest = n_codes - p.warm_codes;
+        // workgroups along the codes, about 8 rounds of the 256 CUs in total, at least 16 Ki codes each
+        const uint64_t rest = n_codes;
         const uint64_t want = (2048 + p.ntiles - 1) / p.ntiles;
         const uint64_t most = (rest + 16383) / 16384;
         uint64_t fb = want < most ? want : most;
@@ -523,18 +508,16 @@ extern "C" int dcpq_scan_query_tile(int m)
 extern "C" int dcpq_scan_plan(uint64_t n_codes, int m, int nq, uint32_t r, int mode, uint64_t *info, int ninfo)
 {
     clear_error();
-    DCPQ_REQUIRE(info && ninfo >= 8, "scan_plan: info must hold 8 values");
+    DCPQ_REQUIRE(info && ninfo >= 6, "scan_plan: info must hold 6 values");
     DCPQ_REQUIRE(nq >= 1 && n_codes >= 1 && r >= 1, "scan_plan: empty problem");
     if (!m_supported(m)) return fail(DCPQ_EUNSUPPORTED, "scan_plan: m=%d not supported", m);
     const ScanPlan p = plan_scan(n_codes, m, nq, r, mode);
     info[0] = p.fast ? p.fqt : p.qt;
     info[1] = p.fast ? p.ntiles : (static_cast<uint64_t>(nq) + p.qt - 1) / p.qt;
-    info[2] = p.fast ? p.warm_codes : 0;
-    info[3] = p.fast && p.warm_codes ? p.warm_blocks : 0;
-    info[4] = p.fast ? p.fblocks : 0;
-    info[5] = p.fast ? p.codes_per_block : p.unit;
-    info[6] = p.fast ? p.slices : 0;
-    info[7] = p.fast ? p.cap : 0;
+    info[2] = p.fast ? p.fblocks : 0;
+    info[3] = p.fast ? p.codes_per_block : p.unit;
+    info[4] = p.fast ? p.slices : 0;
+    info[5] = p.fast ? p.cap : 0;
     return DCPQ_OK;
 }
 

@@ -131,9 +131,15 @@ __global__ __launch_bounds__(256) void swizzle_tables_kernel(const uint8_t *__re
     *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
 }
 
-// T_cur[q] = bucket of the r-th smallest qd of the sample (255 if the sample holds fewer than r).
+// Starting bucket bound of every query from the histogram of a sample of S of the n codes.
+// The bucket of the sample's r-th smallest qd is a bound that cannot fail (the sample is part of the
+// array), but it lets r / S of all codes through.  The array's r-th smallest qd is about the sample's
+// (r S / n)-th smallest, so the bound starts at the bucket where the sample's cumulative count reaches
+// e + 8 sqrt(e) + 8 with e = r S / n (eight standard deviations of the count above its mean), or r
+// if that is smaller.  Should that bucket hold fewer than r codes of the whole array after all, the
+// selection sees fewer than r appended candidates and has the query redone by the three-pass path.
 __global__ __launch_bounds__(256) void sample_threshold_kernel(const uint32_t *__restrict__ shist, uint32_t r,
-                                                               int *__restrict__ t_cur)
+                                                               uint64_t n_codes, int *__restrict__ t_cur)
 {
     __shared__ uint32_t cum[256];
     const int q = blockIdx.x, b = threadIdx.x;
@@ -145,9 +151,15 @@ __global__ __launch_bounds__(256) void sample_threshold_kernel(const uint32_t *_
         cum[b] += add;
         __syncthreads();
     }
+    uint32_t rs = r;
+    if (n_codes) {                                        // 0: the sample's own r-th smallest
+        const float e = static_cast<float>(r) * static_cast<float>(cum[255]) / static_cast<float>(n_codes);
+        const float want = e + 8.0f * sqrtf(e) + 8.0f;
+        if (want < static_cast<float>(r)) rs = static_cast<uint32_t>(want) + 1u;
+    }
     const uint32_t before = b ? cum[b - 1] : 0u;
-    if (before < r && cum[b] >= r) t_cur[q] = b;
-    if (b == 255 && cum[255] < r) t_cur[q] = 255;
+    if (before < rs && cum[b] >= rs) t_cur[q] = b;
+    if (b == 255 && cum[255] < rs) t_cur[q] = 255;
 }
 
 // Low bytes of the M sub-codes of one code, reordered by residue class: byte (j & 3) * CLS + (j >> 2).
@@ -461,7 +473,7 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
         over = over || c > cap;
         n += c;
     }
-    if (over || n < r) {                        // a slice overflowed (n < r cannot happen: the bound is safe)
+    if (over || n < r) {                        // a slice overflowed, or the starting bound was too low after all
         if (tid == 0) flags[q] = 1;
         return;
     }
@@ -564,17 +576,11 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     // sample histogram -> starting bounds
     int rc = launch_sample_hist(codes, n_codes, M, qtab, nq, r, shist, p, st);
     if (rc) return rc;
-    rc = launch_sample_threshold(shist, nq, r, t_cur, st);
+    rc = launch_sample_threshold(shist, nq, r, n_codes, t_cur, st);
     if (rc) return rc;
     // the scan
-    if (p.warm_codes) {
-        DCPQ_LAUNCH(kStageScanFastWarm, st, (scan_fast_kernel<M, QT, WAVES>), dim3(p.ntiles, p.warm_blocks),
-                    dim3(WAVES * 64), C::LDS_BYTES, codes, static_cast<uint64_t>(0), p.warm_codes,
-                    p.warm_codes_per_block, qsw, nq, r, p.slices, p.cap, p.upd, p.qflush, t_cur, fcount, chist, fkeys);
-        DCPQ_CHECK_LAUNCH("scan_fast_kernel");
-    }
     DCPQ_LAUNCH(kStageScanFast, st, (scan_fast_kernel<M, QT, WAVES>), dim3(p.ntiles, p.fblocks), dim3(WAVES * 64),
-                C::LDS_BYTES, codes, p.warm_codes, n_codes, p.codes_per_block, qsw, nq, r, p.slices, p.cap, p.upd,
+                C::LDS_BYTES, codes, static_cast<uint64_t>(0), n_codes, p.codes_per_block, qsw, nq, r, p.slices, p.cap, p.upd,
                 p.qflush, t_cur, fcount, chist, fkeys);
     DCPQ_CHECK_LAUNCH("scan_fast_kernel");
     // exact selection + list of queries to redo
@@ -585,9 +591,9 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     return DCPQ_OK;
 }
 
-int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, int *t_cur, hipStream_t st)
+int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, uint64_t n_codes, int *t_cur, hipStream_t st)
 {
-    DCPQ_LAUNCH(kStageSelect, st, sample_threshold_kernel, dim3(nq), dim3(256), 0, shist, r, t_cur);
+    DCPQ_LAUNCH(kStageSelect, st, sample_threshold_kernel, dim3(nq), dim3(256), 0, shist, r, n_codes, t_cur);
     DCPQ_CHECK_LAUNCH("sample_threshold_kernel");
     return DCPQ_OK;
 }

@@ -37,10 +37,8 @@ struct ScanPlan {
     bool fast;
     uint32_t fqt;             // queries per tile
     uint32_t ntiles;
-    uint32_t fblocks;         // workgroups along the code axis (main launch: codes warm_codes .. n_codes)
+    uint32_t fblocks;         // workgroups along the code axis
     uint32_t codes_per_block;
-    uint64_t warm_codes;      // codes 0 .. warm_codes go first, in a launch of their own (0: no such launch)
-    uint32_t warm_blocks, warm_codes_per_block;
     uint32_t slices;          // slices per query: min(kFastSlices, fblocks)
     uint32_t cap;             // candidate-buffer entries per query and slice
     uint32_t upd;             // appended candidates between two bound updates
@@ -73,7 +71,8 @@ int launch_scan_fast(const uint16_t *codes, uint64_t n_codes, int m, const uint8
                      hipStream_t st);
 
 // Steps of the single-pass selection that the inverted-list variant reuses.
-int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, int *t_cur, hipStream_t st);
+// n_codes: size of the array the sample was drawn from (the sample's own size is the histogram's total)
+int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, uint64_t n_codes, int *t_cur, hipStream_t st);
 int launch_fast_select(const uint64_t *keys, const uint32_t *count, const uint32_t *chist, int nq, uint32_t r,
                        uint32_t nslices, uint32_t cap, uint32_t sortcap, uint64_t *spill, uint32_t *cand_id,
                        uint8_t *cand_qd, uint32_t *flags, hipStream_t st);

@@ -57,24 +57,20 @@ def test_host_side_queries_need_no_gpu(lib):
 
 
 def test_scan_plan_covers_every_code_once_and_picks_the_tile_from_the_batch():
-    """Host-side planning of the scan: the warm-up launch and the main launch together cover codes
-    0 .. N without overlap, and m = 8 takes the smallest tile that holds the batch."""
+    """Host-side planning of the scan: the workgroups of the single pass cover codes 0 .. N without
+    overlap, and m = 8 takes the smallest tile that holds the batch."""
     from paper_1905_06900_amd import binding
     for n, nq, r in [(100_000_000, 4096, 4000), (100_000_000, 16, 4000), (5_000_000, 100, 1000), (70_001, 5, 333),
                      (1, 1, 1)]:
         p = binding.scan_plan(n, 8, nq, r)
         assert p["query_tile"] == (16 if nq <= 16 else 32 if nq <= 32 else 64)
         assert p["tiles"] == -(-nq // p["query_tile"])
-        assert p["warm_codes"] < n or n < (1 << 22)
-        rest = n - p["warm_codes"]
-        assert (p["blocks"] - 1) * p["codes_per_block"] < rest <= p["blocks"] * p["codes_per_block"]
+        assert (p["blocks"] - 1) * p["codes_per_block"] < n <= p["blocks"] * p["codes_per_block"]
         assert 1 <= p["slices"] <= 16 and p["slices"] * p["slice_cap"] >= 10 * r
-        if n < (1 << 22):
-            assert p["warm_codes"] == 0
     forced = binding.scan_plan(100_000_000, 8, 4096, 4000, binding.SCAN_TILE16)
     assert forced["query_tile"] == 16 and forced["tiles"] == 256
     three = binding.scan_plan(70_001, 8, 5, 333, binding.SCAN_THREE_PASS)
-    assert three["blocks"] == 0 and three["warm_codes"] == 0
+    assert three["blocks"] == 0 and three["slices"] == 0
     with pytest.raises(binding.DcpqError):
         binding.scan_plan(1000, 3, 5, 10)
 

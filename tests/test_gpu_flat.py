@@ -248,14 +248,41 @@ def test_scan_random_shapes():
 
 
 @pytest.mark.parametrize("Q", [5, 70])
-def test_scan_with_the_warm_up_launch(Q):
-    """From 4 Mi codes on, the single pass first scans a head of the array with few workgroups; ids must stay
-    global and every code must be scanned exactly once (all tiles, ragged last workgroup)."""
+def test_scan_large_array_estimated_starting_bound(Q):
+    """On a large array the single pass starts from a bound estimated from a sample (the sample's count
+    scaled to the array), not from the sample's own r-th smallest; ids stay global, every code is scanned
+    exactly once (all tiles, ragged last workgroup)."""
     rng = np.random.default_rng(77 + Q)
     N, r = 4_200_003, 700
     codes = rng.integers(0, 65536, size=(N, 8)).astype(np.uint16)
     qtab = rng.integers(0, 40, size=(Q, 8, 256)).astype(np.uint8)
-    plan = binding.scan_plan(N, 8, Q, r)
-    assert plan["warm_codes"] > 0
-    print("scan warm-up case N=%d Q=%d: warm-up %d codes" % (N, Q, plan["warm_codes"]), flush=True)
+    print("scan large-array case N=%d Q=%d r=%d" % (N, Q, r), flush=True)
     scan_vs_oracle(codes, qtab, r, modes=(binding.SCAN_AUTO, binding.SCAN_TILE16, binding.SCAN_TILE64))
+
+
+def test_scan_estimated_bound_too_low_is_redone():
+    """The estimated starting bound fails when the sample misrepresents the array: here the near codes sit
+    exactly in the runs of 256 codes, evenly spread, that the sample reads, so the estimate puts r codes
+    below a bucket that holds fewer in the whole array.  Such queries (the even ones here; the odd ones'
+    tables spread the near codes over half as many buckets, so their first bucket does hold r) must come
+    out exact all the same: the selection sees fewer than r candidates and has them redone."""
+    rng = np.random.default_rng(5150)
+    N, r, Q = 4_200_003, 700, 6
+    runs = 65536 // 256
+    stride = N // runs
+    pos = (np.arange(runs, dtype=np.int64)[:, None] * stride + np.arange(256)[None, :]).ravel()
+    codes = rng.integers(0, 65536, size=(N, 8)).astype(np.uint16)
+    low0 = rng.integers(200, 256, size=N)
+    low0[pos] = rng.integers(0, 100, size=pos.size)
+    codes[:, 0] = (codes[:, 0] & 0xFF00) | low0.astype(np.uint16)
+    qtab = np.zeros((Q, 8, 256), dtype=np.uint8)
+    qtab[0::2, 0, :] = np.arange(256, dtype=np.uint8)[None, :]            # qd = the low byte: ~655 codes per bucket
+    qtab[1::2, 0, :] = (np.arange(256) // 2).astype(np.uint8)[None, :]    # ~1310 per bucket
+    binding.profile_enable(True)
+    try:
+        scan_vs_oracle(codes, qtab, r, modes=(binding.SCAN_AUTO,))
+        stages = binding.profile_read()
+    finally:
+        binding.profile_enable(False)
+    print("redo stages (ms, launches): hist+sample %s, tie count %s, collect %s"
+          % (stages.get("scan_hist"), stages.get("scan_tiecount"), stages.get("scan_collect")), flush=True)
