@@ -2,7 +2,8 @@
 
 The single-pass scan keeps the tables of a tile of 16, 32 or 64 queries in LDS and streams the codes
 once per tile, so the tile trades LDS lookups per byte of code stream against passes over the stream.
-For every (queries, tile, r) this prints one JSON line with the time of the scan kernels, the
+For every (queries, tile, r) this prints one JSON line with the time of the scan kernel (and, beside it, of
+the sample histogram and of the final selection), the
 (query, code) pairs per second, and the code stream rate = passes x N x bytes per code / time, which
 is what the kernel loads (from HBM, or from the L2 when several tiles walk the same codes together).
 
@@ -61,13 +62,15 @@ def main() -> int:
                 st = binding.profile_read()
                 binding.profile_enable(False)
                 ms = st["scan_fast"][0] / args.reps
+                other = {k: round(st[k][0] / args.reps, 4) for k in ("scan_hist", "select") if k in st}
                 passes = -(-nq // tile)
                 stream = passes * w.N * code_bytes / (ms * 1e-3) / 1e9
                 print(json.dumps({
                     "workload": w.name, "N": w.N, "queries": nq, "r": r, "query_tile": tile, "passes": passes,
                     "scan_ms": round(ms, 4), "pairs_per_s": round(w.N * nq / (ms * 1e-3), 1),
                     "code_stream_GBs": round(stream, 1), "frac_of_hbm_peak": round(stream / HBM_PEAK_GBS, 4),
-                    "queries_per_s_scan_only": round(nq / (ms * 1e-3), 1),
+                    "queries_per_s_scan_only": round(nq / (ms * 1e-3), 1), "sample_and_redo_ms": other.get("scan_hist"),
+                    "select_ms": other.get("select"),
                 }), flush=True)
     return 0
 

@@ -451,20 +451,38 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     flush();
 }
 
+// Largest bucket the selection orders by counting ranks (the work grows with the square of the bucket
+// size); queries with a larger bucket at or below the bound go through the bitonic network instead.
+constexpr uint32_t kRankBucket = 2048;
+constexpr uint32_t kRankPad = 1024;          // room for rounding every bucket up to a multiple of 4 ids
+constexpr size_t kSelectLdsMost = 96 * 1024;
+
+// LDS of the rank-counting selection: ids (uint32) and their buckets (uint8) for sortcap + kRankPad entries.
+static size_t rank_lds_bytes(uint32_t sortcap) { return 5 * (static_cast<size_t>(sortcap) + kRankPad); }
+
 // One workgroup per query: pick the exact r smallest (qd, id) out of the appended superset.
-// flags[q] = 1 when the query must be redone (buffer overflow, or a tie bucket too large to sort).
+// flags[q] = 1 when the query must be redone (buffer overflow, fewer than r candidates, or more
+// candidates at or below the bound than the sort area holds).
+// The exact per-bucket counts of the appended candidates give every bucket its place in the output.
+// The candidates at or below the bound are therefore dealt into their buckets (a counting sort by qd)
+// and ordered by id inside the bucket: a candidate's rank is the number of ids of its bucket below its
+// own, counted four ids per LDS read (buckets start at multiples of four and are filled up with the
+// id 2^32 - 1, which no code has).  With r spread over tens of buckets this is several times cheaper
+// than a sorting network over the whole set, which remains for queries with a very large bucket.
 __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__restrict__ keys,
                                                           const uint32_t *__restrict__ count,
                                                           const uint32_t *__restrict__ chist, uint32_t r, uint32_t nslices,
-                                                          uint32_t cap, uint32_t sortcap, int use_lds,
+                                                          uint32_t cap, uint32_t sortcap, int use_lds, int rank_ok,
                                                           uint64_t *__restrict__ spill,
                                                           uint32_t *__restrict__ cand_id,
                                                           uint8_t *__restrict__ cand_qd,
                                                           uint32_t *__restrict__ flags)
 {
     extern __shared__ __align__(16) uint8_t smem[];
-    __shared__ uint32_t cum[256];
-    __shared__ uint32_t s_t, s_keep, s_pos;
+    __shared__ uint32_t cum[256];                // inclusive prefix of the bucket counts
+    __shared__ uint32_t pcum[256];               // the same with every count rounded up to a multiple of 4
+    __shared__ uint32_t cursor[256];
+    __shared__ uint32_t s_t, s_keep, s_pos, s_big;
     const int q = blockIdx.x, tid = threadIdx.x;
     uint32_t n = 0;
     bool over = false;
@@ -477,19 +495,24 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
         if (tid == 0) flags[q] = 1;
         return;
     }
-    if (tid < 256) cum[tid] = chist[static_cast<size_t>(q) * 256 + tid];
-    if (tid == 0) { s_t = 255; s_keep = n; s_pos = 0; }
+    uint32_t mine = 0;
+    if (tid < 256) {
+        mine = chist[static_cast<size_t>(q) * 256 + tid];
+        cum[tid] = mine; pcum[tid] = (mine + 3u) & ~3u; cursor[tid] = 0;
+    }
+    if (tid == 0) { s_t = 255; s_keep = n; s_pos = 0; s_big = 0; }
     __syncthreads();
     for (int off = 1; off < 256; off <<= 1) {
-        uint32_t add = 0;
-        if (tid < 256 && tid >= off) add = cum[tid - off];
+        uint32_t add = 0, padd = 0;
+        if (tid < 256 && tid >= off) { add = cum[tid - off]; padd = pcum[tid - off]; }
         __syncthreads();
-        if (tid < 256) cum[tid] += add;
+        if (tid < 256) { cum[tid] += add; pcum[tid] += padd; }
         __syncthreads();
     }
     if (tid < 256) {
         const uint32_t before = tid ? cum[tid - 1] : 0u;
         if (before < r && cum[tid] >= r) { s_t = tid; s_keep = cum[tid]; }
+        if (before < r && mine > kRankBucket) s_big = 1;         // a large bucket at or below the bound
     }
     __syncthreads();
     const uint32_t T = s_t, keep = s_keep;
@@ -497,9 +520,48 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
         if (tid == 0) flags[q] = 1;
         return;
     }
+    if (rank_ok && !s_big) {
+        uint32_t *ids = reinterpret_cast<uint32_t *>(smem);
+        uint8_t *qds = smem + 4 * (static_cast<size_t>(sortcap) + kRankPad);
+        const uint32_t ptotal = pcum[T];                         // <= keep + 3 * 256 <= sortcap + kRankPad
+        for (uint32_t t = tid; t < ptotal; t += 1024) ids[t] = 0xFFFFFFFFu;
+        __syncthreads();
+        for (uint32_t sl = 0; sl < nslices; ++sl) {
+            const size_t cell = static_cast<size_t>(q) * nslices + sl;
+            const uint32_t c = count[cell];
+            for (uint32_t t = tid; t < c; t += 1024) {
+                const uint64_t key = keys[cell * cap + t];
+                const uint32_t qd = static_cast<uint32_t>(key >> 32);
+                if (qd <= T) {
+                    const uint32_t pos = (qd ? pcum[qd - 1] : 0u) + atomicAdd(&cursor[qd], 1u);
+                    if (pos < pcum[qd]) { ids[pos] = static_cast<uint32_t>(key); qds[pos] = static_cast<uint8_t>(qd); }
+                }
+            }
+        }
+        __syncthreads();
+        for (uint32_t t = tid; t < ptotal; t += 1024) {
+            const uint32_t id = ids[t];
+            if (id == 0xFFFFFFFFu) continue;                     // filler
+            const uint32_t qd = qds[t];
+            const uint32_t lo4 = (qd ? pcum[qd - 1] : 0u) >> 2, hi4 = pcum[qd] >> 2;
+            const uint4 *v4 = reinterpret_cast<const uint4 *>(ids);
+            uint32_t rank = 0;
+            for (uint32_t k = lo4; k < hi4; ++k) {
+                const uint4 v = v4[k];
+                rank += (v.x < id ? 1u : 0u) + (v.y < id ? 1u : 0u) + (v.z < id ? 1u : 0u) + (v.w < id ? 1u : 0u);
+            }
+            const uint32_t out = (qd ? cum[qd - 1] : 0u) + rank;
+            if (out < r) {
+                cand_id[static_cast<size_t>(q) * r + out] = id;
+                cand_qd[static_cast<size_t>(q) * r + out] = static_cast<uint8_t>(qd);
+            }
+        }
+        if (tid == 0) flags[q] = 0;
+        return;
+    }
+    uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(q) * sortcap;
     uint32_t np2 = 1;
     while (np2 < keep) np2 <<= 1;
-    uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(q) * sortcap;
     for (uint32_t t = tid; t < np2; t += 1024) a[t] = ~0ull;
     __syncthreads();
     for (uint32_t sl = 0; sl < nslices; ++sl) {
@@ -606,12 +668,15 @@ int launch_fast_select(const uint64_t *keys, const uint32_t *count, const uint32
     if (!attr_done) {
         DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_select_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           static_cast<int>(sizeof(uint64_t) * kSortLdsKeys)));
+                                           static_cast<int>(kSelectLdsMost)));
         attr_done = true;
     }
     const int use_lds = sortcap <= kSortLdsKeys;
-    DCPQ_LAUNCH(kStageSelect, st, fast_select_kernel, dim3(nq), dim3(1024), use_lds ? sizeof(uint64_t) * sortcap : 0,
-                keys, count, chist, r, nslices, cap, sortcap, use_lds, spill, cand_id, cand_qd, flags);
+    const int rank_ok = rank_lds_bytes(sortcap) <= kSelectLdsMost;
+    size_t lds = use_lds ? sizeof(uint64_t) * sortcap : 0;
+    if (rank_ok && rank_lds_bytes(sortcap) > lds) lds = rank_lds_bytes(sortcap);
+    DCPQ_LAUNCH(kStageSelect, st, fast_select_kernel, dim3(nq), dim3(1024), lds,
+                keys, count, chist, r, nslices, cap, sortcap, use_lds, rank_ok, spill, cand_id, cand_qd, flags);
     DCPQ_CHECK_LAUNCH("fast_select_kernel");
     return DCPQ_OK;
 }
