@@ -526,10 +526,12 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
         const uint32_t ptotal = pcum[T];                         // <= keep + 3 * 256 <= sortcap + kRankPad
         for (uint32_t t = tid; t < ptotal; t += 1024) ids[t] = 0xFFFFFFFFu;
         __syncthreads();
-        for (uint32_t sl = 0; sl < nslices; ++sl) {
+        // one wavefront per slice at a time, so that the slices' loads are in flight together
+        for (uint32_t sl = tid >> 6; sl < nslices; sl += 16) {
             const size_t cell = static_cast<size_t>(q) * nslices + sl;
             const uint32_t c = count[cell];
-            for (uint32_t t = tid; t < c; t += 1024) {
+#pragma unroll 4
+            for (uint32_t t = tid & 63; t < c; t += 64) {
                 const uint64_t key = keys[cell * cap + t];
                 const uint32_t qd = static_cast<uint32_t>(key >> 32);
                 if (qd <= T) {
