@@ -1,13 +1,19 @@
 // Pass two of Alg. 3 (Sec. 3.3, "Refine step"): exact asymmetric distance (Eq. 2) of every
 // candidate from the full tables, then the result set of the k smallest by (distance, id).
-// One workgroup per query: the r keys (distance bits, id) are built and sorted in LDS (or in a
-// global spill area when they do not fit) and the first k are written out.  Squared distances
-// are non-negative, so their fp32 bit patterns order like the values.
+// One workgroup per query: the r keys (distance bits, id) are built in LDS (or in a global spill
+// area when they do not fit).  Only k << r of them are wanted, so the keys are first cut down by
+// value: a histogram over 2048 equal steps between the smallest and the largest distance locates
+// the step that holds the k-th smallest, the keys up to that step (a superset of the k smallest,
+// usually little more than k) are gathered and only those are sorted, by the exact (distance, id)
+// key.  When that superset is large (many equal distances) all r keys are sorted instead.
+// Squared distances are non-negative, so their fp32 bit patterns order like the values.
 #include "common.h"
 
 namespace dcpq {
 
 constexpr uint32_t kRefineLdsKeys = 8192;   // 64 KiB of keys
+constexpr uint32_t kRefineSteps = 2048;     // histogram steps between the smallest and the largest distance
+constexpr uint32_t kRefineFew = 1024;       // keys gathered and sorted when the cut leaves no more than this
 
 static uint32_t next_pow2_r(uint32_t x)
 {
@@ -59,7 +65,84 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
         }
         a[t] = key;
     }
-    bitonic_sort_keys(a, n_pow2);
+    __syncthreads();
+    // ---- cut down by value ----------------------------------------------------------------
+    __shared__ uint32_t hist[kRefineSteps];
+    __shared__ uint64_t few[kRefineFew];
+    __shared__ uint32_t s_lo, s_hi, s_step, s_n, wsum[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t lo = 0xFFFFFFFFu, hi = 0;
+    for (uint32_t t = tid; t < r; t += blockDim.x) {
+        const uint64_t key = a[t];
+        if (key != ~0ull) {
+            const uint32_t d = static_cast<uint32_t>(key >> 32);
+            lo = min(lo, d); hi = max(hi, d);
+        }
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        lo = min(lo, static_cast<uint32_t>(__shfl_xor(static_cast<int>(lo), d)));
+        hi = max(hi, static_cast<uint32_t>(__shfl_xor(static_cast<int>(hi), d)));
+    }
+    if (tid == 0) { s_lo = 0xFFFFFFFFu; s_hi = 0; s_step = kRefineSteps; s_n = 0; }
+    for (uint32_t t = tid; t < kRefineSteps; t += blockDim.x) hist[t] = 0;
+    __syncthreads();
+    if (lane == 0) { atomicMin(&s_lo, lo); atomicMax(&s_hi, hi); }
+    __syncthreads();
+    const float dlo = __uint_as_float(s_lo), dhi = __uint_as_float(s_hi);
+    const float scale = static_cast<float>(kRefineSteps) / (dhi - dlo);
+    // step of a distance: non-decreasing in the distance, so "step <= s" keeps every key below some value
+    auto step_of = [&](uint64_t key) -> uint32_t {
+        const float x = (__uint_as_float(static_cast<uint32_t>(key >> 32)) - dlo) * scale;
+        return x < static_cast<float>(kRefineSteps - 1) ? static_cast<uint32_t>(x) : kRefineSteps - 1;
+    };
+    bool all = !(scale > 0.0f) || !(scale < INFINITY);       // one value only, or nothing finite to scale by
+    if (!all) {
+        for (uint32_t t = tid; t < r; t += blockDim.x) {
+            const uint64_t key = a[t];
+            if (key != ~0ull) atomicAdd(&hist[step_of(key)], 1u);
+        }
+        __syncthreads();
+        // thread t owns steps 2t and 2t + 1 (1024 threads); inclusive prefix over the threads
+        const uint32_t h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+        uint32_t incl = h0 + h1;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t other = __shfl(incl, lane >= d ? lane - d : lane);
+            if (lane >= d) incl += other;
+        }
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        uint32_t before = incl - (h0 + h1);
+        for (int w2 = 0; w2 < wave; ++w2) before += wsum[w2];
+        if (before < k && before + h0 + h1 >= k) {                // exactly one thread, if k keys exist at all
+            const bool first = before + h0 >= k;
+            s_step = first ? 2 * tid : 2 * tid + 1;
+            s_n = first ? before + h0 : before + h0 + h1;
+        }
+        __syncthreads();
+        all = s_step == kRefineSteps || s_n > kRefineFew;          // fewer than k real keys, or too many to gather
+    }
+    if (!all) {
+        const uint32_t step = s_step, nkeep = s_n;
+        uint32_t nf = 1;
+        while (nf < nkeep) nf <<= 1;
+        __syncthreads();
+        if (tid == 0) s_n = 0;
+        for (uint32_t t = tid; t < nf; t += blockDim.x) few[t] = ~0ull;
+        __syncthreads();
+        for (uint32_t t = tid; t < r; t += blockDim.x) {
+            const uint64_t key = a[t];
+            if (key != ~0ull && step_of(key) <= step) {
+                const uint32_t pos = atomicAdd(&s_n, 1u);
+                if (pos < nf) few[pos] = key;
+            }
+        }
+        bitonic_sort_keys(few, nf);
+        a = few;
+    } else {
+        bitonic_sort_keys(a, n_pow2);
+    }
     for (uint32_t t = threadIdx.x; t < k; t += blockDim.x) {
         const uint64_t key = a[t];
         ids[static_cast<size_t>(q) * k + t] = static_cast<uint32_t>(key);
