@@ -69,12 +69,15 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const int q = q0 + mt * 16 + lr;
-            a[mt] = (kin && q < nq) ? static_cast<double>(queries[static_cast<size_t>(q) * D + j * dsub + k]) : 0.0;
+            // unconditional loads (clamped addresses): guarded ones would each be waited for on their own
+            const float av = queries[static_cast<size_t>(q < nq ? q : nq - 1) * D + j * dsub + (kin ? k : dsub - 1)];
+            a[mt] = (kin && q < nq) ? static_cast<double>(av) : 0.0;
         }
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
             const int c = cw + lr * 4 + nt;
-            b[nt] = (kin && c < ncent) ? static_cast<double>(cbj[static_cast<size_t>(c) * dsub + k]) : 0.0;
+            const float bv = cbj[static_cast<size_t>(c < ncent ? c : ncent - 1) * dsub + (kin ? k : dsub - 1)];
+            b[nt] = (kin && c < ncent) ? static_cast<double>(bv) : 0.0;
         }
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
@@ -113,31 +116,32 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
 
 // Same computation for sub-spaces of at most 64 dimensions, laid out for the store stream: a workgroup
 // keeps its 256 centroids (as MFMA B operands, 4 * KS doubles per lane, KS = ceil(dsub / 4)) and their
-// norms in registers and walks kBigTileQ queries in sub-tiles of 16, so the codebook is read once per
-// 128 queries and every wavefront alternates a few MFMAs with 16 KiB of table stores.
-constexpr int kBigTileQ = 128;
-
-template <int KS>
+// norms in registers and walks TQ queries in sub-tiles of 16, so the codebook is read once per
+// TQ queries and every wavefront alternates a few MFMAs with 16 KiB of table stores.  Loading the B
+// operands is a strided, latency-bound read (one centroid per lane and component); for wide sub-spaces
+// (many components, and 64 cycles of MFMA per component step) TQ is larger so that it stays a small
+// part of a workgroup's time.
+template <int KS, int TQ>
 __global__ __launch_bounds__(256) void full_tables_stream_kernel(const float *__restrict__ queries, int nq,
                                                                  const float *__restrict__ cb, int m, int dsub,
                                                                  int ncent, float *__restrict__ tables)
 {
-    __shared__ double ny[kBigTileQ];
+    __shared__ double ny[TQ];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = blockIdx.z;
-    const int q0 = blockIdx.y * kBigTileQ;
+    const int q0 = blockIdx.y * TQ;
     const int c0 = blockIdx.x * kTileC;
     const int D = m * dsub;
     const float *cbj = cb + static_cast<size_t>(j) * ncent * dsub;
     const int lr = lane & 15, lk = lane >> 4;
 
-    if (tid < kBigTileQ) {                               // query norms in fp64
+    for (int ql = tid; ql < TQ; ql += 256) {             // query norms in fp64
         double sy = 0.0;
-        if (q0 + tid < nq) {
-            const float *y = queries + static_cast<size_t>(q0 + tid) * D + j * dsub;
+        if (q0 + ql < nq) {
+            const float *y = queries + static_cast<size_t>(q0 + ql) * D + j * dsub;
             for (int t = 0; t < dsub; ++t) { const double v = y[t]; sy += v * v; }
         }
-        ny[tid] = sy;
+        ny[ql] = sy;
     }
 
     // B operands: lane (lr, lk) holds components 4 * ks + lk of centroids cw + 4 * lr + nt
@@ -150,7 +154,9 @@ __global__ __launch_bounds__(256) void full_tables_stream_kernel(const float *__
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
             const int c = cw + lr * 4 + nt;
-            b[ks][nt] = (k < dsub && c < ncent) ? static_cast<double>(cbj[static_cast<size_t>(c) * dsub + k]) : 0.0;
+            // the load itself is unconditional (clamped address): a guarded load would be waited for on its own
+            const float bv = cbj[static_cast<size_t>(c < ncent ? c : ncent - 1) * dsub + (k < dsub ? k : dsub - 1)];
+            b[ks][nt] = (k < dsub && c < ncent) ? static_cast<double>(bv) : 0.0;
             nc[nt] += b[ks][nt] * b[ks][nt];
         }
     }
@@ -163,7 +169,7 @@ __global__ __launch_bounds__(256) void full_tables_stream_kernel(const float *__
 
     const int cl = wave * 64 + lr * 4;                   // this lane's 4 centroids within the tile
     const bool vec_ok = c0 + cl + 3 < ncent && (ncent & 3) == 0;
-    for (int mt = 0; mt < kBigTileQ / 16; ++mt) {
+    for (int mt = 0; mt < TQ / 16; ++mt) {
         if (q0 + mt * 16 >= nq) break;                   // uniform
         const int qa = q0 + mt * 16 + lr;
         double4_t acc[4];
@@ -173,7 +179,8 @@ __global__ __launch_bounds__(256) void full_tables_stream_kernel(const float *__
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int k = 4 * ks + lk;
-            a[ks] = (k < dsub && qa < nq) ? static_cast<double>(queries[static_cast<size_t>(qa) * D + j * dsub + k]) : 0.0;
+            const float av = queries[static_cast<size_t>(qa < nq ? qa : nq - 1) * D + j * dsub + (k < dsub ? k : dsub - 1)];
+            a[ks] = (k < dsub && qa < nq) ? static_cast<double>(av) : 0.0;
         }
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
@@ -203,12 +210,12 @@ __global__ __launch_bounds__(256) void full_tables_stream_kernel(const float *__
     }
 }
 
-template <int KS>
+template <int KS, int TQ>
 static void launch_stream(const float *queries, int nq, const float *codebooks, int m, int dsub, int ncent,
                           float *tables, int stage, hipStream_t st)
 {
-    const dim3 grid((ncent + kTileC - 1) / kTileC, (nq + kBigTileQ - 1) / kBigTileQ, m);
-    DCPQ_LAUNCH(stage, st, (full_tables_stream_kernel<KS>), grid, dim3(256), 0, queries, nq, codebooks, m, dsub, ncent,
+    const dim3 grid((ncent + kTileC - 1) / kTileC, (nq + TQ - 1) / TQ, m);
+    DCPQ_LAUNCH(stage, st, (full_tables_stream_kernel<KS, TQ>), grid, dim3(256), 0, queries, nq, codebooks, m, dsub, ncent,
                 tables);
 }
 
@@ -217,10 +224,10 @@ int launch_distance_tables(const float *queries, int nq, const float *codebooks,
 {
     if (nq == 0) return DCPQ_OK;
     const int ks = (dsub + 3) / 4;
-    if (ks <= 3) launch_stream<3>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
-    else if (ks <= 4) launch_stream<4>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
-    else if (ks <= 8) launch_stream<8>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
-    else if (ks <= 16) launch_stream<16>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
+    if (ks <= 3) launch_stream<3, 128>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
+    else if (ks <= 4) launch_stream<4, 128>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
+    else if (ks <= 8) launch_stream<8, 256>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
+    else if (ks <= 16) launch_stream<16, 512>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
     else {
         const dim3 grid((ncent + kTileC - 1) / kTileC, (nq + kTileQ - 1) / kTileQ, m);
         DCPQ_LAUNCH(stage, st, full_tables_kernel, grid, dim3(256), 0, queries, nq, codebooks, m, dsub, ncent, tables);
