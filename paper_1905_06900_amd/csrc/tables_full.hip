@@ -28,30 +28,12 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
                                                           int ncent, float *__restrict__ tables)
 {
     __shared__ double ny[kTileQ];
-    __shared__ double nc[kTileC];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int j = blockIdx.z;
     const int q0 = blockIdx.y * kTileQ;
     const int c0 = blockIdx.x * kTileC;
     const int D = m * dsub;
     const float *cbj = cb + static_cast<size_t>(j) * ncent * dsub;
-
-    {   // squared norms in fp64: one centroid per thread, one query per thread of wave 0
-        double s = 0.0;
-        if (c0 + tid < ncent) {
-            const float *c = cbj + static_cast<size_t>(c0 + tid) * dsub;
-            for (int t = 0; t < dsub; ++t) { const double v = c[t]; s += v * v; }
-        }
-        nc[tid] = s;
-        if (tid < kTileQ) {
-            double sy = 0.0;
-            if (q0 + tid < nq) {
-                const float *y = queries + static_cast<size_t>(q0 + tid) * D + j * dsub;
-                for (int t = 0; t < dsub; ++t) { const double v = y[t]; sy += v * v; }
-            }
-            ny[tid] = sy;
-        }
-    }
 
     constexpr int MT = kTileQ / 16;
     double4_t acc[MT][4];
@@ -62,33 +44,63 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
 
     const int lr = lane & 15, lk = lane >> 4;
     const int cw = c0 + wave * 64;                     // first centroid of this wavefront
-    for (int k0 = 0; k0 < dsub; k0 += 4) {
-        const int k = k0 + lk;
-        const bool kin = k < dsub;
-        double a[MT], b[4];
+    // Operands of component step k0 + 4 are loaded while the MFMAs of step k0 run.  The loads are
+    // unconditional (clamped addresses): guarded ones would each be waited for on their own.
+    float av[MT], bv[4];
+    double na[MT], nb[4] = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) na[mt] = 0.0;
+    auto load_step = [&](int k0) {
+        const int k = k0 + lk < dsub ? k0 + lk : dsub - 1;
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
             const int q = q0 + mt * 16 + lr;
-            // unconditional loads (clamped addresses): guarded ones would each be waited for on their own
-            const float av = queries[static_cast<size_t>(q < nq ? q : nq - 1) * D + j * dsub + (kin ? k : dsub - 1)];
-            a[mt] = (kin && q < nq) ? static_cast<double>(av) : 0.0;
+            av[mt] = queries[static_cast<size_t>(q < nq ? q : nq - 1) * D + j * dsub + k];
         }
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
             const int c = cw + lr * 4 + nt;
-            const float bv = cbj[static_cast<size_t>(c < ncent ? c : ncent - 1) * dsub + (kin ? k : dsub - 1)];
-            b[nt] = (kin && c < ncent) ? static_cast<double>(bv) : 0.0;
+            bv[nt] = cbj[static_cast<size_t>(c < ncent ? c : ncent - 1) * dsub + k];
         }
+    };
+    load_step(0);
+    for (int k0 = 0; k0 < dsub; k0 += 4) {
+        const bool kin = k0 + lk < dsub;
+        double a[MT], b[4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) a[mt] = (kin && q0 + mt * 16 + lr < nq) ? static_cast<double>(av[mt]) : 0.0;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) b[nt] = (kin && cw + lr * 4 + nt < ncent) ? static_cast<double>(bv[nt]) : 0.0;
+        if (k0 + 4 < dsub) load_step(k0 + 4);            // uniform
+        // squared norms in fp64 from the operands themselves (this lane's share of the components)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) na[mt] += a[mt] * a[mt];
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) nb[nt] += b[nt] * b[nt];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
                 acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
     }
-    __syncthreads();   // norms visible
+    // sum the four component residues: lane (lr, *) then holds the norms of queries q0 + 16 mt + lr and of
+    // its own four centroids; the queries' norms go through LDS, because the outputs of a lane belong to
+    // other queries than its A operands
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        na[mt] += __shfl_xor(na[mt], 16);
+        na[mt] += __shfl_xor(na[mt], 32);
+        if (wave == 0 && lk == 0) ny[mt * 16 + lr] = na[mt];
+    }
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+        nb[nt] += __shfl_xor(nb[nt], 16);
+        nb[nt] += __shfl_xor(nb[nt], 32);
+    }
+    __syncthreads();   // query norms visible
 
     const int cl = wave * 64 + lr * 4;                 // this lane's 4 centroids within the tile
-    const double n0 = nc[cl], n1 = nc[cl + 1], n2 = nc[cl + 2], n3 = nc[cl + 3];
+    const double n0 = nb[0], n1 = nb[1], n2 = nb[2], n3 = nb[3];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
