@@ -34,6 +34,8 @@ struct IvfUnit {
 // dist: [nq][nlist] fp32 squared distances.  One workgroup per query, 4-level radix select on the
 // bit patterns (non-negative floats order like their bits), ties at the cut taken in id order.
 // ------------------------------------------------------------------------------------------------
+constexpr uint32_t kProbeSteps = 2048;   // histogram steps of the cut by value (two per thread)
+
 __global__ __launch_bounds__(1024) void ivf_select_probe_kernel(const float *__restrict__ dist, int nlist, int nprobe,
                                                                int32_t *__restrict__ probe)
 {
@@ -43,6 +45,82 @@ __global__ __launch_bounds__(1024) void ivf_select_probe_kernel(const float *__r
     __shared__ uint64_t sel[kIvfMaxProbe * 2];
     const int q = blockIdx.x, tid = threadIdx.x;
     const uint32_t *d = reinterpret_cast<const uint32_t *>(dist) + static_cast<size_t>(q) * nlist;
+
+    // Cut by value first: a histogram over kProbeSteps equal steps between the smallest and the largest
+    // distance locates the step that holds the nprobe-th smallest; the keys up to that step (a superset of
+    // the nprobe smallest, usually little more) are gathered and sorted by (distance, id).  The radix
+    // select below remains for inputs where that superset is large (many equal distances) or the
+    // distances span no finite range.  (Its first levels put all keys into a handful of counters, since
+    // distances of similar size share their top bits, which serializes the LDS atomics.)
+    {
+        __shared__ uint32_t steps[kProbeSteps];
+        __shared__ uint32_t s_lo, s_hi, s_step, s_n, wsum[16];
+        const int lane = tid & 63, wave = tid >> 6;
+        uint32_t lo = 0xFFFFFFFFu, hi = 0;
+        for (int l = tid; l < nlist; l += 1024) { const uint32_t key = d[l]; lo = min(lo, key); hi = max(hi, key); }
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            lo = min(lo, static_cast<uint32_t>(__shfl_xor(static_cast<int>(lo), o)));
+            hi = max(hi, static_cast<uint32_t>(__shfl_xor(static_cast<int>(hi), o)));
+        }
+        if (tid == 0) { s_lo = 0xFFFFFFFFu; s_hi = 0; s_step = kProbeSteps; s_n = 0; }
+        for (uint32_t t = tid; t < kProbeSteps; t += 1024) steps[t] = 0;
+        __syncthreads();
+        if (lane == 0) { atomicMin(&s_lo, lo); atomicMax(&s_hi, hi); }
+        __syncthreads();
+        const float dlo = __uint_as_float(s_lo), dhi = __uint_as_float(s_hi);
+        const float scale = static_cast<float>(kProbeSteps) / (dhi - dlo);
+        // non-decreasing in the distance, so "step <= s" keeps every key below some value
+        auto step_of = [&](uint32_t key) -> uint32_t {
+            const float x = (__uint_as_float(key) - dlo) * scale;
+            return x < static_cast<float>(kProbeSteps - 1) ? static_cast<uint32_t>(x) : kProbeSteps - 1;
+        };
+        bool cut = scale > 0.0f && scale < INFINITY;
+        if (cut) {                                               // uniform
+            for (int l = tid; l < nlist; l += 1024) atomicAdd(&steps[step_of(d[l])], 1u);
+            __syncthreads();
+            const uint32_t h0 = steps[2 * tid], h1 = steps[2 * tid + 1];      // kProbeSteps = 2 x 1024 threads
+            uint32_t incl = h0 + h1;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t other = __shfl(incl, lane >= o ? lane - o : lane);
+                if (lane >= o) incl += other;
+            }
+            if (lane == 63) wsum[wave] = incl;
+            __syncthreads();
+            uint32_t before = incl - (h0 + h1);
+            for (int w2 = 0; w2 < wave; ++w2) before += wsum[w2];
+            const uint32_t want = static_cast<uint32_t>(nprobe);
+            if (before < want && before + h0 + h1 >= want) {      // exactly one thread (nprobe <= nlist)
+                const bool first = before + h0 >= want;
+                s_step = first ? 2 * tid : 2 * tid + 1;
+                s_n = first ? before + h0 : before + h0 + h1;
+            }
+            __syncthreads();
+            cut = s_step < kProbeSteps && s_n <= kIvfMaxProbe * 2;
+        }
+        if (cut) {                                               // uniform
+            const uint32_t step = s_step, nkeep = s_n;
+            uint32_t nf = 1;
+            while (nf < nkeep) nf <<= 1;
+            __syncthreads();
+            if (tid == 0) s_n = 0;
+            for (uint32_t t = tid; t < nf; t += 1024) sel[t] = ~0ull;
+            __syncthreads();
+            for (int l = tid; l < nlist; l += 1024) {
+                const uint32_t key = d[l];
+                if (step_of(key) <= step) {
+                    const uint32_t pos = atomicAdd(&s_n, 1u);
+                    if (pos < nf) sel[pos] = make_key(key, static_cast<uint32_t>(l));
+                }
+            }
+            bitonic_sort(sel, nf);
+            for (int t = tid; t < nprobe; t += 1024)
+                probe[static_cast<size_t>(q) * nprobe + t] = static_cast<int32_t>(sel[t] & 0xFFFFFFFFu);
+            return;
+        }
+        __syncthreads();
+    }
 
     // value of the nprobe-th smallest key, one byte at a time from the top
     uint32_t prefix = 0, need = nprobe;
