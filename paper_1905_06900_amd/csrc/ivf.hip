@@ -199,21 +199,14 @@ __device__ inline float ivf_block_reduce(float v, bool want_max, float *red)
     return out;
 }
 
-// Small-table entry i of sub-quantizer j for the residual rho (in LDS): sum_t (rho_jt - cbar_jit)^2.
-__device__ inline float ivf_entry(const float *rho, const float *derived, int dsub, int j, int i)
-{
-    const float *c = derived + (static_cast<size_t>(j) * kSmallSize + i) * dsub;
-    float acc = 0.0f;
-    for (int t = 0; t < dsub; ++t) {
-        const float diff = __fsub_rn(rho[j * dsub + t], c[t]);
-        acc = __fadd_rn(acc, __fmul_rn(diff, diff));
-    }
-    return acc;
-}
-
 // MODE 0: smallest entry of the (query, list) tables -> atomic min into qmin_bits[q].
 // MODE 1: quantize with the query's bounds -> qtab[q][p][m][256].
-// grid (nprobe, nq), 256 threads; thread i owns entry i of every table.
+// grid (ceil(nprobe / kIvfTabProbes), nq), 256 threads; thread i owns entry i of every table of
+// kIvfTabProbes probed lists of the query.  The derived centroid is read once per component and used for
+// all of those lists' residuals (the kernel is bound by these reads, which all come from the L2); every
+// entry is still the sum over t, in ascending t, of the individually rounded squares.
+constexpr int kIvfTabProbes = 8;
+
 template <int MODE>
 __global__ __launch_bounds__(256) void ivf_tables_kernel(const float *__restrict__ queries, const float *__restrict__ coarse,
                                                         const int32_t *__restrict__ probe, int nprobe,
@@ -221,31 +214,56 @@ __global__ __launch_bounds__(256) void ivf_tables_kernel(const float *__restrict
                                                         uint32_t *__restrict__ qmin_bits, const float *__restrict__ bounds,
                                                         uint8_t *__restrict__ qtab)
 {
-    extern __shared__ float lds[];         // rho [m*dsub]
+    extern __shared__ float lds[];         // rho [kIvfTabProbes][m*dsub]
     __shared__ float red[4];
-    const int p = blockIdx.x, q = blockIdx.y, tid = threadIdx.x;
+    const int p0 = blockIdx.x * kIvfTabProbes, q = blockIdx.y, tid = threadIdx.x;
+    const int np = min(kIvfTabProbes, nprobe - p0);
     const int D = m * dsub;
-    const int l = probe[static_cast<size_t>(q) * nprobe + p];
-    for (int t = tid; t < D; t += 256)
-        lds[t] = __fsub_rn(queries[static_cast<size_t>(q) * D + t], coarse[static_cast<size_t>(l) * D + t]);
+    for (int pp = 0; pp < np; ++pp) {
+        const int l = probe[static_cast<size_t>(q) * nprobe + p0 + pp];
+        for (int t = tid; t < D; t += 256)
+            lds[pp * D + t] = __fsub_rn(queries[static_cast<size_t>(q) * D + t], coarse[static_cast<size_t>(l) * D + t]);
+    }
     __syncthreads();
+    float qmin = 0.0f, den = 0.0f;
+    if (MODE == 1) {
+        qmin = bounds[2 * q];
+        den = __fsub_rn(bounds[2 * q + 1], qmin);
+    }
+    float lo = INFINITY;
+    for (int j = 0; j < m; ++j) {
+        const float *c = derived + (static_cast<size_t>(j) * kSmallSize + tid) * dsub;
+        float acc[kIvfTabProbes];
+#pragma unroll
+        for (int pp = 0; pp < kIvfTabProbes; ++pp) acc[pp] = 0.0f;
+        for (int t = 0; t < dsub; ++t) {
+            const float ct = c[t];
+#pragma unroll
+            for (int pp = 0; pp < kIvfTabProbes; ++pp) {
+                if (pp < np) {                                    // uniform
+                    const float diff = __fsub_rn(lds[pp * D + j * dsub + t], ct);
+                    acc[pp] = __fadd_rn(acc[pp], __fmul_rn(diff, diff));
+                }
+            }
+        }
+#pragma unroll
+        for (int pp = 0; pp < kIvfTabProbes; ++pp) {
+            if (pp >= np) continue;                               // uniform
+            if (MODE == 0) {
+                lo = fminf(lo, acc[pp]);
+            } else {
+                uint8_t code = 0;
+                if (den > 0.0f) {
+                    const float u = __fmul_rn(__fdiv_rn(__fsub_rn(acc[pp], qmin), den), 255.0f);
+                    code = (u >= 255.0f) ? static_cast<uint8_t>(255) : static_cast<uint8_t>(floorf(u));
+                }
+                qtab[((static_cast<size_t>(q) * nprobe + p0 + pp) * m + j) * kSmallSize + tid] = code;
+            }
+        }
+    }
     if (MODE == 0) {
-        float lo = INFINITY;
-        for (int j = 0; j < m; ++j) lo = fminf(lo, ivf_entry(lds, derived, dsub, j, tid));
         lo = ivf_block_reduce(lo, false, red);
         if (tid == 0) atomicMin(&qmin_bits[q], __float_as_uint(lo));    // entries are >= +0
-    } else {
-        const float qmin = bounds[2 * q], qmax = bounds[2 * q + 1];
-        const float den = __fsub_rn(qmax, qmin);
-        for (int j = 0; j < m; ++j) {
-            const float v = ivf_entry(lds, derived, dsub, j, tid);
-            uint8_t code = 0;
-            if (den > 0.0f) {
-                const float u = __fmul_rn(__fdiv_rn(__fsub_rn(v, qmin), den), 255.0f);
-                code = (u >= 255.0f) ? static_cast<uint8_t>(255) : static_cast<uint8_t>(floorf(u));
-            }
-            qtab[((static_cast<size_t>(q) * nprobe + p) * m + j) * kSmallSize + tid] = code;
-        }
     }
 }
 
@@ -791,14 +809,26 @@ extern "C" int dcpq_ivf_build_small_tables(const float *queries, int nq, const f
     // +inf as the starting minimum
     rc = launch_fill_u64(reinterpret_cast<uint64_t *>(qmin_bits), (static_cast<size_t>(nq) + 1) / 2, 0x7f8000007f800000ull, st);
     if (rc) return rc;
-    const size_t lds = sizeof(float) * static_cast<size_t>(m) * dsub;
-    DCPQ_LAUNCH(kStageIvf, st, ivf_tables_kernel<0>, dim3(nprobe, nq), dim3(256), lds, queries, coarse, probe, nprobe,
+    const size_t lds = sizeof(float) * static_cast<size_t>(kIvfTabProbes) * m * dsub;
+    const dim3 tgrid((nprobe + kIvfTabProbes - 1) / kIvfTabProbes, nq);
+    if (lds > 64 * 1024) {                  // LDS above 64 KiB must be requested per kernel (at most 128 KiB here)
+        static bool attr_done = false;
+        if (!attr_done) {
+            const int most = static_cast<int>(sizeof(float) * kIvfTabProbes * 32 * 128);
+            DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&ivf_tables_kernel<0>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, most));
+            DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&ivf_tables_kernel<1>),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, most));
+            attr_done = true;
+        }
+    }
+    DCPQ_LAUNCH(kStageIvf, st, ivf_tables_kernel<0>, tgrid, dim3(256), lds, queries, coarse, probe, nprobe,
                 derived, m, dsub, qmin_bits, bounds, qtab);
     DCPQ_CHECK_LAUNCH("ivf_tables_kernel<min>");
     DCPQ_LAUNCH(kStageIvf, st, ivf_qmax_kernel, dim3(nq), dim3(256), 0, queries, coarse, probe, nprobe, derived, m, dsub,
                 codes, offsets, r, qmin_bits, bounds);
     DCPQ_CHECK_LAUNCH("ivf_qmax_kernel");
-    DCPQ_LAUNCH(kStageIvf, st, ivf_tables_kernel<1>, dim3(nprobe, nq), dim3(256), lds, queries, coarse, probe, nprobe,
+    DCPQ_LAUNCH(kStageIvf, st, ivf_tables_kernel<1>, tgrid, dim3(256), lds, queries, coarse, probe, nprobe,
                 derived, m, dsub, qmin_bits, bounds, qtab);
     DCPQ_CHECK_LAUNCH("ivf_tables_kernel<quantize>");
     return DCPQ_OK;
