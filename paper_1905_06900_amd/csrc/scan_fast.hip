@@ -1,8 +1,8 @@
-// Pass one of Alg. 3 (Sec. 3.3, "Scan step") -- the single-pass kernel.
+// Pass one of Alg. 3 (Sec. 3.3, Scan step) -- the single-pass kernel.
 //
 // What is computed is the same as in scan.hip: qd = min(255, sum_j Q_j[low8(c[j])]) for every
 // (query, code) and the r smallest by (qd, id).  How it is computed differs from the paper's CPU
-// loop in four ways that matter on this chip:
+// loop in five ways that matter on this chip:
 //
 // 1. Row lookups instead of byte lookups.  A tile of QT queries keeps its tables in LDS
 //    transposed, T[j][e][q] with the query fastest, so that the table entries of one (code, j)
@@ -10,38 +10,43 @@
 //    lookups per wavefront instruction, against 64 for byte gathers.  Rows of the same
 //    sub-quantizer group are interleaved over a 256-byte LDS line (row slot = j mod NSLOT), and
 //    which sub-quantizer a lane reads is rotated with its code slot so that the 16 lanes of a
-//    lane group always touch 16 different 16-byte units of their lines.  Not every such rotation
-//    is equally fast: the lane-to-unit patterns used here (see rotated_j) are the ones that
-//    measured at the rate of a linear ds_read_b128 sweep (about 170 bytes per clock per CU);
-//    other conflict-free-looking rotations measured 110-120.
+//    lane group always touch 16 different 16-byte units of their lines (see rotated_j).
 //
-// 2. The sum over j runs on the matrix cores as an exact integer accumulation: with A = the
-//    gathered rows (16 x 64 bytes: 16 (code, query-block) rows, 4 sub-quantizers x 16 queries) and
-//    B = four stacked 16 x 16 identities, v_mfma_i32_16x16x64_i8 returns
-//    D[row][n] = sum over the 4 sub-quantizers of T[j][e][16 * qb + n], and chaining M/4 of them
-//    through the accumulator gives the unsaturated integer distance.  The instruction multiplies
-//    SIGNED bytes, so the LDS copy of the tables holds x - 128 (the byte with its top bit flipped)
-//    and the accumulator starts at 128 * M instead of 0, which restores the unsigned sum exactly.
-//    This is not a reshaping of the scan into a dense product (no one-hot expansion: every byte
-//    multiplied is a byte the method looks up); the matrix unit only replaces the byte
-//    unpack-and-add that the vector ALU would otherwise spend three instructions per four lookups on.
+// 2. The sum over j runs on the matrix cores as an exact integer accumulation.  The 16-byte rows
+//    are one operand; the other is constant and only says which bytes belong to which output:
+//    for m = 4 four stacked 16 x 16 identities (v_mfma_i32_16x16x64_i8 adds 4 sub-quantizers), for
+//    m >= 8 a structured-sparse pattern of ones (v_smfmac_i32_16x16x128_i8 adds 8 sub-quantizers
+//    in the same time).  The instructions multiply SIGNED bytes, so the LDS copy of the tables
+//    holds x - 128 (the byte with its top bit flipped) and the accumulator starts at 128 * M
+//    instead of 0, which restores the unsigned sum exactly.  This is not a reshaping of the scan
+//    into a dense product (no one-hot expansion: every byte multiplied is a byte the method looks
+//    up); the matrix unit only replaces the byte unpack-and-add that the vector ALU would
+//    otherwise spend three instructions per four lookups on.
 //
-// 3. Capped buckets become a running threshold.  Each query has a bucket bound T_cur that is
-//    never below the bucket of its r-th best candidate: it starts as the exact r-th smallest qd
-//    of a strided sample of the codes and is lowered whenever the exact per-bucket counts of the
-//    candidates appended so far reach r below a smaller bucket (the paper's "distance of the
-//    r2-th farthest vector as upper bound").  A pair with qd <= T_cur is appended to the query's
-//    candidate buffer.  Whatever the timing of the updates, the buffer ends up a superset of the
-//    true candidate set, from which the exact, id-tie-broken r are then selected; the result does
-//    not depend on the order of arrival.  If a buffer overflows (pathological ties), the query is
-//    flagged and redone by the three-pass path of scan.hip.
+// 3. Capped buckets become a running threshold.  Each query has a bucket bound T_cur that the
+//    scan never lets fall below the bucket of its r-th best candidate: it starts from the histogram
+//    of a strided sample of the codes, at the bucket where the sample's count reaches what r
+//    codes of the whole array would leave in a sample of that size (plus eight standard
+//    deviations), and it is lowered whenever the exact per-bucket counts of the candidates
+//    appended so far reach r below a smaller bucket (Sec. 3.3, Scan step: the dynamic upper bound
+//    of the capped buckets).  A pair with qd <= T_cur is appended to the query's candidate buffer.
+//    Whatever the timing of the updates, the buffer ends up a superset of the true candidate set,
+//    from which the exact, id-tie-broken r are then selected; the result does not depend on the
+//    order of arrival.  If a buffer overflows (pathological ties), or the estimated starting bound
+//    turns out too low (fewer than r appended), the query is flagged and redone by the three-pass
+//    path of scan.hip.
 //
 // 4. Appends stay off the critical path.  A query's buffer and append cursor are split into slices by
-//    the workgroup's position along the codes (same-address returning atomics serialize in the L2);
-//    a first, narrow launch over a small head of the array settles the bounds before the main launch
-//    starts thousands of wavefronts from the sample's loose bound; and a wavefront hands its pending
-//    candidates over early when few queries face many wavefronts, so that candidates waiting in
-//    queues never outnumber r.
+//    the workgroup's position along the codes (same-address returning atomics serialize in the L2),
+//    and a wavefront hands its pending candidates over early when few queries face many
+//    wavefronts, so that candidates waiting in queues never outnumber r.
+//
+// 5. The inner loop is a software pipeline.  The vector instruction port of a SIMD (matrix and
+//    ordinary vector instructions share it) and the LDS are both close to full, and an LDS read
+//    comes back hundreds of clocks after its issue; so the rows of the next iteration and the code
+//    bytes of the one after it are always in flight, and everything per-iteration that is not a
+//    row read, a matrix instruction, an address permute or the sign test has been moved out of the
+//    loop (bounds live in LDS, code bytes are published a batch at a time).
 #include <type_traits>
 
 #include "common.h"
@@ -51,6 +56,7 @@
 namespace dcpq {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 
 template <int M, int QT, int WAVES>
 struct FastCfg {
@@ -60,21 +66,26 @@ struct FastCfg {
     static constexpr int NMF = M / 4;               // chained MFMAs per step
     static constexpr int STEPS = 64 / CPS;          // steps per 64-code group
     static constexpr int UNROLL = NMF >= 8 ? 1 : 8 / NMF;   // steps issued together (8 row reads in flight)
-    static constexpr int PREFETCH = M <= 8 ? 4 : M == 16 ? 2 : 1;   // 64-code groups fetched ahead per wavefront
     static constexpr int CLS = M / 4;               // bytes per residue class j mod 4 of one code
     static constexpr bool ADJ = NQB != 4;           // lanes of one table row adjacent (else strided by CPS)
+    static constexpr bool SPARSE = M >= 8;          // sum 8 rows per matrix instruction (else 4)
     static constexpr int REGION = STEPS * CLS;      // scratch bytes per (code slot, class): all steps of a group
     // Table rows per code value: when a line has more row slots than there are sub-quantizers the
     // tables are stored NSLOT / M times, so that every lane still finds its row in the slot its
     // position in the wavefront asks for.
     static constexpr int VJ = NSLOT > M ? NSLOT : M;
     static constexpr int TAB_BYTES = VJ * 256 * QT;
-    static constexpr int SCR_BYTES = WAVES * 64 * M;
     static constexpr int QCAP = 64;                 // pending-candidate queue entries per wavefront (>= 64)
     static constexpr int Q_BYTES = WAVES * QCAP * 8;
-    static constexpr int LDS_BYTES = TAB_BYTES + SCR_BYTES + Q_BYTES;
+    // 64-code groups fetched ahead per wavefront (and published to its scratch together): as many
+    // as the LDS left beside the tables holds, at most 4
+    static constexpr int BND_BYTES = 4 * QT;        // starting values of the accumulators, one per query of the tile
+    static constexpr int ROOM = (160 * 1024 - TAB_BYTES - Q_BYTES - BND_BYTES) / (WAVES * 64 * M);
+    static constexpr int PREFETCH = ROOM >= 4 ? 4 : ROOM >= 2 ? 2 : 1;
+    static constexpr int SCR_BYTES = WAVES * PREFETCH * 64 * M;
+    static constexpr int LDS_BYTES = TAB_BYTES + SCR_BYTES + Q_BYTES + BND_BYTES;
     static_assert(M % 4 == 0 && VJ % M == 0, "row slots rotate within the (possibly repeated) sub-quantizers");
-    static_assert(LDS_BYTES <= 160 * 1024, "one workgroup must fit the LDS of a CU");
+    static_assert(ROOM >= 1 && LDS_BYTES <= 160 * 1024, "one workgroup must fit the LDS of a CU");
     static_assert(STEPS % UNROLL == 0, "unroll must divide the steps of a group");
     static_assert(UNROLL * CLS == 8, "the steps issued together read one 8-byte word of code bytes");
     static_assert(CPS * 4 * REGION == 64 * M, "scratch regions tile the group");
@@ -167,13 +178,20 @@ template <int M>
 __device__ inline void transposed_low_bytes(const uint32_t (&w)[M / 2], uint32_t (&out)[M / 4])
 {
     // w[i] holds sub-codes 2i (bits 0..15) and 2i+1 (bits 16..31); low byte of j is byte 2*(j&1) of w[j/2]
+    if constexpr (M == 4) {
+        out[0] = __builtin_amdgcn_perm(w[1], w[0], 0x06040200u);       // j = 0, 1, 2, 3
+    } else if constexpr (M == 8) {
+        out[0] = __builtin_amdgcn_perm(w[2], w[0], 0x06020400u);       // j = 0, 4, 1, 5
+        out[1] = __builtin_amdgcn_perm(w[3], w[1], 0x06020400u);       // j = 2, 6, 3, 7
+    } else {
 #pragma unroll
-    for (int d = 0; d < M / 4; ++d) out[d] = 0;
+        for (int d = 0; d < M / 4; ++d) out[d] = 0;
 #pragma unroll
-    for (int j = 0; j < M; ++j) {
-        const uint32_t b = (w[j >> 1] >> (16 * (j & 1))) & 255u;
-        const int p = (j & 3) * (M / 4) + (j >> 2);
-        out[p >> 2] |= b << (8 * (p & 3));
+        for (int j = 0; j < M; ++j) {
+            const uint32_t b = (w[j >> 1] >> (16 * (j & 1))) & 255u;
+            const int p = (j & 3) * (M / 4) + (j >> 2);
+            out[p >> 2] |= b << (8 * (p & 3));
+        }
     }
 }
 
@@ -202,27 +220,39 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     uint32_t qflush, int *t_cur, uint32_t *count, uint32_t *chist, uint64_t *__restrict__ keys)
 {
     using C = FastCfg<M, QT, WAVES>;
+    constexpr int PF = C::PREFETCH;
     extern __shared__ __align__(16) uint8_t smem[];
     uint8_t *ltab = smem;
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // wave-uniform: keep it (and what derives from it) scalar
-    uint8_t *scr = smem + C::TAB_BYTES + wave * (64 * M);
+    uint8_t *scr = smem + C::TAB_BYTES + wave * (PF * 64 * M);
     uint64_t *wq = reinterpret_cast<uint64_t *>(smem + C::TAB_BYTES + C::SCR_BYTES) + wave * C::QCAP;
+    int *lbnd = reinterpret_cast<int *>(smem + C::TAB_BYTES + C::SCR_BYTES + C::Q_BYTES);
 
     const int tile = blockIdx.x;
     const int q0 = tile * QT;
+    // Bucket bound T of a query as the value its accumulators start from, 128 * M - (T + 1): the
+    // 128 * M undoes the -128 bias of the M signed bytes and the rest turns "qd <= T" into
+    // "result < 0".  A bound of 255 lets every code through (the sum itself is not capped), an
+    // absent query has the bound -1 that nothing reaches.
+    auto start_value = [&](int q) {
+        int t = -1;
+        if (q < nq) t = __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return t >= 255 ? static_cast<int>(128u * M - 0x80000000u) : static_cast<int>(128u * M - static_cast<uint32_t>(t) - 1u);
+    };
     {
         const uint4 *src = reinterpret_cast<const uint4 *>(qsw + static_cast<size_t>(tile) * C::TAB_BYTES);
         uint4 *dst = reinterpret_cast<uint4 *>(ltab);
         for (int v = tid; v < C::TAB_BYTES / 16; v += WAVES * 64) dst[v] = src[v];
+        if (tid < QT) lbnd[tid] = start_value(q0 + tid);
     }
     __syncthreads();
 
     // ---- per-lane constants -------------------------------------------------------------
     const int s = lane >> 4, i = lane & 15;
-    // A operand: row i of the MFMA is (code slot ca, query block qba)
+    // position i of a 16-lane chunk stands for (code slot ca, query block qba)
     const int ca = C::ADJ ? i / C::NQB : i % C::CPS, qba = C::ADJ ? i % C::NQB : i / C::CPS;
-    // Row address of MFMA f = laneoff[f] with its (zero) second byte replaced by the code byte, one
+    // Address of row read f = laneoff[f] with its (zero) second byte replaced by the code byte, one
     // v_perm_b32: sel[f] picks, out of a 32-bit word of class bytes, the byte of this lane's
     // sub-quantizer j (byte j / 4 of the class word j mod 4).
     // The tables start at LDS offset lds0 = 0 (the kernel has no static LDS; the host checks that),
@@ -236,22 +266,43 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
         selb[f] = C::NSLOT == 4 ? static_cast<uint32_t>(f) : static_cast<uint32_t>((jv % M) >> 2);
     }
     const int cls = rotated_j<C::NSLOT>(0, s, ca) & 3;     // residue class j mod 4 read by this lane
-    const uint32_t scr_rd = (ca * 4 + cls) * C::REGION;    // + 8 * (iteration within the group)
-    v4i bsel = {0, 0, 0, 0};                               // B: four stacked identities
-    bsel[i >> 2] = 1 << (8 * (i & 3));
-    // D operand: value v of this lane is row 4 * (lane / 16) + v, column lane % 16
-    int cd[4], ql[4];
-#pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        const int row = 4 * s + v;
-        cd[v] = C::ADJ ? row / C::NQB : row % C::CPS;
-        ql[v] = (C::ADJ ? row % C::NQB : row / C::CPS) * 16 + i;
+    const uint32_t scr_rd = lds_offset_of(scr) + (ca * 4 + cls) * C::REGION;    // + 64 M (group of the batch) + 8 (iteration)
+    // Dense form (M = 4): A = the gathered rows (row i of the matrix = this chunk position), B = four
+    // stacked 16 x 16 identities; output value v of this lane belongs to chunk position
+    // 4 * (lane / 16) + v and to query lane % 16 of the block.
+    // Sparse form (M >= 8): the roles are swapped and the structured-sparse operand (two stored
+    // values out of every four along K = 128) is the constant one: its row n holds a 1 wherever K
+    // addresses byte n of one of the 8 gathered rows of a column, so one instruction adds 8
+    // sub-quantizers.  The stored values sit in 8 pairs per lane; pair g of lane (n, k) with index p
+    // meets byte 16 * (k / 2) + 4 * (g mod 4) + p of the dense operand's lane 2 * (k mod 2) + g / 4 of
+    // the same column (found by feeding the instruction single ones).  Output value v of this lane
+    // belongs to query 4 * (lane / 16) + v of the block and to chunk position lane % 16.
+    constexpr bool SP = C::SPARSE;
+    v4i bsel = {0, 0, 0, 0};
+    int spidx = 0;
+    if constexpr (SP) {
+        const int t1 = 2 * (i >> 2), t2 = 8 + 2 * (i >> 2);        // first value of pairs i / 4 and 4 + i / 4
+        bsel[t1 >> 2] |= 1 << (8 * (t1 & 3));
+        bsel[t2 >> 2] |= 1 << (8 * (t2 & 3));
+        spidx = ((i & 3) << (2 * t1)) | ((i & 3) << (2 * t2));
+    } else {
+        bsel[i >> 2] = 1 << (8 * (i & 3));
     }
+    // code slot and query (within the tile) of output value v
+    auto code_slot_of = [&](int v) { return SP ? ca : (C::ADJ ? (4 * s + v) / C::NQB : (4 * s + v) % C::CPS); };
+    auto query_at = [](int ln, int v) {
+        const int ss = ln >> 4, ii = ln & 15;
+        if constexpr (SP) return (C::ADJ ? ii % C::NQB : ii / C::CPS) * 16 + 4 * ss + v;
+        else return (C::ADJ ? (4 * ss + v) % C::NQB : (4 * ss + v) / C::CPS) * 16 + ii;
+    };
+    auto query_of = [&](int v) { return query_at(lane, v); };
 
-    // this workgroup's codes: a stretch of codes_per_block out of code_begin .. code_end
-    const uint64_t cbeg = code_begin + static_cast<uint64_t>(blockIdx.y) * codes_per_block;
-    const uint64_t cend = min(code_end, cbeg + codes_per_block);
-    const uint32_t ngroups = cbeg < cend ? static_cast<uint32_t>((cend - cbeg + 63) / 64) : 0u;
+    // this workgroup's codes: a stretch of codes_per_block out of code_begin .. code_end (ids fit 32
+    // bits: the host checks n_codes)
+    const uint64_t cbeg64 = code_begin + static_cast<uint64_t>(blockIdx.y) * codes_per_block;
+    const uint32_t cbeg = static_cast<uint32_t>(cbeg64);
+    const uint32_t cend = static_cast<uint32_t>(min(code_end, cbeg64 + codes_per_block));
+    const uint32_t ngroups = cbeg64 < code_end ? (cend - cbeg + 63u) / 64u : 0u;
 
     // Pending candidates of this wavefront: records wq[0 .. qlen), qlen <= QCAP = 64.  qlen is
     // wave-uniform (it only changes by ballot counts), so it lives in a scalar register and the queue
@@ -280,19 +331,22 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
 
-    // ---- main loop: one 64-code group per iteration ---------------------------------------
+    // ---- the code stream ------------------------------------------------------------------
+    // This wavefront's groups are wave, wave + WAVES, ...; they are fetched PF at a time and one batch
+    // ahead of their use, so that each wavefront keeps PF kilobytes of the code stream in flight.
+    const uint32_t ng_w = ngroups > static_cast<uint32_t>(wave) ? (ngroups - wave + WAVES - 1) / WAVES : 0u;
     auto load_group = [&](uint32_t g, uint32_t (&dst)[M / 2]) {
-        const uint64_t id = cbeg + static_cast<uint64_t>(g) * 64 + lane;
+        const uint32_t id = cbeg + g * 64u + lane;
         if (g < ngroups && id < cend) {
             if constexpr (M % 8 == 0) {
-                const uint4 *p = reinterpret_cast<const uint4 *>(codes + id * M);
+                const uint4 *p = reinterpret_cast<const uint4 *>(codes + static_cast<uint64_t>(id) * M);
 #pragma unroll
                 for (int v = 0; v < M / 8; ++v) {
                     const uint4 x = p[v];
                     dst[4 * v] = x.x; dst[4 * v + 1] = x.y; dst[4 * v + 2] = x.z; dst[4 * v + 3] = x.w;
                 }
             } else {
-                const uint2 x = *reinterpret_cast<const uint2 *>(codes + id * M);
+                const uint2 x = *reinterpret_cast<const uint2 *>(codes + static_cast<uint64_t>(id) * M);
                 dst[0] = x.x; dst[1] = x.y;
             }
         } else {
@@ -300,153 +354,203 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
             for (int v = 0; v < M / 2; ++v) dst[v] = 0;
         }
     };
-    // Groups are fetched PF at a time and one batch ahead of their use, so that each wavefront
-    // keeps PF kilobytes of the code stream in flight (HBM latency x bandwidth needs that much).
-    constexpr int PF = C::PREFETCH;
     uint32_t wb[PF][M / 2];
     auto load_batch = [&](uint32_t g0) {
 #pragma unroll
         for (int pf = 0; pf < PF; ++pf) load_group(g0 + pf * WAVES, wb[pf]);
     };
     load_batch(wave);
-    // Bucket bounds of the queries of this lane's four outputs, re-read once per batch and one batch
-    // ahead of their use; absent queries never match.  The four outputs are NB different queries
-    // (output v belongs to query v mod NB).  A stale bound is still a valid one (bounds only go down), so
-    // most reads may be served by the CU's vector cache; the first batches of a workgroup (when the
-    // bound moves fastest) and every 4th one after them read past it.  This keeps the thousands of
-    // wavefronts of a tile from queueing on the one cache line that holds its bounds.
-    constexpr int NB = (C::ADJ && C::NQB == 2) ? 2 : 1;
-    auto load_bounds = [&](int (&dst)[NB], bool fresh) {
-#pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            const int q = q0 + ql[b];
-            int t = -1;
-            if (q < nq)
-                t = fresh ? __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                          : __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-            dst[b] = t >= 255 ? 0x7fffffff : t;
-        }
-    };
-    int tb_next[NB];
-    load_bounds(tb_next, true);
+    uint32_t g_load = wave + PF * WAVES;                     // first group of the batch to fetch next
+
+    // Bucket bounds.  The workgroup keeps the accumulator start values of its tile's queries in LDS;
+    // once per batch every wavefront re-reads those of its four outputs, and now and then (every
+    // batch at first, when the bounds move fastest, every fourth later) one wavefront, in turn,
+    // renews the array from the bounds in global memory (lane = query).  A stale bound is still a
+    // valid one (bounds only go down), so neither step needs any ordering, and only one wavefront per
+    // workgroup touches the cache line that holds the tile's bounds.
     uint32_t batch = 0;
 
-    for (uint32_t g0 = wave; g0 < ngroups; g0 += PF * WAVES) {
-        uint32_t tbp[PF][M / 4];
-#pragma unroll
-        for (int pf = 0; pf < PF; ++pf) transposed_low_bytes<M>(wb[pf], tbp[pf]);
-        load_batch(g0 + PF * WAVES);                                 // prefetch the next batch
-        int tl[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) tl[v] = tb_next[v % NB];
-        ++batch;
-        load_bounds(tb_next, batch < 4 || (batch & 3u) == 0);
-        v4i acc0;
-#pragma unroll
-        for (int v = 0; v < 4; ++v)
-            acc0[v] = static_cast<int>(128u * M - static_cast<uint32_t>(tl[v]) - 1u);
-#pragma unroll 1
-      for (int pf = 0; pf < PF; ++pf) {
-        const uint32_t g = g0 + pf * WAVES;
-        if (g >= ngroups) break;                                     // uniform
-        const uint64_t gbase = cbeg + static_cast<uint64_t>(g) * 64;
-        const uint32_t gbase32 = static_cast<uint32_t>(gbase);     // ids fit 32 bits (the host checks n_codes)
-        const int nlive = static_cast<int>(min(static_cast<uint64_t>(64), cend - gbase));   // codes in this group
-        // Publish the low bytes of the group's codes to the wavefront's scratch.  Lane l holds code l
-        // = step l / CPS, code slot l % CPS; its M / 4 bytes of class k go to region (slot, k) at the
-        // step's position, so that a reader finds the bytes of UNROLL consecutive steps in one
-        // 8-byte word.
-        {
-            uint32_t tb[M / 4];
-#pragma unroll
-            for (int d = 0; d < M / 4; ++d) {
-                tb[d] = tbp[0][d];
-#pragma unroll
-                for (int z = 1; z < PF; ++z) tb[d] = pf == z ? tbp[z][d] : tb[d];
-            }
+    // ---- the pipeline ---------------------------------------------------------------------
+    // One iteration = U steps = 8 table-row reads per lane and the matrix instructions that add
+    // them; a 64-code group is NI iterations.  All iterations of the wavefront form one software
+    // pipeline, because with 16 wavefronts queueing on one LDS a read comes back hundreds of clocks
+    // after it was issued: while the matrix instructions of iteration n run, the row reads of
+    // iteration n + 1 and the 8-byte read of the code bytes of iteration n + 2 are already in flight.
+    // Two register sets of rows (ra, rb) and two code-byte words alternate; the loop body is one
+    // group (two when a group is a single iteration), so that every LDS instruction has a fixed
+    // place in it and the waits can count.  The pipeline runs up to two iterations past the
+    // wavefront's last group: those reads find zero code bytes and valid table rows, and their
+    // results are never used.
+    constexpr int U = C::UNROLL, NI = C::STEPS / U, GB = NI == 1 ? 2 : 1;
+    static_assert(NI == 1 || NI % 2 == 0, "the two row sets alternate evenly over a group");
+    static_assert(PF % GB == 0, "a batch is a whole number of loop bodies");
+
+    // Makes the next group the current one: `area` is the scratch offset of its code bytes.  When
+    // the fetched batch is used up, the low bytes of the next one are published to the wavefront's
+    // scratch, PF groups side by side.  Lane l holds code l = step l / CPS, code slot l % CPS of its
+    // group; its M / 4 bytes of class k go to region (slot, k) at the step's position, so that a
+    // reader finds the bytes of the U steps of an iteration in one 8-byte word.  Overwriting the
+    // scratch is safe: the LDS executes a wavefront's instructions in order, and every read of the
+    // previous batch has been issued by now (the code-byte reads run two iterations ahead).
+    uint32_t ring = PF;                                      // groups of the published batch used up
+    uint32_t area = 0;
+    auto next_group = [&]() {
+        if (ring == PF) {                                    // uniform
             uint8_t *dst = scr + (lane % C::CPS) * (4 * C::REGION) + (lane / C::CPS) * C::CLS;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                uint8_t *d = dst + k * C::REGION;
-                if constexpr (C::CLS == 1) *d = static_cast<uint8_t>(tb[0] >> (8 * k));
-                else if constexpr (C::CLS == 2) *reinterpret_cast<uint16_t *>(d) = static_cast<uint16_t>(tb[k >> 1] >> (16 * (k & 1)));
-                else if constexpr (C::CLS == 4) *reinterpret_cast<uint32_t *>(d) = tb[k];
-                else *reinterpret_cast<uint2 *>(d) = make_uint2(tb[2 * k], tb[2 * k + 1]);
-            }
-        }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-        // U steps are issued together: one 8-byte read of their code bytes, all their row reads,
-        // then U independent MFMA chains, so that several kilobytes of LDS reads per wavefront are
-        // in flight at any time.
-        constexpr int U = C::UNROLL;
-#pragma unroll 1
-        for (int t0 = 0; t0 < C::STEPS; t0 += U) {
-            const uint2 word = *reinterpret_cast<const uint2 *>(scr + scr_rd + (t0 / U) * 8);
-            v4i a[U][C::NMF];
+            for (int pf = 0; pf < PF; ++pf) {
+                uint32_t tb[M / 4];
+                transposed_low_bytes<M>(wb[pf], tb);
 #pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int f = 0; f < C::NMF; ++f) {
-                    // byte u * CLS + j / 4 of the 8-byte word; which of its two halves is known statically
-                    const int stat = u * C::CLS + (C::CLS == 8 ? 4 * (f >> 2) : 0);
-                    const uint32_t half = stat >= 4 ? word.y : word.x;
-                    const uint32_t sel = 0x07060004u | (((static_cast<uint32_t>(stat) + selb[f]) & 3u) << 8);
-                    const uint32_t addr = __builtin_amdgcn_perm(laneoff[f], half, sel);
-                    a[u][f] = lds_read_v4i(addr);
+                for (int k = 0; k < 4; ++k) {
+                    uint8_t *d = dst + pf * (64 * M) + k * C::REGION;
+                    if constexpr (C::CLS == 1) *d = static_cast<uint8_t>(tb[0] >> (8 * k));
+                    else if constexpr (C::CLS == 2) *reinterpret_cast<uint16_t *>(d) = static_cast<uint16_t>(tb[k >> 1] >> (16 * (k & 1)));
+                    else if constexpr (C::CLS == 4) *reinterpret_cast<uint32_t *>(d) = tb[k];
+                    else *reinterpret_cast<uint2 *>(d) = make_uint2(tb[2 * k], tb[2 * k + 1]);
                 }
-            // Each accumulator starts at 128 * M - (T + 1): the 128 * M undoes the -128 bias of the M
-            // signed bytes and the rest turns "qd <= T" into "result < 0", so one sign test of the
-            // OR of all results of the U steps decides whether anything was hit.
-            v4i acc[U];
+            }
+            load_batch(g_load);                              // fetch the batch after it
+            g_load += PF * WAVES;
+            ring = 0;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        area = ring * (64 * M);
+        ++ring;
+    };
+    // code bytes of the U steps at position p of the current group
+    auto read_word = [&](int p) -> uint2 {
+        typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+        typedef const u32x2 __attribute__((address_space(3))) *ptr_t;
+        const u32x2 x = *reinterpret_cast<ptr_t>(static_cast<uintptr_t>(scr_rd + area + p * 8));
+        return make_uint2(x[0], x[1]);
+    };
+    // the 8 row reads of an iteration
+    auto issue_rows = [&](const uint2 word, v4i (&a)[U][C::NMF]) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) acc[u] = acc0;
+        for (int u = 0; u < U; ++u)
 #pragma unroll
-            for (int f = 0; f < C::NMF; ++f)
+            for (int f = 0; f < C::NMF; ++f) {
+                // byte u * CLS + j / 4 of the 8-byte word; which of its two halves is known statically
+                const int stat = u * C::CLS + (C::CLS == 8 ? 4 * (f >> 2) : 0);
+                const uint32_t half = stat >= 4 ? word.y : word.x;
+                const uint32_t sel = 0x07060004u | (((static_cast<uint32_t>(stat) + selb[f]) & 3u) << 8);
+                const uint32_t addr = __builtin_amdgcn_perm(laneoff[f], half, sel);
+                a[u][f] = lds_read_v4i(addr);
+            }
+    };
+    // The accumulations over the rows of the iteration at position p of group g (independent chains,
+    // UC steps at a time so that few accumulators are live at once), the sign test of each such
+    // chunk, and (for a few per cent of the chunks) the hits
+    constexpr int UC = U < 2 ? U : 2;
+    auto compute = [&](const v4i (&a)[U][C::NMF], const v4i acc0, uint32_t g, int p) {
 #pragma unroll
-                for (int u = 0; u < U; ++u)
-                    acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[u][f], bsel, acc[u], 0, 0, 0);
-            int sign = 0;
+        for (int uc = 0; uc < U; uc += UC) {
+            v4i acc[UC];
 #pragma unroll
-            for (int u = 0; u < U; ++u) sign |= acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
-            if (__builtin_amdgcn_ballot_w64(sign < 0)) {             // uniform, rare
-                // PARTIAL: the group holds fewer than 64 codes (last group of the array only)
-                auto decode = [&](auto partial) {
+            for (int u = 0; u < UC; ++u) acc[u] = acc0;
+            if constexpr (SP) {
 #pragma unroll
-                    for (int u = 0; u < U; ++u) {
-                        const int su = acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
-                        if (!__builtin_amdgcn_ballot_w64(su < 0)) continue;      // uniform: no hit in this step
-                        const int first = (t0 + u) * C::CPS;         // first code of the step within the group
+                for (int f = 0; f < C::NMF; f += 2)
 #pragma unroll
-                        for (int v = 0; v < 4; ++v) {
-                            bool h = acc[u][v] < 0;
-                            if constexpr (decltype(partial)::value) h = h && first + cd[v] < nlive;
-                            const uint64_t mask = __builtin_amdgcn_ballot_w64(h);
-                            if (!mask) continue;                     // uniform
-                            const uint32_t cnt = __popcll(mask);
-                            if (qlen + cnt > C::QCAP) flush();       // uniform: make room (cnt <= 64 = QCAP)
-                            if (h) {
-                                const uint32_t id = gbase32 + static_cast<uint32_t>(first + cd[v]);
-                                // result + T + 1 is the unsaturated sum (unsigned wrap-around is intended)
-                                const uint32_t sum = static_cast<uint32_t>(acc[u][v]) + static_cast<uint32_t>(tl[v]) + 1u;
-                                const uint32_t qd = min(sum, 255u);
-                                const uint32_t rank = __builtin_amdgcn_mbcnt_hi(
-                                    static_cast<uint32_t>(mask >> 32),
-                                    __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
-                                wq[qlen + rank] = (static_cast<uint64_t>((static_cast<uint32_t>(ql[v]) << 8) | qd) << 32) | id;
-                            }
-                            qlen = __builtin_amdgcn_readfirstlane(qlen + cnt);      // wave-uniform: keep it scalar
-                        }
+                    for (int u = 0; u < UC; ++u) {
+                        const v8i rows = __builtin_shufflevector(a[uc + u][f], a[uc + u][f + 1], 0, 1, 2, 3, 4, 5, 6, 7);
+                        acc[u] = __builtin_amdgcn_smfmac_i32_16x16x128_i8(bsel, rows, acc[u], spidx, 0, 0);
                     }
-                };
-                if (nlive == 64) decode(std::false_type{});
-                else decode(std::true_type{});
-                if (qlen >= qflush) flush();                       // uniform: keep the invisible backlog small
+            } else {
+#pragma unroll
+                for (int f = 0; f < C::NMF; ++f)
+#pragma unroll
+                    for (int u = 0; u < UC; ++u)
+                        acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[uc + u][f], bsel, acc[u], 0, 0, 0);
+            }
+            int sign = acc[0][0] | acc[0][1] | acc[0][2];
+            sign = sign | acc[0][3];
+#pragma unroll
+            for (int u = 1; u < UC; ++u) {
+                sign = sign | acc[u][0] | acc[u][1];
+                sign = sign | acc[u][2] | acc[u][3];
+            }
+            if (!__builtin_amdgcn_ballot_w64(sign < 0)) continue;    // uniform
+            // codes in this group: fewer than 64 in the last group of the stretch, none past it
+            const uint32_t gbase = cbeg + g * 64u;
+            const int nlive = g < ngroups ? static_cast<int>(min(64u, cend - gbase)) : 0;
+#pragma unroll
+            for (int u = 0; u < UC; ++u) {
+                const int su = acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
+                if (!__builtin_amdgcn_ballot_w64(su < 0)) continue;      // uniform: no hit in this step
+                const int first = (p * U + uc + u) * C::CPS;    // first code of the step within the group
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    // (the empty asm keeps the compiler from precomputing, and then spilling, this sum for
+                    // every step of a group outside the loop)
+                    int slot = code_slot_of(v);
+                    asm volatile("" : "+v"(slot));
+                    const int code = first + slot;
+                    const bool h = acc[u][v] < 0 && code < nlive;
+                    const uint64_t mask = __builtin_amdgcn_ballot_w64(h);
+                    if (!mask) continue;                         // uniform
+                    const uint32_t cnt = __popcll(mask);
+                    if (qlen + cnt > C::QCAP) flush();           // uniform: make room (cnt <= 64 = QCAP)
+                    if (h) {
+                        const uint32_t id = gbase + static_cast<uint32_t>(code);
+                        // result - start value + 128 M is the unsaturated sum (unsigned wrap-around is intended)
+                        const uint32_t sum = static_cast<uint32_t>(acc[u][v]) - static_cast<uint32_t>(acc0[v]) + 128u * M;
+                        const uint32_t qd = min(sum, 255u);
+                        const uint32_t rank = __builtin_amdgcn_mbcnt_hi(
+                            static_cast<uint32_t>(mask >> 32),
+                            __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u));
+                        wq[qlen + rank] = (static_cast<uint64_t>((static_cast<uint32_t>(query_of(v)) << 8) | qd) << 32) | id;
+                    }
+                    qlen = __builtin_amdgcn_readfirstlane(qlen + cnt);      // wave-uniform: keep it scalar
+                }
+            }
+            if (qlen >= qflush) flush();                       // uniform: keep the invisible backlog small
+        }
+    };
+
+    if (ng_w) {
+        v4i ra[U][C::NMF], rb[U][C::NMF];
+        uint2 w[2];
+        next_group();
+        w[0] = read_word(0);
+        if constexpr (NI == 1) next_group();
+        w[1] = read_word(NI == 1 ? 0 : 1);
+        issue_rows(w[0], ra);
+#pragma unroll 1
+        for (uint32_t gi = 0; gi < ng_w; gi += GB) {
+            if (gi % PF == 0) {                                  // uniform
+                if ((batch < 8 || (batch & 3u) == 0) && batch % WAVES == static_cast<uint32_t>(wave)) {
+                    if (lane < QT) lbnd[lane] = start_value(q0 + lane);      // this wavefront's turn to renew them
+                }
+                ++batch;
+            }
+            // start values of this lane's four accumulator values, re-read for every loop body: one sign
+            // test of the OR of all results of a chunk decides whether anything was hit
+            // (the lane index is taken afresh so that the addresses are recomputed here rather than
+            // kept, spilled, in registers over the whole loop)
+            v4i acc0;
+            {
+                uint32_t zero = 0;
+                asm volatile("" : "+v"(zero));
+                const int ln = static_cast<int>(__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, zero)));
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc0[v] = lbnd[query_at(ln, v)];
+            }
+            const uint32_t g = wave + gi * WAVES;
+#pragma unroll
+            for (int t = 0; t < GB * NI; ++t) {
+                // code bytes of the iteration after the next (into the word whose rows are already
+                // on their way), then the rows of the next iteration
+                if ((t + 2) % NI == 0) next_group();
+                w[t % 2] = read_word((t + 2) % NI);
+                if (t % 2 == 0) issue_rows(w[1], rb); else issue_rows(w[0], ra);
+                if (t % 2 == 0) compute(ra, acc0, g + (t / NI) * WAVES, t % NI);
+                else compute(rb, acc0, g + (t / NI) * WAVES, t % NI);
             }
         }
-      }
     }
     flush();
 }
