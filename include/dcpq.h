@@ -128,6 +128,19 @@ int dcpq_scan_candidates_mode(const uint16_t *codes, uint64_t n_codes, int m, co
                               uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
                               size_t workspace_bytes, int mode, void *stream);
 
+/* The same scan for callers that cannot allocate (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc) and have no workspace to pass: the scratch memory is an array
+ * inside the library, DCPQ_STATIC_SCRATCH_BYTES per GPU, held from the first call on that GPU until
+ * the process ends.  Inputs, outputs, order and error behaviour as dcpq_scan_candidates; the call
+ * itself allocates nothing.  A problem whose dcpq_scan_workspace_bytes exceeds
+ * dcpq_static_scratch_bytes() is refused with DCPQ_EWORKSPACE before anything is launched.  All
+ * calls on one GPU share the one array: two of them must not overlap in time (they would race),
+ * whichever streams they use. */
+#define DCPQ_STATIC_SCRATCH_BYTES (64u << 20)
+size_t dcpq_static_scratch_bytes(void);
+int dcpq_scan_candidates_static(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                                uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * refine_topk -- Sec. 3.3 "Refine step" (Alg. 3 refine / adc_refine, Eq. 2): exact re-ranking of
  * the candidates with the full tables, then the k best.

@@ -41,6 +41,8 @@ _SIGNATURES = {
     "dcpq_scan_plan": (_i, [_u64, _i, _i, _u32, _i, _vp, _i]),
     "dcpq_search_chunk": (_i, [_i, _i, _i]),
     "dcpq_scan_candidates_mode": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp, _sz, _i, _vp]),
+    "dcpq_static_scratch_bytes": (_sz, []),
+    "dcpq_scan_candidates_static": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp]),
     "dcpq_refine_workspace_bytes": (_sz, [_i, _u32]),
     "dcpq_refine_topk": (_i, [_vp, _vp, _u64, _i, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_search_workspace_bytes": (_sz, [_u64, _i, _i, _u32, _i]),
@@ -187,6 +189,19 @@ def scan_candidates(codes: torch.Tensor, qtab: torch.Tensor, r: int, workspace: 
                                                _dev(qtab, torch.uint8, "qtab"), nq, r, cand_id.data_ptr(),
                                                cand_qd.data_ptr(), workspace.data_ptr(), workspace.numel(), mode,
                                                _stream()))
+    return cand_id, cand_qd
+
+
+def scan_candidates_static(codes: torch.Tensor, qtab: torch.Tensor, r: int, cand_id: torch.Tensor,
+                           cand_qd: torch.Tensor):
+    """The scan through the entry point that allocates nothing: outputs are the caller's tensors,
+    the scratch memory is the library's static array (dcpq_static_scratch_bytes())."""
+    n, m = codes.shape
+    nq = qtab.shape[0]
+    assert qtab.shape[1:] == (m, 256) and cand_id.shape == (nq, r) and cand_qd.shape == (nq, r)
+    _check(lib().dcpq_scan_candidates_static(_dev(codes, torch.uint16, "codes"), n, m, _dev(qtab, torch.uint8, "qtab"),
+                                             nq, r, _dev(cand_id, torch.uint32, "cand_id"),
+                                             _dev(cand_qd, torch.uint8, "cand_qd"), _stream()))
     return cand_id, cand_qd
 
 

@@ -21,6 +21,8 @@
 // Workgroups walk a list of (query tile, block of 4 units) items with a grid stride, so the same
 // launch shape serves "all queries" and "the few flagged queries" (count read on the device).
 #include "common.h"
+#include <mutex>
+
 #include "scan_internal.h"
 
 namespace dcpq {
@@ -574,4 +576,57 @@ extern "C" int dcpq_scan_candidates_mode(const uint16_t *codes, uint64_t n_codes
                                          size_t workspace_bytes, int mode, void *stream)
 {
     return scan_checked(codes, n_codes, m, qtab, nq, r, cand_id, cand_qd, workspace, workspace_bytes, mode, stream);
+}
+
+// ---- the entry point that allocates nothing ------------------------------------------------------
+// For callers that cannot call hipMalloc (code under graph capture, tight serving loops, harnesses
+// that forbid allocation) and have no workspace to hand over: the scan's workspace is this array,
+// which every GPU the library runs on holds from the first call until the process ends.
+constexpr size_t kStaticScratchBytes = DCPQ_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMostDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMostDevices];      // device address of `scratch` on each GPU (the array's name is only a host-side stand-in)
+
+// Device address of the current device's copy of the array, looked up once per device.
+int static_scratch(void **out)
+{
+    int dev = 0;
+    DCPQ_CHECK_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMostDevices) return fail(DCPQ_EUNSUPPORTED, "scan_candidates_static: device %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        DCPQ_CHECK_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(DCPQ_EHIP, "scan_candidates_static: no device address for the static scratch array");
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DCPQ_OK;
+}
+}  // namespace
+
+extern "C" size_t dcpq_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+extern "C" int dcpq_scan_candidates_static(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                                           uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *stream)
+{
+    clear_error();
+    // the size check comes first: a problem that does not fit is refused before the device is touched
+    if (nq > 0 && m_supported(m) && n_codes >= 1 && r >= 1 && r <= (1u << 26)) {
+        const size_t need = dcpq_scan_workspace_bytes(n_codes, m, nq, r);
+        if (need > kStaticScratchBytes)
+            return fail(DCPQ_EWORKSPACE, "scan_candidates_static: the scan needs %zu bytes of scratch, the static array holds %zu",
+                        need, kStaticScratchBytes);
+    }
+    void *ws = nullptr;
+    if (nq > 0) {
+        const int rc = static_scratch(&ws);
+        if (rc) return rc;
+    }
+    // every counter the kernels expect at zero is cleared by the scan itself (a fill kernel, so the
+    // call may be captured), whatever the previous call left in the array
+    return scan_checked(codes, n_codes, m, qtab, nq, r, cand_id, cand_qd, ws, kStaticScratchBytes, DCPQ_SCAN_AUTO, stream);
 }
