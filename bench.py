@@ -1,14 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the two-pass derived-codebook PQ search on one MI355X.
 
-One step = the whole hot path (small tables + quantizer, scan + candidate selection, full tables,
-refine + top-k) for one batch of queries over the resident code array, through the C ABI.
-Prints ONE JSON line.  Workload: BASELINE's headline configuration (flat PQ 8x16, N = 100M,
-4096 queries, r = 4000, k = 100) unless --cfg / --n / --q say otherwise.
+One step = the whole hot path for one batch of queries over the resident code array, through the C
+ABI: small tables + quantizer, scan + candidate selection, full tables, refine + top-k (flat
+workloads, one dcpq_search call) or coarse probe, residual tables, scan of the probed lists, residual
+refine (inverted-index workload, one dcpq_ivf_search call).  Prints ONE JSON line.
+
+The headline workload is BASELINE's flat PQ 8x16, N = 100M, 4096 queries, r = 4000, k = 100
+(--cfg 2, the default).  Without --cfg the other four workloads are measured as well, more briefly,
+and reported under "other_workloads" of the same line; a failure there is recorded, never raised.
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -16,39 +21,54 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+FP64_MFMA_PEAK_TFLOPS = 78.6   # MI355X published dense fp64 matrix rate
 SCAN_STAGES = ("scan_fast", "scan_hist", "scan_tiecount", "scan_collect")
+METRIC = "queries/sec at k=100 + scan GB/s vs HBM peak (PQ 8x16, N=100M, 1 GPU)"
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=3)
-    ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--cfg", type=int, default=2, help="workload index in BASELINE.json (flat ones)")
-    ap.add_argument("--n", type=int, default=None, help="override database size (experiments only)")
-    ap.add_argument("--q", type=int, default=None, help="override query batch (experiments only)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--chunk", type=int, default=0, help="queries per chunk of the fused search (0 = default)")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also launch one 1 GiB calibration_copy_kernel (for scaling rocprofv3 --pmc traffic counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        return 2
+def timed(step, steps, warmup, binding, torch):
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    stages = binding.profile_read()
+    binding.profile_enable(False)
+    return elapsed, stages
 
-    import numpy as np
+
+def committed_traffic(kernel, workload):
+    """HBM-side bytes per launch from the committed rocprofv3 --pmc summary of this kernel and workload
+    (FETCH_SIZE + WRITE_SIZE scaled by the calibration copy), or None."""
+    prof = os.path.join(ROOT, "profiles", "%s_%s_counters.txt" % (kernel, workload.split("_")[0]))
+    if not os.path.exists(prof):
+        return None
+    m = re.search(r"measured traffic below the L2 = .*?\((\d+) bytes\)", open(prof).read())
+    return int(m.group(1)) if m else None
+
+
+def hbm_roofline(kernel, bytes_per_launch, total_ms, launches, steps, workload, limiter, extra=None):
+    avg_ms = total_ms / launches
+    achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+    traffic = committed_traffic(kernel, workload)
+    r = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+         "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "bytes_per_launch": bytes_per_launch,
+         "avg_launch_ms": round(avg_ms, 4), "launches_per_step": launches / steps, "limiter": limiter}
+    if traffic is not None:
+        r["hbm_traffic_frac"] = round(traffic / (avg_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    if extra:
+        r.update(extra)
+    return r
+
+
+def run_flat(w, args, steps, warmup, with_cpu, headline):
     import torch
     from paper_1905_06900_amd import binding, synth
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    binding.lib()
     dev = "cuda:0"
-    torch.cuda.set_device(0)
-    w = synth.WORKLOADS[args.cfg]
-    assert w.kind == "flat", "bench.py times the flat path; the IVF variant has its own tests"
-    w = synth.scaled(w, N=args.n, Q=args.q)
-
     t0 = time.perf_counter()
     data = synth.make_flat(w, dev)
     cb, codes, queries = data["codebooks"], data["codes"], data["queries"]
@@ -69,101 +89,89 @@ def main() -> int:
         binding.profile_copy(a, b)
         torch.cuda.synchronize()
         del a, b
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    binding.profile_enable(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    stages = binding.profile_read()
-    binding.profile_enable(False)
+    elapsed, stages = timed(step, steps, warmup, binding, torch)
+    ms_per_step = elapsed / steps * 1e3
+    qps = w.Q * steps / elapsed
 
-    ms_per_step = elapsed / args.steps * 1e3
-    qps = w.Q * args.steps / elapsed
-
-    # Roofline of the dominant kernel (the scan over the code stream).
+    # Roofline of the dominant kernel.
     code_bytes = 2 * w.m                                         # bytes per code per pass, as stored
-    qt = binding.scan_query_tile(w.m)
-    dom = max(SCAN_STAGES, key=lambda s: stages.get(s, (0.0, 0))[0])
-    dom_ms, dom_launches = stages[dom]
-    passes_per_step = sum((min(binding.search_chunk(w.m, w.Q, args.chunk), w.Q - q0) + qt - 1) // qt
-                          for q0 in range(0, w.Q, binding.search_chunk(w.m, w.Q, args.chunk)))
-    launches_per_step = dom_launches / args.steps
     chunk = binding.search_chunk(w.m, w.Q, args.chunk)
-    bytes_per_launch = passes_per_step * w.N * code_bytes / launches_per_step
-    avg_launch_s = dom_ms / dom_launches * 1e-3
-    achieved = bytes_per_launch / avg_launch_s / 1e9
-    scan_ms = sum(stages.get(s, (0.0, 0))[0] for s in SCAN_STAGES) / args.steps
-    # HBM-side bytes per launch of that kernel from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    # WRITE_SIZE scaled by the calibration copy); only meaningful for the workload it was taken on.
-    traffic = None
-    prof = os.path.join(ROOT, "profiles", "scan_fast_cfg2_counters.txt")
-    if dom == "scan_fast" and args.cfg == 2 and args.n is None and args.q is None and args.chunk == 0 and os.path.exists(prof):
-        import re
-        mt = re.search(r"measured traffic below the L2 = .*?\((\d+) bytes\)", open(prof).read())
-        if mt:
-            traffic = int(mt.group(1))
-    roofline = {
-        "bound": "hbm", "kernel": dom, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-        "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
-        "bytes_per_launch": bytes_per_launch, "avg_launch_ms": round(dom_ms / dom_launches, 4),
-        "launches_per_step": launches_per_step, "queries_per_pass": qt,
-        "code_passes_per_step": passes_per_step, "codes_per_pass": w.N,
-        "pairs_per_s": round(w.N * w.Q / (scan_ms * 1e-3), 1) if scan_ms > 0 else None,
-    }
-
-    # The same scan with the 16-query tile on one chunk: a quarter of the lookups per byte of code stream,
-    # i.e. the configuration in which pass one is bound by the stream and not by LDS lookups.  Context for
-    # `roofline` (which describes the configuration that gives the most queries/s), not part of `value`.
-    stream_variant = None
-    if w.m == 8 and dom == "scan_fast":
-        nq_v = min(chunk, w.Q)
-        qtab_v, _, _ = binding.build_small_tables(queries[:nq_v].contiguous(), derived, codes, w.r)
-        ws_v = torch.empty(binding.scan_workspace_bytes(w.N, w.m, nq_v, w.r), dtype=torch.uint8, device=dev)
-        binding.scan_candidates(codes, qtab_v, w.r, workspace=ws_v, mode=binding.SCAN_TILE16)
-        torch.cuda.synchronize()
-        binding.profile_enable(True)
-        for _ in range(2):
-            binding.scan_candidates(codes, qtab_v, w.r, workspace=ws_v, mode=binding.SCAN_TILE16)
-        torch.cuda.synchronize()
-        st_v = binding.profile_read()
-        binding.profile_enable(False)
-        plan_v = binding.scan_plan(w.N, w.m, nq_v, w.r, binding.SCAN_TILE16)
-        ms_v = st_v["scan_fast"][0] / st_v["scan_fast"][1]
-        bytes_v = plan_v["tiles"] * w.N * code_bytes
-        stream_variant = {
-            "query_tile": 16, "queries": nq_v, "bound": "hbm", "achieved": round(bytes_v / (ms_v * 1e-3) / 1e9, 1),
-            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(bytes_v / (ms_v * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "avg_launch_ms": round(ms_v, 4), "bytes_per_launch": bytes_v,
-        }
-        del ws_v, qtab_v
+    dom = max((s for s in stages if s != "misc" and stages[s][1]), key=lambda s: stages[s][0])
+    dom_ms, dom_launches = stages[dom]
+    scan_ms = sum(stages.get(s, (0.0, 0))[0] for s in SCAN_STAGES) / steps
+    if dom == "full_tables":
+        # 2 Q 65536 D flop per step on the double-precision matrix cores, and 4 Q m 65536 bytes of
+        # table writes: the bound is whichever roof the launch is closer to
+        flops = 2.0 * w.Q * 65536 * w.D / (dom_launches / steps)
+        wbytes = 4.0 * w.Q * w.m * 65536 / (dom_launches / steps)
+        avg_s = dom_ms / dom_launches * 1e-3
+        f_mfma, f_hbm = flops / avg_s / 1e12 / FP64_MFMA_PEAK_TFLOPS, wbytes / avg_s / 1e9 / HBM_PEAK_GBS
+        if f_mfma >= f_hbm:
+            roofline = {"bound": "mfma", "kernel": dom, "achieved": round(flops / avg_s / 1e12, 2),
+                        "peak": FP64_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(f_mfma, 4),
+                        "traffic": committed_traffic(dom, w.name), "flops_per_launch": flops,
+                        "avg_launch_ms": round(avg_s * 1e3, 4), "launches_per_step": dom_launches / steps,
+                        "limiter": "fp64 matrix instructions (K = dsub = %d per sub-quantizer)" % w.dsub}
+        else:
+            roofline = hbm_roofline(dom, wbytes, dom_ms, dom_launches, steps, w.name, "table writes to HBM")
+    else:
+        qt = binding.scan_plan(w.N, w.m, min(chunk, w.Q), w.r)["query_tile"]
+        passes_per_step = sum((min(chunk, w.Q - q0) + qt - 1) // qt for q0 in range(0, w.Q, chunk))
+        launches_per_step = dom_launches / steps
+        bytes_per_launch = passes_per_step * w.N * code_bytes / launches_per_step
+        limiter = ("LDS row reads + the SIMDs' vector/matrix instruction port (%d queries share one pass over the "
+                   "codes; the passes in flight share the stream through the L2)" % qt) if dom == "scan_fast" \
+            else "LDS byte gathers (three-pass scan)"
+        roofline = hbm_roofline(dom, bytes_per_launch, dom_ms, dom_launches, steps, w.name, limiter, {
+            "queries_per_pass": qt, "code_passes_per_step": passes_per_step, "codes_per_pass": w.N,
+            "pairs_per_s": round(w.N * w.Q / (scan_ms * 1e-3), 1) if scan_ms > 0 else None})
 
     out = {
-        "metric": "queries/sec at k=100 + scan GB/s vs HBM peak (PQ 8x16, N=100M, 1 GPU)",
-        "value": round(qps, 2), "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u8 scan / f32 refine", "data": "synthetic",
+        "value": round(qps, 2), "unit": "queries/s", "ms_per_step": round(ms_per_step, 3),
         "config": {"workload": w.name, "N": w.N, "queries": w.Q, "m": w.m, "dsub": w.dsub, "r": w.r, "k": w.k,
                    "code_bytes": code_bytes, "seed": w.seed},
         "roofline": roofline,
-        "scan_stream_variant": stream_variant,
-        "stage_ms_per_step": {s: round(v[0] / args.steps, 3) for s, v in stages.items() if v[1]},
+        "stage_ms_per_step": {s: round(v[0] / steps, 3) for s, v in stages.items() if v[1]},
         "setup_s": round(setup_s, 2),
     }
 
-    if not args.no_cpu_baseline:
+    if headline:
+        # What a kernel that reads the code array once reaches on this device, and pass one in the
+        # configuration where it really is bound by that stream: a single tile of 16 queries, every
+        # code read from HBM once (context for `roofline`, not part of `value`).
+        out["hbm_stream_read_gbs"] = round(binding.stream_read_gbs(codes.view(torch.uint8).view(-1)), 1)
+        if w.m == 8:
+            qtab_v, _, _ = binding.build_small_tables(queries[:16].contiguous(), derived, codes, w.r)
+            ws_v = torch.empty(binding.scan_workspace_bytes(w.N, w.m, 16, w.r), dtype=torch.uint8, device=dev)
+
+            def one_tile():
+                binding.scan_candidates(codes, qtab_v, w.r, workspace=ws_v, mode=binding.SCAN_TILE16)
+            _, st_v = timed(one_tile, 3, 1, binding, torch)
+            ms_v = st_v["scan_fast"][0] / st_v["scan_fast"][1]
+            gbs = w.N * code_bytes / (ms_v * 1e-3) / 1e9
+            out["scan_single_tile"] = {
+                "queries": 16, "query_tile": 16, "passes": 1, "bound": "hbm", "achieved": round(gbs, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                "frac_of_stream_read": round(gbs / out["hbm_stream_read_gbs"], 4), "avg_launch_ms": round(ms_v, 4),
+                "bytes_per_launch": w.N * code_bytes, "traffic": committed_traffic("scan_fast_single_tile", w.name)}
+            del ws_v, qtab_v
+
+    if with_cpu:
         import oracle
         threads = oracle.num_threads()
-        nsample = min(w.Q, 2 * threads)
         cb_np, codes_np = synth.to_numpy(cb), synth.to_numpy(codes)
-        q_np = synth.to_numpy(queries)[:nsample]
         der_np = oracle.derive_codebooks(cb_np)
-        t0 = time.perf_counter()
-        ref = oracle.search_flat(cb_np, der_np, codes_np, q_np, w.r, w.k)
-        cpu_s = time.perf_counter() - t0
+        nsample = min(w.Q, 2 * threads)
+        for attempt in range(2):
+            q_np = synth.to_numpy(queries)[:nsample]
+            t0 = time.perf_counter()
+            ref = oracle.search_flat(cb_np, der_np, codes_np, q_np, w.r, w.k)
+            cpu_s = time.perf_counter() - t0
+            # the headline sample is grown once to about 10 s of oracle work
+            grown = min(w.Q, int(nsample * 10.0 / max(cpu_s, 1e-3)) // threads * threads)
+            if not headline or attempt or grown <= nsample:
+                break
+            nsample = grown
         got = synth.to_numpy(ids)[:nsample]
         out["cpu_baseline"] = {
             "value": round(nsample / cpu_s, 3), "unit": "queries/s", "cores": threads, "kind": "oracle",
@@ -171,6 +179,145 @@ def main() -> int:
             "seconds": round(cpu_s, 2),
             "result_ids_equal_fraction": float((got == ref["ids"]).mean()),
         }
+    del data, cb, codes, queries, ws
+    torch.cuda.empty_cache()
+    return out
+
+
+def run_ivf(w, args, steps, warmup, with_cpu):
+    import numpy as np
+    import torch
+    from paper_1905_06900_amd import binding, synth
+    dev = "cuda:0"
+    t0 = time.perf_counter()
+    d = synth.make_ivf(w, dev)
+    cb, coarse, offsets, codes, queries = d["codebooks"], d["coarse"], d["offsets"], d["codes"], d["queries"]
+    derived = binding.derive_codebooks(cb)                       # index build, not timed
+    plane = binding.pack_low_bytes(codes)                        # index build: the bytes pass one reads
+    ws = torch.empty(binding.ivf_search_workspace_bytes(w.Q, w.nlist, w.nprobe, w.m, w.r), dtype=torch.uint8, device=dev)
+    ids = torch.empty((w.Q, w.k), dtype=torch.uint32, device=dev)
+    dist = torch.empty((w.Q, w.k), dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+    setup_s = time.perf_counter() - t0
+
+    def step():
+        binding.ivf_search(queries, coarse, cb, derived, codes, offsets, w.nprobe, w.r, w.k, plane=plane,
+                           workspace=ws, ids=ids, dist=dist)
+
+    elapsed, stages = timed(step, steps, warmup, binding, torch)
+    qps = w.Q * steps / elapsed
+    # codes in the probed lists of the batch: what one pass of the scan streams (no two queries share them)
+    probe = binding.ivf_probe(queries, coarse, w.nprobe).long()
+    probed_codes = int((offsets[probe + 1] - offsets[probe]).sum().item())
+    dom = max((s for s in stages if s != "misc" and stages[s][1]), key=lambda s: stages[s][0])
+    dom_ms, dom_launches = stages[dom]
+    if dom == "ivf_scan":
+        roofline = hbm_roofline(dom, float(probed_codes) * w.m, dom_ms, dom_launches, steps, w.name,
+                                "the stream of low bytes of the probed lists from HBM (lane = code, byte gathers from LDS)",
+                                {"probed_codes_per_step": probed_codes, "bytes_per_code": w.m})
+    else:
+        roofline = {"bound": "alu", "kernel": dom, "achieved": None, "peak": None, "unit": None, "frac": None,
+                    "traffic": None, "avg_launch_ms": round(dom_ms / dom_launches, 4)}
+    out = {
+        "value": round(qps, 2), "unit": "queries/s", "ms_per_step": round(elapsed / steps * 1e3, 3),
+        "config": {"workload": w.name, "N": w.N, "queries": w.Q, "m": w.m, "dsub": w.dsub, "r": w.r, "k": w.k,
+                   "nlist": w.nlist, "nprobe": w.nprobe, "code_bytes": 2 * w.m, "scan_reads": "low-byte plane",
+                   "seed": w.seed},
+        "roofline": roofline,
+        "stage_ms_per_step": {s: round(v[0] / steps, 3) for s, v in stages.items() if v[1]},
+        "setup_s": round(setup_s, 2),
+    }
+    if with_cpu:
+        # The oracle walks only the probed lists: it gets a compact copy of the lists the sample's
+        # queries probe (lists renumbered, ids = positions in the compact array) and the library's
+        # own probe lists.
+        import oracle
+        threads = oracle.num_threads()
+        nsample = min(w.Q, 2 * threads)
+        pr = probe[:nsample]
+        lists = torch.unique(pr)
+        sizes = offsets[lists + 1] - offsets[lists]
+        off_c = torch.zeros(lists.numel() + 1, dtype=torch.int64, device=dev)
+        off_c[1:] = torch.cumsum(sizes, 0)
+        idx = torch.repeat_interleave(offsets[lists] - off_c[:-1], sizes) + torch.arange(int(off_c[-1]), device=dev)
+        codes_c = codes.view(torch.int16)[idx].contiguous().view(torch.uint16)
+        remap = torch.full((w.nlist,), -1, dtype=torch.int64, device=dev)
+        remap[lists] = torch.arange(lists.numel(), device=dev)
+        cb_np, der_np = synth.to_numpy(cb), oracle.derive_codebooks(synth.to_numpy(cb))
+        args_np = (cb_np, der_np, synth.to_numpy(codes_c), off_c.cpu().numpy(), synth.to_numpy(coarse[lists]),
+                   synth.to_numpy(queries[:nsample]), remap[pr].to(torch.int32).cpu().numpy(), w.r, w.k)
+        t0 = time.perf_counter()
+        ref = oracle.search_ivf(*args_np)
+        cpu_s = time.perf_counter() - t0
+        back = (idx.cpu().numpy())[np.minimum(ref["ids"].astype(np.int64), idx.numel() - 1)]
+        got = synth.to_numpy(ids)[:nsample]
+        out["cpu_baseline"] = {
+            "value": round(nsample / cpu_s, 3), "unit": "queries/s", "cores": threads, "kind": "oracle",
+            "sample": "%d queries of the batch over their own %d probed lists (%d codes), one query per thread"
+                      % (nsample, int(lists.numel()), int(off_c[-1])),
+            "seconds": round(cpu_s, 2),
+            "result_ids_equal_fraction": float((got.astype(np.int64) == back).mean()),
+        }
+    del d, cb, codes, queries, plane, ws
+    torch.cuda.empty_cache()
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--cfg", type=int, default=None, help="workload index in BASELINE.json (default: 2, the headline, "
+                    "with the four others measured briefly beside it)")
+    ap.add_argument("--n", type=int, default=None, help="override database size (experiments only)")
+    ap.add_argument("--q", type=int, default=None, help="override query batch (experiments only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-others", action="store_true", help="headline workload only")
+    ap.add_argument("--chunk", type=int, default=0, help="queries per chunk of the fused search (0 = default)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also launch one 1 GiB calibration_copy_kernel (for scaling rocprofv3 --pmc traffic counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1905_06900_amd import binding, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    binding.lib()
+    torch.cuda.set_device(0)
+    cfg = 2 if args.cfg is None else args.cfg
+    w = synth.scaled(synth.WORKLOADS[cfg], N=args.n, Q=args.q)
+    with_cpu = not args.no_cpu_baseline
+    if w.kind == "flat":
+        res = run_flat(w, args, args.steps, args.warmup, with_cpu, headline=True)
+    else:
+        res = run_ivf(w, args, args.steps, args.warmup, with_cpu)
+    out = {
+        "metric": METRIC, "value": res.pop("value"), "unit": res.pop("unit"), "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": res.pop("ms_per_step"), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "u8 scan / f32 refine", "data": "synthetic",
+    }
+    out.update(res)
+
+    if args.cfg is None and not args.no_others and args.n is None and args.q is None:
+        others = []
+        for c in (0, 1, 3, 4):
+            wo = synth.WORKLOADS[c]
+            try:
+                if wo.kind == "flat":
+                    r = run_flat(wo, args, 3, 1, with_cpu, headline=False)
+                else:
+                    r = run_ivf(wo, args, 3, 1, with_cpu)
+                r["steps"] = 3
+            except Exception as e:      # never let a side measurement take the headline line down
+                r = {"config": {"workload": wo.name}, "error": "%s: %s" % (type(e).__name__, e)}
+                torch.cuda.empty_cache()
+            others.append(r)
+        out["other_workloads"] = others
     print(json.dumps(out))
     return 0
 

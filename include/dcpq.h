@@ -17,8 +17,10 @@
  *     matching *_workspace_bytes call returns; its contents on entry do not matter, and two calls
  *     that share a workspace must not overlap in time.
  *   - Return value: DCPQ_OK or an error code; dcpq_last_error() then holds a message (thread
- *     local).  Arguments are validated on the host before anything is launched; on error nothing
- *     has been enqueued.
+ *     local).  Arguments are validated on the host before anything is launched: on DCPQ_EINVAL,
+ *     DCPQ_EWORKSPACE or DCPQ_EUNSUPPORTED nothing has been enqueued.  DCPQ_EHIP (a launch the
+ *     runtime refused) can come from any kernel of a call, after earlier ones were enqueued; the
+ *     outputs are then undefined.
  *   - Ties are always broken by the smaller vector id.  Ids are 32-bit: N < 2^32.
  */
 #ifndef DCPQ_H
@@ -173,8 +175,8 @@ int dcpq_search(const float *queries, int nq, const float *codebooks, const floa
                 size_t workspace_bytes, void *stream);
 
 /* =============================================================================================
- * Inverted-index variant (Sec. 2.2 inverted lists with residual encoding; Sec. 2.3 Index step and
- * "each step is repeated ma times"; Sec. 3.3 with derived codebooks).
+ * Inverted-index variant (Sec. 2.2: inverted lists with residual encoding; Sec. 2.3: the Index step,
+ * and every later step done once per probed list; Sec. 3.3 with derived codebooks).
  *
  * Layout: nlist cells with centres coarse[nlist][D]; list l holds the codes at positions
  * offsets[l] .. offsets[l+1]-1 of the code array (offsets: int64 [nlist+1], increasing, last one =
@@ -238,6 +240,18 @@ int dcpq_ivf_refine_topk(const float *queries, const float *coarse, int nlist, c
                          int nprobe, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
                          float *dist, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The four steps above in one call (Alg. 3 with an index: Index, Tables, Scan, Refine) for a batch
+ * of queries.  `plane` is the low-byte plane of `codes` from dcpq_pack_low_bytes, or NULL to scan
+ * the codes themselves; the probe lists, tables and candidates live in the workspace.  Short lists
+ * are padded as in the staged calls (id DCPQ_PAD_ID, distance +inf).
+ *   ids : uint32_t [nq][k]  dist : float [nq][k] (outputs)
+ *   workspace : dcpq_ivf_search_workspace_bytes(nq, nlist, nprobe, m, r), 256-byte aligned */
+size_t dcpq_ivf_search_workspace_bytes(int nq, int nlist, int nprobe, int m, uint32_t r);
+int dcpq_ivf_search(const float *queries, int nq, const float *coarse, int nlist, int nprobe,
+                    const float *codebooks, const float *derived, int m, int dsub, const uint16_t *codes,
+                    const uint8_t *plane, const int64_t *offsets, uint32_t r, uint32_t k, uint32_t *ids,
+                    float *dist, void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---------------------------------------------------------------------------------------------
  * Optional per-kernel timing (measurement aid, not part of the search).  While enabled, every
  * kernel the library launches is bracketed by two HIP events recorded on the stream it is launched
@@ -254,6 +268,12 @@ int dcpq_profile_read(int stage, double *total_ms, uint64_t *launches);
  * calibration_copy_kernel: reads `bytes`, writes `bytes`.  Hardware traffic counters collected for
  * the search kernels are scaled by what the same counters report for this copy of known size. */
 int dcpq_profile_copy(const void *src, void *dst, size_t bytes, void *stream);
+/* Read-only stream over `bytes` (multiple of 16) of device memory by a kernel named
+ * stream_read_kernel (stage "misc" of the timing above): the rate a kernel that reads an array once
+ * reaches on this device, the yardstick beside the published HBM peak for the scans that are bound
+ * by the code stream.  `sink` receives dcpq_profile_stream_read_sink_bytes() bytes of checksums. */
+size_t dcpq_profile_stream_read_sink_bytes(void);
+int dcpq_profile_stream_read(const void *src, size_t bytes, void *sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -56,11 +56,15 @@ _SIGNATURES = {
     "dcpq_pack_low_bytes": (_i, [_vp, _u64, _i, _vp, _vp]),
     "dcpq_ivf_refine_workspace_bytes": (_sz, [_i, _u32]),
     "dcpq_ivf_refine_topk": (_i, [_vp, _vp, _i, _vp, _i, _i, _vp, _vp, _vp, _i, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_ivf_search_workspace_bytes": (_sz, [_i, _i, _i, _i, _u32]),
+    "dcpq_ivf_search": (_i, [_vp, _i, _vp, _i, _i, _vp, _vp, _i, _i, _vp, _vp, _vp, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_profile_enable": (_i, [_i]),
     "dcpq_profile_stage_count": (_i, []),
     "dcpq_profile_stage_name": (C.c_char_p, [_i]),
     "dcpq_profile_read": (_i, [_i, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]),
     "dcpq_profile_copy": (_i, [_vp, _vp, _sz, _vp]),
+    "dcpq_profile_stream_read_sink_bytes": (_sz, []),
+    "dcpq_profile_stream_read": (_i, [_vp, _sz, _vp, _vp]),
     "dcpq_search": (_i, [_vp, _i, _vp, _vp, _i, _i, _vp, _u64, _u32, _u32, _vp, _vp, _i, _vp, _sz, _vp]),
 }
 
@@ -248,6 +252,20 @@ def search(queries: torch.Tensor, codebooks: torch.Tensor, derived: torch.Tensor
     return ids, dist
 
 
+def stream_read_gbs(t: torch.Tensor, reps: int = 3) -> float:
+    """GB/s of the read-only stream kernel over the bytes of `t` (timed with torch events on the current stream)."""
+    nbytes = t.numel() * t.element_size() // 16 * 16
+    sink = torch.empty(lib().dcpq_profile_stream_read_sink_bytes(), dtype=torch.uint8, device=t.device)
+    _check(lib().dcpq_profile_stream_read(t.data_ptr(), nbytes, sink.data_ptr(), _stream()))
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        _check(lib().dcpq_profile_stream_read(t.data_ptr(), nbytes, sink.data_ptr(), _stream()))
+    b.record()
+    b.synchronize()
+    return nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9
+
+
 def profile_enable(on: bool) -> None:
     _check(lib().dcpq_profile_enable(1 if on else 0))
 
@@ -340,6 +358,33 @@ def ivf_refine_topk(queries, coarse, codebooks, codes, offsets, probe, cand_id, 
         _dev(offsets, torch.int64, "offsets"), _dev(probe, torch.int32, "probe"), nprobe,
         _dev(cand_id, torch.uint32, "cand_id"), nq, r, k, ids.data_ptr(), dist.data_ptr(), ws.data_ptr(),
         ws.numel(), _stream()))
+    return ids, dist
+
+
+def ivf_search_workspace_bytes(nq: int, nlist: int, nprobe: int, m: int, r: int) -> int:
+    return lib().dcpq_ivf_search_workspace_bytes(nq, nlist, nprobe, m, r)
+
+
+def ivf_search(queries, coarse, codebooks, derived, codes, offsets, nprobe: int, r: int, k: int, plane=None,
+               workspace=None, ids=None, dist=None):
+    """Index, Tables, Scan, Refine in one call -> (ids u32 [nq][k], dist f32 [nq][k])"""
+    m, _, dsub = codebooks.shape
+    nq = queries.shape[0]
+    nlist = coarse.shape[0]
+    assert queries.shape == (nq, m * dsub) and coarse.shape[1] == m * dsub and codes.shape[1] == m
+    dev = queries.device
+    if ids is None:
+        ids = torch.empty((nq, k), dtype=torch.uint32, device=dev)
+    if dist is None:
+        dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = _workspace(ivf_search_workspace_bytes(nq, nlist, nprobe, m, r), dev)
+    _check(lib().dcpq_ivf_search(
+        _dev(queries, torch.float32, "queries"), nq, _dev(coarse, torch.float32, "coarse"), nlist, nprobe,
+        _dev(codebooks, torch.float32, "codebooks"), _dev(derived, torch.float32, "derived"), m, dsub,
+        _dev(codes, torch.uint16, "codes"), 0 if plane is None else _dev(plane, torch.uint8, "plane"),
+        _dev(offsets, torch.int64, "offsets"), r, k, ids.data_ptr(), dist.data_ptr(), workspace.data_ptr(),
+        workspace.numel(), _stream()))
     return ids, dist
 
 

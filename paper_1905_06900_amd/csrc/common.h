@@ -46,7 +46,8 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Stages reported by the optional event-based profiler (dcpq_profile_*).
 enum Stage {
     kStageSmallTables = 0, kStageScanHist, kStageScanTieCount, kStageScanCollect, kStageScanFast,
-    kStageSelect, kStageFullTables, kStageRefine, kStageIvf, kStageMisc, kNumStages
+    kStageSelect, kStageFullTables, kStageRefine, kStageIvf, kStageMisc,
+    kStageIvfProbe, kStageIvfTables, kStageIvfScan, kStageIvfRefine, kStagePlainScan, kNumStages
 };
 namespace prof {
 bool enabled();

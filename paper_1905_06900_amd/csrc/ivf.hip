@@ -1,5 +1,5 @@
-// Alg. 3 with an inverted index and residual encoding (Sec. 2.2, Sec. 2.3 "each step is repeated
-// ma times", Sec. 3.3).  List l holds the codes at positions offsets[l] .. offsets[l+1]-1 of the
+// Alg. 3 with an inverted index and residual encoding (Sec. 2.2; Sec. 2.3: every step after the
+// Index step is done once per probed list; Sec. 3.3).  List l holds the codes at positions offsets[l] .. offsets[l+1]-1 of the
 // code array (a vector's id is its position); codes quantize the residual x - c_l.
 //
 //   Index   ivf_probe           the nprobe closest cell centres per query (matrix cores, fp64)
@@ -725,7 +725,7 @@ static int ivf_scan_m(const CodeT *codes, const int64_t *offsets, const int32_t 
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<sample>");
     rc = launch_sample_threshold(shist, nq, r, 0, t_cur, st);     // 0: the sample's own r-th smallest
     if (rc) return rc;
-    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_single_kernel<M, CodeT>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
+    DCPQ_LAUNCH(kStageIvfScan, st, (ivf_scan_single_kernel<M, CodeT>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
                 lds_tab + 4 * 64 * 8, codes, units, nunits, qtab, nprobe, r, p.cap, p.upd, p.qflush, t_cur, fcount, chist,
                 fkeys);
     DCPQ_CHECK_LAUNCH("ivf_scan_single_kernel");
@@ -781,9 +781,9 @@ extern "C" int dcpq_ivf_probe(const float *queries, int nq, int D, const float *
     if (workspace_bytes < need) return fail(DCPQ_EWORKSPACE, "ivf_probe: workspace %zu < %zu bytes", workspace_bytes, need);
     hipStream_t st = as_stream(stream);
     float *dist = static_cast<float *>(workspace);
-    int rc = launch_distance_tables(queries, nq, coarse, 1, D, nlist, dist, kStageIvf, st);
+    int rc = launch_distance_tables(queries, nq, coarse, 1, D, nlist, dist, kStageIvfProbe, st);
     if (rc) return rc;
-    DCPQ_LAUNCH(kStageIvf, st, ivf_select_probe_kernel, dim3(nq), dim3(1024), 0, dist, nlist, nprobe, probe);
+    DCPQ_LAUNCH(kStageIvfProbe, st, ivf_select_probe_kernel, dim3(nq), dim3(1024), 0, dist, nlist, nprobe, probe);
     DCPQ_CHECK_LAUNCH("ivf_select_probe_kernel");
     return DCPQ_OK;
 }
@@ -822,13 +822,13 @@ extern "C" int dcpq_ivf_build_small_tables(const float *queries, int nq, const f
             attr_done = true;
         }
     }
-    DCPQ_LAUNCH(kStageIvf, st, ivf_tables_kernel<0>, tgrid, dim3(256), lds, queries, coarse, probe, nprobe,
+    DCPQ_LAUNCH(kStageIvfTables, st, ivf_tables_kernel<0>, tgrid, dim3(256), lds, queries, coarse, probe, nprobe,
                 derived, m, dsub, qmin_bits, bounds, qtab);
     DCPQ_CHECK_LAUNCH("ivf_tables_kernel<min>");
-    DCPQ_LAUNCH(kStageIvf, st, ivf_qmax_kernel, dim3(nq), dim3(256), 0, queries, coarse, probe, nprobe, derived, m, dsub,
+    DCPQ_LAUNCH(kStageIvfTables, st, ivf_qmax_kernel, dim3(nq), dim3(256), 0, queries, coarse, probe, nprobe, derived, m, dsub,
                 codes, offsets, r, qmin_bits, bounds);
     DCPQ_CHECK_LAUNCH("ivf_qmax_kernel");
-    DCPQ_LAUNCH(kStageIvf, st, ivf_tables_kernel<1>, tgrid, dim3(256), lds, queries, coarse, probe, nprobe,
+    DCPQ_LAUNCH(kStageIvfTables, st, ivf_tables_kernel<1>, tgrid, dim3(256), lds, queries, coarse, probe, nprobe,
                 derived, m, dsub, qmin_bits, bounds, qtab);
     DCPQ_CHECK_LAUNCH("ivf_tables_kernel<quantize>");
     return DCPQ_OK;
@@ -954,7 +954,7 @@ extern "C" int dcpq_ivf_refine_topk(const float *queries, const float *coarse, i
         DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&ivf_refine_kernel<MV>),                  \
                                            hipFuncAttributeMaxDynamicSharedMemorySize,                              \
                                            static_cast<int>(sizeof(uint64_t) * kSortLdsKeys)));                      \
-        DCPQ_LAUNCH(kStageIvf, st, ivf_refine_kernel<MV>, dim3(nq), dim3(1024), lds, queries, coarse, codebooks, dsub, \
+        DCPQ_LAUNCH(kStageIvfRefine, st, ivf_refine_kernel<MV>, dim3(nq), dim3(1024), lds, queries, coarse, codebooks, dsub, \
                     codes, offsets, probe, nprobe, cand_id, r, k, np2, use_lds, spill, ids, dist);                   \
         break;
     switch (m) {
@@ -965,4 +965,74 @@ extern "C" int dcpq_ivf_refine_topk(const float *queries, const float *coarse, i
 #undef DCPQ_LAUNCH_IVF_REFINE
     DCPQ_CHECK_LAUNCH("ivf_refine_kernel");
     return DCPQ_OK;
+}
+
+// ---- the whole inverted-index search in one call ------------------------------------------------
+namespace {
+struct IvfSearchPlan {
+    size_t off_probe, off_qtab, off_bounds, off_cand_id, off_cand_qd, off_count, off_sub, sub_bytes, total;
+};
+IvfSearchPlan plan_ivf_search(int nq, int nlist, int nprobe, int m, uint32_t r)
+{
+    IvfSearchPlan p{};
+    const size_t Q = static_cast<size_t>(nq);
+    size_t off = 0;
+    p.off_probe = off;   off = align_up(off + sizeof(int32_t) * Q * nprobe, 256);
+    p.off_qtab = off;    off = align_up(off + Q * nprobe * m * kSmallSize, 256);
+    p.off_bounds = off;  off = align_up(off + sizeof(float) * 2 * Q, 256);
+    p.off_cand_id = off; off = align_up(off + sizeof(uint32_t) * Q * r, 256);
+    p.off_cand_qd = off; off = align_up(off + Q * r, 256);
+    p.off_count = off;   off = align_up(off + sizeof(uint32_t) * Q, 256);
+    // the four steps run one after the other on the stream and share one scratch region
+    size_t sub = dcpq_ivf_probe_workspace_bytes(nq, nlist);
+    const size_t others[] = {dcpq_ivf_tables_workspace_bytes(nq), dcpq_ivf_scan_workspace_bytes(nq, r),
+                             dcpq_ivf_refine_workspace_bytes(nq, r)};
+    for (size_t o : others) sub = o > sub ? o : sub;
+    p.off_sub = off;     p.sub_bytes = align_up(sub, 256); off += p.sub_bytes;
+    p.total = off;
+    return p;
+}
+}  // namespace
+
+extern "C" size_t dcpq_ivf_search_workspace_bytes(int nq, int nlist, int nprobe, int m, uint32_t r)
+{
+    if (nq <= 0 || nlist <= 0 || nprobe <= 0 || nprobe > nlist || !m_supported(m) || r == 0 || r > (1u << 26)) return 0;
+    return plan_ivf_search(nq, nlist, nprobe, m, r).total;
+}
+
+extern "C" int dcpq_ivf_search(const float *queries, int nq, const float *coarse, int nlist, int nprobe,
+                               const float *codebooks, const float *derived, int m, int dsub, const uint16_t *codes,
+                               const uint8_t *plane, const int64_t *offsets, uint32_t r, uint32_t k, uint32_t *ids,
+                               float *dist, void *workspace, size_t workspace_bytes, void *stream)
+{
+    clear_error();
+    int rc = ivf_check_common("ivf_search", nq, m, dsub, nlist, nprobe);
+    if (rc) return rc;
+    DCPQ_REQUIRE(r >= 1 && r <= (1u << 26) && k >= 1 && k <= r, "ivf_search: needs 1 <= k <= r <= 2^26 (k=%u r=%u)", k, r);
+    if (nq == 0) return DCPQ_OK;
+    DCPQ_REQUIRE(queries && coarse && codebooks && derived && codes && offsets && ids && dist && workspace,
+                 "ivf_search: null pointer");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "ivf_search: workspace must be 256-byte aligned");
+    const IvfSearchPlan p = plan_ivf_search(nq, nlist, nprobe, m, r);
+    if (workspace_bytes < p.total) return fail(DCPQ_EWORKSPACE, "ivf_search: workspace %zu < %zu bytes", workspace_bytes, p.total);
+    uint8_t *base = static_cast<uint8_t *>(workspace);
+    int32_t *probe = reinterpret_cast<int32_t *>(base + p.off_probe);
+    uint8_t *qtab = base + p.off_qtab;
+    float *bounds = reinterpret_cast<float *>(base + p.off_bounds);
+    uint32_t *cand_id = reinterpret_cast<uint32_t *>(base + p.off_cand_id);
+    uint8_t *cand_qd = base + p.off_cand_qd;
+    uint32_t *count = reinterpret_cast<uint32_t *>(base + p.off_count);
+    void *sub = base + p.off_sub;
+    rc = dcpq_ivf_probe(queries, nq, m * dsub, coarse, nlist, nprobe, probe, sub, p.sub_bytes, stream);
+    if (rc) return rc;
+    rc = dcpq_ivf_build_small_tables(queries, nq, coarse, nlist, probe, nprobe, derived, m, dsub, codes, offsets, r, qtab,
+                                     bounds, sub, p.sub_bytes, stream);
+    if (rc) return rc;
+    rc = plane ? dcpq_ivf_scan_candidates_packed(plane, offsets, nlist, m, probe, nprobe, qtab, nq, r, cand_id, cand_qd,
+                                                 count, sub, p.sub_bytes, stream)
+               : dcpq_ivf_scan_candidates(codes, offsets, nlist, m, probe, nprobe, qtab, nq, r, cand_id, cand_qd, count, sub,
+                                          p.sub_bytes, stream);
+    if (rc) return rc;
+    return dcpq_ivf_refine_topk(queries, coarse, nlist, codebooks, m, dsub, codes, offsets, probe, nprobe, cand_id, nq, r,
+                                k, ids, dist, sub, p.sub_bytes, stream);
 }

@@ -13,6 +13,7 @@ static const char *const kNames[kNumStages] = {
     "small_tables", "scan_hist", "scan_tiecount", "scan_collect", "scan_fast", "select",
     "full_tables",
     "refine_topk", "ivf", "misc",
+    "ivf_probe", "ivf_tables", "ivf_scan", "ivf_refine", "plain_scan",
 };
 
 struct Pending { int stage; hipEvent_t a, b; };
@@ -95,6 +96,44 @@ extern "C" int dcpq_profile_copy(const void *src, void *dst, size_t bytes, void 
     hipLaunchKernelGGL(calibration_copy_kernel, dim3(8192), dim3(256), 0, as_stream(stream),
                        static_cast<const uint4 *>(src), static_cast<uint4 *>(dst), bytes / 16);
     DCPQ_CHECK_LAUNCH("calibration_copy_kernel");
+    return DCPQ_OK;
+}
+
+// Read-only stream over `n` 16-byte words: what a kernel that only reads an array once can reach on
+// this chip (the yardstick for the HBM-bound scans).  Every thread keeps 8 independent 16-byte loads
+// in flight; the XOR of what it read goes to `sink` so that the loads cannot be dropped.
+constexpr int kStreamReadBlocks = 256 * 16;
+__global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ src, size_t n, uint32_t *__restrict__ sink)
+{
+    const size_t stride = static_cast<size_t>(gridDim.x) * blockDim.x;
+    size_t i = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    uint4 acc = make_uint4(0, 0, 0, 0);
+    for (; i + 7 * stride < n; i += 8 * stride) {
+        uint4 x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = src[i + u * stride];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { acc.x ^= x[u].x; acc.y ^= x[u].y; acc.z ^= x[u].z; acc.w ^= x[u].w; }
+    }
+    for (; i < n; i += stride) {
+        const uint4 x = src[i];
+        acc.x ^= x.x; acc.y ^= x.y; acc.z ^= x.z; acc.w ^= x.w;
+    }
+    sink[static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
+}
+
+extern "C" size_t dcpq_profile_stream_read_sink_bytes(void) { return sizeof(uint32_t) * kStreamReadBlocks * 256; }
+
+extern "C" int dcpq_profile_stream_read(const void *src, size_t bytes, void *sink, void *stream)
+{
+    clear_error();
+    DCPQ_REQUIRE(src && sink && bytes % 16 == 0, "profile_stream_read: needs non-null pointers and a multiple of 16 bytes");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(src) & 15) == 0 && (reinterpret_cast<uintptr_t>(sink) & 3) == 0,
+                 "profile_stream_read: alignment");
+    if (bytes == 0) return DCPQ_OK;
+    DCPQ_LAUNCH(kStageMisc, as_stream(stream), stream_read_kernel, dim3(kStreamReadBlocks), dim3(256), 0,
+                static_cast<const uint4 *>(src), bytes / 16, static_cast<uint32_t *>(sink));
+    DCPQ_CHECK_LAUNCH("stream_read_kernel");
     return DCPQ_OK;
 }
 

@@ -343,7 +343,10 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode)
         p.codes_per_block = static_cast<uint32_t>(cpb);
         p.fblocks = static_cast<uint32_t>((rest + cpb - 1) / cpb);
         p.slices = p.fblocks < static_cast<uint32_t>(kFastSlices) ? p.fblocks : kFastSlices;
-        p.cap = 32 * r / p.slices < 1024 ? 1024 : 32 * r / p.slices;   // 32 r per query in all: twice the even share
+        {
+            const uint64_t share = 32ull * r / p.slices;         // 32 r per query in all: twice the even share
+            p.cap = static_cast<uint32_t>(share < 1024 ? 1024 : share);
+        }
         p.upd = r / 16 < 16 ? 16 : r / 16;                   // appends to one slice between bound updates
         // Candidates waiting in the wavefronts' queues are invisible to the bound.  With few queries and
         // thousands of wavefronts they would outnumber r, so a wavefront hands its queue over as soon as
@@ -525,7 +528,7 @@ extern "C" int dcpq_scan_plan(uint64_t n_codes, int m, int nq, uint32_t r, int m
 
 extern "C" size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r)
 {
-    if (nq <= 0 || !m_supported(m) || n_codes == 0 || r == 0) return 0;
+    if (nq <= 0 || !m_supported(m) || n_codes == 0 || r == 0 || r > (1u << 26)) return 0;
     // enough for every algorithm the caller may ask for
     size_t most = 0;
     const int modes[] = {DCPQ_SCAN_AUTO, DCPQ_SCAN_THREE_PASS, DCPQ_SCAN_TILE16, DCPQ_SCAN_TILE32, DCPQ_SCAN_TILE64};

@@ -27,8 +27,20 @@ static SearchPlan plan_search(uint64_t n_codes, int m, int nq, uint32_t r, int c
     p.off_cand_id = off; off = align_up(off + sizeof(uint32_t) * static_cast<size_t>(chunk) * r, 256);
     p.off_cand_qd = off; off = align_up(off + static_cast<size_t>(chunk) * r, 256);
     p.off_tables = off;  off = align_up(off + sizeof(float) * static_cast<size_t>(chunk) * m * kFullSize, 256);
-    p.off_scan = off;    off = align_up(off + dcpq_scan_workspace_bytes(n_codes, m, chunk, r), 256);
-    p.off_refine = off;  off = align_up(off + dcpq_refine_workspace_bytes(chunk, r), 256);
+    // The scan and the refinement lay their scratch out for the number of queries they are given, and
+    // a smaller batch does not always need less (fewer queries can mean more units or slices), so
+    // the regions hold the larger of what a full chunk and what the ragged last chunk need: those
+    // are the only two batch sizes the loop below ever passes.
+    const int tail = nq % chunk;
+    size_t scan_bytes = dcpq_scan_workspace_bytes(n_codes, m, chunk, r);
+    size_t refine_bytes = dcpq_refine_workspace_bytes(chunk, r);
+    if (tail) {
+        const size_t st = dcpq_scan_workspace_bytes(n_codes, m, tail, r), rt = dcpq_refine_workspace_bytes(tail, r);
+        scan_bytes = st > scan_bytes ? st : scan_bytes;
+        refine_bytes = rt > refine_bytes ? rt : refine_bytes;
+    }
+    p.off_scan = off;    off = align_up(off + scan_bytes, 256);
+    p.off_refine = off;  off = align_up(off + refine_bytes, 256);
     p.total = off;
     return p;
 }
@@ -45,7 +57,7 @@ extern "C" int dcpq_search_chunk(int m, int nq, int chunk_queries)
 
 extern "C" size_t dcpq_search_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r, int chunk_queries)
 {
-    if (nq <= 0 || !m_supported(m) || n_codes == 0 || r == 0) return 0;
+    if (nq <= 0 || !m_supported(m) || n_codes == 0 || r == 0 || r > (1u << 26)) return 0;
     return plan_search(n_codes, m, nq, r, chunk_queries).total;
 }
 
@@ -59,6 +71,7 @@ extern "C" int dcpq_search(const float *queries, int nq, const float *codebooks,
     if (!dcpq_shape_supported(m, dsub)) return fail(DCPQ_EUNSUPPORTED, "search: m=%d dsub=%d not supported", m, dsub);
     DCPQ_REQUIRE(n_codes >= 1 && n_codes < (1ull << 32), "search: n_codes out of range");
     DCPQ_REQUIRE(r >= 1 && r <= n_codes && k >= 1 && k <= r, "search: needs 1 <= k <= r <= n_codes");
+    DCPQ_REQUIRE(r <= (1u << 26), "search: r=%u above the supported 2^26", r);
     if (nq == 0) return DCPQ_OK;
     DCPQ_REQUIRE(queries && codebooks && derived && codes && ids && dist && workspace, "search: null pointer");
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "search: workspace must be 256-byte aligned");

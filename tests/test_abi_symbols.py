@@ -81,3 +81,25 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_lib", None)
     with pytest.raises(FileNotFoundError):
         binding.lib()
+
+
+def test_search_workspace_covers_a_ragged_last_chunk(lib):
+    """The scan lays its scratch out for the batch it is given, and a smaller batch can need more
+    (fewer queries: more units, more slices).  The fused search must reserve for the full chunks and
+    for the last, ragged one."""
+    lib.dcpq_search_workspace_bytes.restype = ctypes.c_size_t
+    lib.dcpq_search_workspace_bytes.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_uint32, ctypes.c_int]
+    lib.dcpq_scan_workspace_bytes.restype = ctypes.c_size_t
+    lib.dcpq_scan_workspace_bytes.argtypes = [ctypes.c_uint64, ctypes.c_int, ctypes.c_int, ctypes.c_uint32]
+    cases = [(10_000_000, 2, 64, 48, 1000), (1000, 1, 32768, 32746, 10), (10_000_000, 16, 8192, 8151, 100),
+             (100_000, 8, 64, 1, 500), (5_000_000, 4, 100, 37, 2000)]
+    for n, m, chunk, tail, r in cases:
+        full_only = lib.dcpq_search_workspace_bytes(n, m, chunk, r, chunk)
+        with_tail = lib.dcpq_search_workspace_bytes(n, m, chunk + tail, r, chunk)
+        extra = lib.dcpq_scan_workspace_bytes(n, m, tail, r) - lib.dcpq_scan_workspace_bytes(n, m, chunk, r)
+        assert with_tail >= full_only
+        if extra > 0:
+            assert with_tail - full_only >= extra - 256, (n, m, chunk, tail, r)
+    # r above the supported range: no size is promised
+    assert lib.dcpq_search_workspace_bytes(1 << 28, 8, 16, (1 << 26) + 1, 0) == 0
+    assert lib.dcpq_scan_workspace_bytes(1 << 28, 8, 16, (1 << 26) + 1) == 0

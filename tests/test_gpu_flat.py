@@ -43,6 +43,24 @@ def test_cfg0_scaled_fused_search_matches_staged(case0):
     np.testing.assert_array_equal(to_np(dist), to_np(c.dist))
 
 
+def test_fused_search_m2_with_a_ragged_last_chunk():
+    # m = 2 goes through the three-pass scan, whose scratch layout depends on the batch size: the
+    # last chunk (48 queries after a chunk of 64) lays it out differently from the full chunks
+    w = dataclasses.replace(small_flat(2, 120_007, 112, 300), m=2, dsub=12)
+    print("fused search m=2 N=%d Q=%d chunk 64" % (w.N, w.Q), flush=True)
+    dev = DEV
+    cb = synth.hierarchical_codebooks(2, 12, w.b, w.pbits, lambda shape, g: 0.3 * torch.randn(
+        shape, generator=g, device=dev, dtype=torch.float32), 0.03, dev, w.seed + 1)
+    codes = synth.random_codes(w.N, 2, dev, w.seed + 2).view(torch.uint16)
+    g = torch.Generator(device=dev); g.manual_seed(w.seed + 3)
+    queries = 0.3 * torch.randn((w.Q, 24), generator=g, device=dev, dtype=torch.float32)
+    c = FlatCase(w, dev, data=dict(codebooks=cb, codes=codes, queries=queries))
+    ids, dist = binding.search(c.queries, c.cb, c.derived, c.codes, w.r, w.k, chunk_queries=64)
+    torch.cuda.synchronize()
+    c.oracle(qsel=[0, 63, 64, 65, 100, 111])
+    c.check_pass_two(ids, dist)
+
+
 def test_full_tables_against_fp64_definition(case0):
     c = case0
     T = to_np(c.tables)

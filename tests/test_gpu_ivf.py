@@ -16,13 +16,18 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-def run_ivf_case(d, nprobe, r, k, check_probe=True):
+def run_ivf_case(d, nprobe, r, k, check_probe=True, plane=False, fused=False):
+    """plane: the scan reads the low-byte plane instead of the codes; fused: the final ids and distances come
+    from the one-call search (whose probe lists are the staged ones: same kernels, same inputs)."""
     cb, coarse, offsets, codes, queries = d["codebooks"], d["coarse"], d["offsets"], d["codes"], d["queries"]
     derived = binding.derive_codebooks(cb)
+    low = binding.pack_low_bytes(codes) if plane else None
     probe = binding.ivf_probe(queries, coarse, nprobe)
     qtab, bounds = binding.ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r)
-    cand_id, cand_qd, count = binding.ivf_scan_candidates(codes, offsets, probe, qtab, r)
+    cand_id, cand_qd, count = binding.ivf_scan_candidates(low if plane else codes, offsets, probe, qtab, r)
     ids, dist = binding.ivf_refine_topk(queries, coarse, cb, codes, offsets, probe, cand_id, k)
+    if fused:
+        ids, dist = binding.ivf_search(queries, coarse, cb, derived, codes, offsets, nprobe, r, k, plane=low)
     torch.cuda.synchronize()
 
     cb_np, coarse_np, off_np = to_np(cb), to_np(coarse), to_np(offsets)
@@ -122,25 +127,32 @@ def test_ivf_argument_errors():
     assert e.value.code == binding.EUNSUPPORTED
 
 
-def test_low_byte_plane_gives_the_same_candidates():
-    """pack_low_bytes is the low byte of every sub-code, and the scan of probed lists returns the same
-    candidate ids / integer distances / counts from the plane as from the codes (ragged N, padded lists)."""
+def test_low_byte_plane_scan_against_the_oracle():
+    """pack_low_bytes is the low byte of every sub-code, and the scan of probed lists reading the plane gives the
+    oracle's candidate ids / integer distances / counts (ragged N, padded lists)."""
     for (N, Q, r, nlist, nprobe) in [(300_007, 23, 500, 512, 16), (3001, 7, 300, 64, 5)]:
         w = synth.scaled(synth.WORKLOADS[3], N=N, Q=Q, r=r, nlist=nlist, nprobe=nprobe)
         print("ivf plane case: N=%d Q=%d r=%d nlist=%d nprobe=%d" % (N, Q, r, nlist, nprobe), flush=True)
         d = synth.make_ivf(w, DEV)
-        cb, coarse, offsets, codes, queries = d["codebooks"], d["coarse"], d["offsets"], d["codes"], d["queries"]
-        plane = binding.pack_low_bytes(codes)
+        plane = binding.pack_low_bytes(d["codes"])
         torch.cuda.synchronize()
-        np.testing.assert_array_equal(to_np(plane), (to_np(codes) & 255).astype(np.uint8))
-        derived = binding.derive_codebooks(cb)
-        probe = binding.ivf_probe(queries, coarse, nprobe)
-        qtab, _ = binding.ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r)
-        a = binding.ivf_scan_candidates(codes, offsets, probe, qtab, r)
-        b = binding.ivf_scan_candidates(plane, offsets, probe, qtab, r)
-        torch.cuda.synchronize()
-        for x, y, name in zip(a, b, ("cand_id", "cand_qd", "count")):
-            np.testing.assert_array_equal(to_np(x), to_np(y), err_msg=name)
+        np.testing.assert_array_equal(to_np(plane), (to_np(d["codes"]) & 255).astype(np.uint8))
+        run_ivf_case(d, nprobe, r, 50, plane=True)
+
+
+def test_ivf_search_in_one_call_against_the_oracle():
+    for use_plane in (False, True):
+        w = synth.scaled(synth.WORKLOADS[3], N=200_003, Q=19, r=400, nlist=256, nprobe=12)
+        print("ivf fused search: N=%d Q=%d plane=%s" % (w.N, w.Q, use_plane), flush=True)
+        d = synth.make_ivf(w, DEV)
+        run_ivf_case(d, w.nprobe, w.r, w.k, plane=use_plane, fused=True)
+    # a workspace one byte short is refused, nothing is launched
+    cb, q = d["codebooks"], d["queries"]
+    need = binding.ivf_search_workspace_bytes(q.shape[0], 256, 12, 8, 400)
+    with pytest.raises(binding.DcpqError) as e:
+        binding.ivf_search(q, d["coarse"], cb, binding.derive_codebooks(cb), d["codes"], d["offsets"], 12, 400, 100,
+                           workspace=torch.empty(need - 256, dtype=torch.uint8, device=DEV))
+    assert e.value.code == binding.EWORKSPACE
 
 
 @pytest.mark.parametrize("m", [1, 2, 4, 16, 32])
