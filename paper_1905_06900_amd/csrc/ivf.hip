@@ -348,7 +348,12 @@ __global__ __launch_bounds__(256) void ivf_plan_kernel(const int32_t *__restrict
     if (tid == 0) {
         uint64_t total = 0;
         for (int s = 0; s < nprobe; ++s) { const int l = static_cast<int>(key[s] >> 32); total += static_cast<uint64_t>(offsets[l + 1] - offsets[l]); }
-        uint64_t unit = (total + (kIvfUnitsPerQuery - nprobe) - 1) / (kIvfUnitsPerQuery - nprobe);
+        // three units per probed list on average, and at least 512 less one per list in all (measured: fewer,
+        // longer units leave the chip unevenly loaded, more of them pay the latency of a wavefront's first
+        // loads too often); never more than the unit table holds
+        uint64_t want = 4ull * nprobe < 512 ? 512 : 4ull * nprobe;
+        if (want > static_cast<uint64_t>(kIvfUnitsPerQuery)) want = kIvfUnitsPerQuery;
+        uint64_t unit = (total + (want - nprobe) - 1) / (want - nprobe);
         unit = (unit + 63) / 64 * 64;
         if (unit < 256) unit = 256;
         uint32_t u = 0;
@@ -491,9 +496,50 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const CodeT *__restrict__
 // overflows (or whose lists hold fewer than r codes) is redone by the three passes above.
 // Grid (nq, kIvfUnitsPerQuery / 4): the query index varies fastest, so only a few wavefronts of one
 // query run at a time and the candidates waiting in their queues stay few against r.
+//
+// The kernel is bound by the stream of codes from HBM, so a wavefront is built around keeping that
+// stream in flight: the codes stay in registers as loaded (their low bytes are picked out when they
+// are looked up), in two sets of kIvfRawWords words per lane; while one set is processed the loads
+// of the next are under way, the first of them issued together with the load of the unit's tables,
+// and nothing in the kernel waits for another wavefront.
 constexpr uint32_t kIvfSampleStep = 16;
+constexpr int kIvfRawWords = 16;         // registers per lane and set that hold codes in flight
 
-template <int M, typename CodeT>
+// The bytes of code i as stored, in RW words (a narrower code is zero-extended).
+template <int M, typename CodeT, int RW>
+__device__ inline void load_raw_code(const CodeT *__restrict__ codes, uint64_t i, uint32_t (&w)[RW])
+{
+    constexpr int BPC = M * static_cast<int>(sizeof(CodeT));
+    const uint8_t *p = reinterpret_cast<const uint8_t *>(codes) + i * BPC;
+    if constexpr (BPC >= 16) {
+#pragma unroll
+        for (int v = 0; v < BPC / 16; ++v) {
+            const uint4 x = reinterpret_cast<const uint4 *>(p)[v];
+            w[4 * v] = x.x; w[4 * v + 1] = x.y; w[4 * v + 2] = x.z; w[4 * v + 3] = x.w;
+        }
+    } else if constexpr (BPC == 8) {
+        const uint2 x = *reinterpret_cast<const uint2 *>(p);
+        w[0] = x.x; w[1] = x.y;
+    } else if constexpr (BPC == 4) {
+        w[0] = *reinterpret_cast<const uint32_t *>(p);
+    } else if constexpr (BPC == 2) {
+        w[0] = *reinterpret_cast<const uint16_t *>(p);
+    } else {
+        w[0] = *p;
+    }
+}
+
+// Low byte of sub-code j of a code held as loaded (property P1: the derived index is the low 8 bits).
+template <typename CodeT, int RW>
+__device__ inline uint32_t low_byte_of(const uint32_t (&w)[RW], int j)
+{
+    if constexpr (sizeof(CodeT) == 2) return (w[j >> 1] >> (16 * (j & 1))) & 255u;
+    else return (w[j >> 2] >> (8 * (j & 3))) & 255u;
+}
+
+// SAMPLE: the pass that finds the starting bounds -- only every kIvfSampleStep-th unit is read, nothing
+// is appended, and `count` is the per-query histogram of the integer distances ([nq][256]).
+template <int M, typename CodeT, bool SAMPLE>
 __global__ __launch_bounds__(256) void ivf_scan_single_kernel(const CodeT *__restrict__ codes,
                                                              const IvfUnit *__restrict__ units,
                                                              const uint32_t *__restrict__ nunits,
@@ -501,23 +547,60 @@ __global__ __launch_bounds__(256) void ivf_scan_single_kernel(const CodeT *__res
                                                              uint32_t cap, uint32_t upd, uint32_t qflush, int *t_cur,
                                                              uint32_t *count, uint32_t *chist, uint64_t *__restrict__ keys)
 {
+    constexpr int BPC = M * static_cast<int>(sizeof(CodeT));
+    constexpr int RW = BPC >= 4 ? BPC / 4 : 1;                // words per code
+    constexpr int GPB = RW >= kIvfRawWords ? 1 : kIvfRawWords / RW;   // 64-code groups per set
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = blockIdx.x;
     const uint32_t u = blockIdx.y * 4 + wave;
+    if (u >= nunits[q]) return;                              // uniform per wavefront; the kernel has no workgroup barrier
+    if (SAMPLE && u % kIvfSampleStep != 0) return;
     uint8_t *tab = smem + wave * (M * 256);                                           // [M][256]
     uint64_t *wq = reinterpret_cast<uint64_t *>(smem + 4 * M * 256) + wave * 64;      // pending candidates
-    const bool active = u < nunits[q];
-    IvfUnit un{0, 0, 0};
-    if (active) un = units[static_cast<size_t>(q) * kIvfUnitsPerQuery + u];
-    if (active) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(qtab + (static_cast<size_t>(q) * nprobe + un.p) * M * 256);
-        uint4 *dst = reinterpret_cast<uint4 *>(tab);
-        for (int v = lane; v < M * 256 / 16; v += 64) dst[v] = src[v];
+    uint32_t *lhist = reinterpret_cast<uint32_t *>(smem + 4 * M * 256) + wave * 256;  // SAMPLE: this wavefront's histogram
+    if constexpr (SAMPLE) {
+#pragma unroll
+        for (int b = 0; b < 4; ++b) lhist[lane + 64 * b] = 0;
     }
-    __syncthreads();
-    if (!active) return;
+    const IvfUnit un = units[static_cast<size_t>(q) * kIvfUnitsPerQuery + u];
+    if (un.count == 0) return;                               // uniform (the planner makes no empty units)
+
+    auto load_set = [&](uint32_t base0, uint32_t (&w)[GPB][RW]) {
+#pragma unroll
+        for (int g = 0; g < GPB; ++g) {
+            const uint32_t k = base0 + g * 64 + lane;
+            // past the end of the unit the last code is read again (a valid address); it is masked below
+            load_raw_code<M, CodeT, RW>(codes, un.begin + (k < un.count ? k : un.count - 1), w[g]);
+        }
+    };
+    auto load_bound = [&]() {
+        if constexpr (SAMPLE) return 0;
+        const int t = __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return t >= 255 ? 0x7fffffff : t;
+    };
+    // the unit's tables and its first codes travel together
+    constexpr int TV = M * 256 / 16 / 64 > 0 ? M * 256 / 16 / 64 : 1;   // 16-byte words of the tables per lane
+    uint4 tv[TV];
+    {
+        const uint4 *src = reinterpret_cast<const uint4 *>(qtab + (static_cast<size_t>(q) * nprobe + un.p) * M * 256);
+#pragma unroll
+        for (int v = 0; v < TV; ++v)
+            if (lane + 64 * v < M * 256 / 16) tv[v] = src[lane + 64 * v];
+    }
+    uint32_t wa[GPB][RW], wb[GPB][RW];
+    load_set(0, wa);
+    int T = load_bound();
+    {
+        uint4 *dst = reinterpret_cast<uint4 *>(tab);
+#pragma unroll
+        for (int v = 0; v < TV; ++v)
+            if (lane + 64 * v < M * 256 / 16) dst[lane + 64 * v] = tv[v];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 
     const size_t cell = static_cast<size_t>(q) * kFastSlices + u % kFastSlices;
     uint32_t qlen = 0;                                   // wave-uniform
@@ -540,31 +623,21 @@ __global__ __launch_bounds__(256) void ivf_scan_single_kernel(const CodeT *__res
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     };
-
-    for (uint32_t base0 = 0; base0 < un.count; base0 += 64 * kIvfAhead) {
-        int T = __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (T >= 255) T = 0x7fffffff;
-        uint32_t low[kIvfAhead][M];
+    auto process = [&](uint32_t base0, const uint32_t (&w)[GPB][RW], int bound) {
 #pragma unroll
-        for (int g = 0; g < kIvfAhead; ++g) {
-            const uint32_t k = base0 + g * 64 + lane;
-            if (k < un.count) {
-                load_low_bytes<M>(codes, un.begin + k, low[g]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < M; ++j) low[g][j] = 0;
-            }
-        }
-#pragma unroll
-        for (int g = 0; g < kIvfAhead; ++g) {
+        for (int g = 0; g < GPB; ++g) {
             const uint32_t base = base0 + g * 64;
             if (base >= un.count) break;                              // uniform
             const uint32_t k = base + lane;
             uint32_t s = 0;
 #pragma unroll
-            for (int j = 0; j < M; ++j) s += tab[j * 256 + low[g][j]];
+            for (int j = 0; j < M; ++j) s += tab[j * 256 + low_byte_of<CodeT, RW>(w[g], j)];
             const uint32_t qd = min(s, 255u);
-            const bool h = k < un.count && static_cast<int>(qd) <= T;
+            if constexpr (SAMPLE) {
+                if (k < un.count) atomicAdd(&lhist[qd], 1u);
+                continue;
+            }
+            const bool h = k < un.count && static_cast<int>(qd) <= bound;
             const uint64_t mask = __builtin_amdgcn_ballot_w64(h);
             if (!mask) continue;                                      // uniform
             const uint32_t cnt = __popcll(mask);
@@ -577,6 +650,29 @@ __global__ __launch_bounds__(256) void ivf_scan_single_kernel(const CodeT *__res
             qlen = __builtin_amdgcn_readfirstlane(qlen + cnt);
             if (qlen >= qflush) flush();                              // uniform
         }
+    };
+
+    constexpr uint32_t SET = 64 * GPB;
+    for (uint32_t base0 = 0; base0 < un.count; base0 += 2 * SET) {
+        int Tn = T;
+        if (base0 + SET < un.count) { load_set(base0 + SET, wb); Tn = load_bound(); }
+        process(base0, wa, T);
+        if (base0 + SET >= un.count) break;
+        T = Tn;
+        if (base0 + 2 * SET < un.count) { load_set(base0 + 2 * SET, wa); Tn = load_bound(); }
+        process(base0 + SET, wb, T);
+        T = Tn;
+    }
+    if constexpr (SAMPLE) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const uint32_t c = lhist[lane + 64 * b];
+            if (c) atomicAdd(&count[static_cast<size_t>(q) * 256 + lane + 64 * b], c);
+        }
+        return;
     }
     if (qlen) flush();
 }
@@ -720,12 +816,12 @@ static int ivf_scan_m(const CodeT *codes, const int64_t *offsets, const int32_t 
     uint64_t *fkeys = reinterpret_cast<uint64_t *>(base + p.off_fkeys);
     uint64_t *fsort = reinterpret_cast<uint64_t *>(base + p.off_fsort);
     // single pass: bounds from a sample of the units, one pass over all of them, exact selection
-    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist, CodeT>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
-                nunits, qtab, nprobe, r, kIvfSampleStep, nullptr, shist, thr, tie, counter, keys);
-    DCPQ_CHECK_LAUNCH("ivf_scan_kernel<sample>");
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_single_kernel<M, CodeT, true>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
+                lds_tab + 4 * 256 * 4, codes, units, nunits, qtab, nprobe, r, p.cap, p.upd, p.qflush, t_cur, shist, chist, fkeys);
+    DCPQ_CHECK_LAUNCH("ivf_scan_single_kernel<sample>");
     rc = launch_sample_threshold(shist, nq, r, 0, t_cur, st);     // 0: the sample's own r-th smallest
     if (rc) return rc;
-    DCPQ_LAUNCH(kStageIvfScan, st, (ivf_scan_single_kernel<M, CodeT>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
+    DCPQ_LAUNCH(kStageIvfScan, st, (ivf_scan_single_kernel<M, CodeT, false>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
                 lds_tab + 4 * 64 * 8, codes, units, nunits, qtab, nprobe, r, p.cap, p.upd, p.qflush, t_cur, fcount, chist,
                 fkeys);
     DCPQ_CHECK_LAUNCH("ivf_scan_single_kernel");
