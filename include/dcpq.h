@@ -130,6 +130,13 @@ int dcpq_scan_candidates_mode(const uint16_t *codes, uint64_t n_codes, int m, co
                               uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
                               size_t workspace_bytes, int mode, void *stream);
 
+/* The same scan reading the low-byte plane of the codes (dcpq_pack_low_bytes: uint8_t [n_codes][m], the
+ * only bytes pass one consumes, Sec. 3.3 adc_low_bits) instead of the codes: half the bytes per code
+ * and pass.  Same outputs; `mode` as in dcpq_scan_candidates_mode. */
+int dcpq_scan_candidates_packed(const uint8_t *plane, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                                uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
+                                size_t workspace_bytes, int mode, void *stream);
+
 /* The same scan for callers that cannot allocate (code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc) and have no workspace to pass: the scratch memory is an array
  * inside the library, DCPQ_STATIC_SCRATCH_BYTES per GPU, held from the first call on that GPU until

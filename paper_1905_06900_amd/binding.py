@@ -41,6 +41,7 @@ _SIGNATURES = {
     "dcpq_scan_plan": (_i, [_u64, _i, _i, _u32, _i, _vp, _i]),
     "dcpq_search_chunk": (_i, [_i, _i, _i]),
     "dcpq_scan_candidates_mode": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp, _sz, _i, _vp]),
+    "dcpq_scan_candidates_packed": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp, _sz, _i, _vp]),
     "dcpq_static_scratch_bytes": (_sz, []),
     "dcpq_scan_candidates_static": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp]),
     "dcpq_refine_workspace_bytes": (_sz, [_i, _u32]),
@@ -184,6 +185,11 @@ def scan_candidates(codes: torch.Tensor, qtab: torch.Tensor, r: int, workspace: 
     cand_qd = torch.empty((nq, r), dtype=torch.uint8, device=dev)
     if workspace is None:
         workspace = _workspace(scan_workspace_bytes(n, m, nq, r), dev)
+    if codes.dtype == torch.uint8:          # the low-byte plane of the codes
+        _check(lib().dcpq_scan_candidates_packed(_dev(codes, torch.uint8, "plane"), n, m, _dev(qtab, torch.uint8, "qtab"),
+                                                 nq, r, cand_id.data_ptr(), cand_qd.data_ptr(), workspace.data_ptr(),
+                                                 workspace.numel(), mode, _stream()))
+        return cand_id, cand_qd
     if mode == SCAN_AUTO:
         _check(lib().dcpq_scan_candidates(_dev(codes, torch.uint16, "codes"), n, m, _dev(qtab, torch.uint8, "qtab"),
                                           nq, r, cand_id.data_ptr(), cand_qd.data_ptr(), workspace.data_ptr(),

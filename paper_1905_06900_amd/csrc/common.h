@@ -63,6 +63,11 @@ void end(void *token, hipStream_t st);
         ::dcpq::prof::end(tok_, st);                                                           \
     } while (0)
 
+// Raises a kernel's dynamic LDS limit to `bytes` (needed above 64 KiB) once per (device, kernel); when
+// `no_static_lds` is set, also checks that the kernel has no static LDS of its own (kernels that
+// address their dynamic LDS from offset 0 rely on it).  Thread-safe.
+int allow_dynamic_lds(const void *kernel, int bytes, bool no_static_lds = false);
+
 inline bool m_supported(int m) { return m == 1 || m == 2 || m == 4 || m == 8 || m == 16 || m == 32; }
 
 // Sortable 64-bit key: major part in the high word, vector id in the low word.
@@ -82,6 +87,9 @@ int launch_distance_tables(const float *queries, int nq, const float *codebooks,
                            float *tables, int stage, hipStream_t st);
 // mode: DCPQ_SCAN_AUTO or DCPQ_SCAN_THREE_PASS
 int launch_scan(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st);
+// the same reading the low-byte plane of the codes (uint8 [n_codes][m])
+int launch_scan(const uint8_t *plane, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                 uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st);
 int launch_refine(const float *tables, const uint16_t *codes, uint64_t n_codes, int m,
                   const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist,

@@ -34,9 +34,10 @@ enum ScanMode { kHist = 0, kTieCount = 1, kCollect = 2 };
 
 // Queries are addressed by their position p in the active list: query id = qlist ? qlist[p] : p.
 // Workspace arrays (hist, thr, tie, counter, keys) are indexed by p; qtab by the query id.
-template <int M, int QT, int MODE>
+// CodeT: uint16_t (the codes as stored) or uint8_t (their low-byte plane).
+template <int M, int QT, int MODE, typename CodeT>
 __global__ __launch_bounds__(kScanThreads) void scan_kernel(
-    const uint16_t *__restrict__ codes, uint64_t n_codes, uint32_t unit, uint32_t nunits, uint64_t unit_stride,
+    const CodeT *__restrict__ codes, uint64_t n_codes, uint32_t unit, uint32_t nunits, uint64_t unit_stride,
     const uint8_t *__restrict__ qtab, int nq_host, const int *__restrict__ qlist,
     const uint32_t *__restrict__ nq_dev, uint32_t r,
     uint32_t *__restrict__ hist,        // [nq][256]          (kHist: accumulated)
@@ -385,8 +386,8 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode)
     return p;
 }
 
-template <int M, int MODE>
-static void launch_scan_pass(int stage, const uint16_t *codes, uint64_t n_codes, uint32_t unit, uint32_t nunits,
+template <int M, int MODE, typename CodeT>
+static void launch_scan_pass(int stage, const CodeT *codes, uint64_t n_codes, uint32_t unit, uint32_t nunits,
                              uint64_t stride, const uint8_t *qtab, int nq, const int *qlist, const uint32_t *nq_dev,
                              uint32_t r, uint32_t *hist, const uint32_t *thr, uint32_t *tie, uint32_t *counter,
                              uint64_t *keys, bool few_expected, hipStream_t st)
@@ -398,13 +399,13 @@ static void launch_scan_pass(int stage, const uint16_t *codes, uint64_t n_codes,
     const uint64_t most = few_expected ? 4096 : (1u << 20);
     const uint32_t grid = static_cast<uint32_t>(items < most ? (items ? items : 1) : most);
     const size_t lds = static_cast<size_t>(QT) * M * 256 + (MODE == kHist ? QT * 256 * 4 : 0);
-    DCPQ_LAUNCH(stage, st, (scan_kernel<M, QT, MODE>), dim3(grid), dim3(kScanThreads), lds, codes, n_codes, unit,
+    DCPQ_LAUNCH(stage, st, (scan_kernel<M, QT, MODE, CodeT>), dim3(grid), dim3(kScanThreads), lds, codes, n_codes, unit,
                 nunits, stride, qtab, nq, qlist, nq_dev, r, hist, thr, tie, counter, keys);
 }
 
 // The three passes for the queries qlist[0 .. *nq_dev) (or all nq when qlist is null).
-template <int M>
-static int launch_three_pass(const uint16_t *codes, uint64_t n_codes, const uint8_t *qtab, int nq, const int *qlist,
+template <int M, typename CodeT>
+static int launch_three_pass(const CodeT *codes, uint64_t n_codes, const uint8_t *qtab, int nq, const int *qlist,
                              const uint32_t *nq_dev, uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, uint8_t *base,
                              const ScanPlan &p, hipStream_t st)
 {
@@ -441,8 +442,8 @@ static int launch_three_pass(const uint16_t *codes, uint64_t n_codes, const uint
     return DCPQ_OK;
 }
 
-template <int M>
-static int launch_sample_hist_m(const uint16_t *codes, uint64_t n_codes, const uint8_t *qtab, int nq, uint32_t r,
+template <int M, typename CodeT>
+static int launch_sample_hist_m(const CodeT *codes, uint64_t n_codes, const uint8_t *qtab, int nq, uint32_t r,
                                 uint32_t *shist, const ScanPlan &p, hipStream_t st)
 {
     launch_scan_pass<M, kHist>(kStageScanHist, codes, n_codes, p.s_unit, p.s_nunits, p.s_stride, qtab, nq, nullptr,
@@ -451,26 +452,32 @@ static int launch_sample_hist_m(const uint16_t *codes, uint64_t n_codes, const u
     return DCPQ_OK;
 }
 
-int launch_sample_hist(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
+template <typename CodeT>
+int launch_sample_hist(const CodeT *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
                        uint32_t *shist, const ScanPlan &p, hipStream_t st)
 {
     switch (m) {
-        case 4: return launch_sample_hist_m<4>(codes, n_codes, qtab, nq, r, shist, p, st);
-        case 8: return launch_sample_hist_m<8>(codes, n_codes, qtab, nq, r, shist, p, st);
-        case 16: return launch_sample_hist_m<16>(codes, n_codes, qtab, nq, r, shist, p, st);
-        case 32: return launch_sample_hist_m<32>(codes, n_codes, qtab, nq, r, shist, p, st);
+        case 4: return launch_sample_hist_m<4, CodeT>(codes, n_codes, qtab, nq, r, shist, p, st);
+        case 8: return launch_sample_hist_m<8, CodeT>(codes, n_codes, qtab, nq, r, shist, p, st);
+        case 16: return launch_sample_hist_m<16, CodeT>(codes, n_codes, qtab, nq, r, shist, p, st);
+        case 32: return launch_sample_hist_m<32, CodeT>(codes, n_codes, qtab, nq, r, shist, p, st);
         default: return fail(DCPQ_EUNSUPPORTED, "sample histogram: m=%d not supported", m);
     }
 }
 
-template <int M>
-static int launch_scan_m(const uint16_t *codes, uint64_t n_codes, const uint8_t *qtab, int nq, uint32_t r,
+template int launch_sample_hist<uint16_t>(const uint16_t *, uint64_t, int, const uint8_t *, int, uint32_t, uint32_t *,
+                                          const ScanPlan &, hipStream_t);
+template int launch_sample_hist<uint8_t>(const uint8_t *, uint64_t, int, const uint8_t *, int, uint32_t, uint32_t *,
+                                         const ScanPlan &, hipStream_t);
+
+template <int M, typename CodeT>
+static int launch_scan_m(const CodeT *codes, uint64_t n_codes, const uint8_t *qtab, int nq, uint32_t r,
                          uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st)
 {
     const ScanPlan p = plan_scan(n_codes, M, nq, r, mode);
     uint8_t *base = static_cast<uint8_t *>(ws);
     if (!p.fast)
-        return launch_three_pass<M>(codes, n_codes, qtab, nq, nullptr, nullptr, r, cand_id, cand_qd, base, p, st);
+        return launch_three_pass<M, CodeT>(codes, n_codes, qtab, nq, nullptr, nullptr, r, cand_id, cand_qd, base, p, st);
 
     const size_t nwords = p.fzero_bytes / sizeof(uint32_t);
     DCPQ_LAUNCH(kStageMisc, st, zero_words_kernel, dim3((nwords + 255) / 256), dim3(256), 0,
@@ -479,24 +486,37 @@ static int launch_scan_m(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     int rc = launch_scan_fast(codes, n_codes, M, qtab, nq, r, cand_id, cand_qd, base, p, st);
     if (rc) return rc;
     // queries the single pass could not finish (their count is known on the device only)
-    return launch_three_pass<M>(codes, n_codes, qtab, nq, reinterpret_cast<const int *>(base + p.off_qlist),
+    return launch_three_pass<M, CodeT>(codes, n_codes, qtab, nq, reinterpret_cast<const int *>(base + p.off_qlist),
                                 reinterpret_cast<const uint32_t *>(base + p.off_nflag), r, cand_id, cand_qd, base,
                                 p, st);
+}
+
+template <typename CodeT>
+static int launch_scan_any(const CodeT *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
+                           uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st)
+{
+    if (nq == 0) return DCPQ_OK;
+    switch (m) {
+        case 1: return launch_scan_m<1, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        case 2: return launch_scan_m<2, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        case 4: return launch_scan_m<4, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        case 8: return launch_scan_m<8, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        case 16: return launch_scan_m<16, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        case 32: return launch_scan_m<32, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+        default: return fail(DCPQ_EUNSUPPORTED, "m=%d not supported", m);
+    }
 }
 
 int launch_scan(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
                 uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st)
 {
-    if (nq == 0) return DCPQ_OK;
-    switch (m) {
-        case 1: return launch_scan_m<1>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
-        case 2: return launch_scan_m<2>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
-        case 4: return launch_scan_m<4>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
-        case 8: return launch_scan_m<8>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
-        case 16: return launch_scan_m<16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
-        case 32: return launch_scan_m<32>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
-        default: return fail(DCPQ_EUNSUPPORTED, "m=%d not supported", m);
-    }
+    return launch_scan_any(codes, n_codes, m, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
+}
+
+int launch_scan(const uint8_t *plane, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
+                uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st)
+{
+    return launch_scan_any(plane, n_codes, m, qtab, nq, r, cand_id, cand_qd, ws, mode, st);
 }
 
 }  // namespace dcpq
@@ -539,7 +559,8 @@ extern "C" size_t dcpq_scan_workspace_bytes(uint64_t n_codes, int m, int nq, uin
     return most;
 }
 
-static int scan_checked(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
+template <typename CodeT>
+static int scan_checked(const CodeT *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
                         uint32_t *cand_id, uint8_t *cand_qd, void *workspace, size_t workspace_bytes, int mode,
                         void *stream)
 {
@@ -559,7 +580,7 @@ static int scan_checked(const uint16_t *codes, uint64_t n_codes, int m, const ui
     DCPQ_REQUIRE(codes && qtab && cand_id && cand_qd && workspace, "scan_candidates: null pointer");
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "scan_candidates: workspace must be 256-byte aligned");
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(codes) & 15) == 0 && (reinterpret_cast<uintptr_t>(qtab) & 15) == 0,
-                 "scan_candidates: codes and qtab must be 16-byte aligned");
+                 "scan_candidates: codes (or their plane) and qtab must be 16-byte aligned");
     const size_t need = dcpq_scan_workspace_bytes(n_codes, m, nq, r);
     if (workspace_bytes < need)
         return fail(DCPQ_EWORKSPACE, "scan_candidates: workspace %zu < %zu bytes", workspace_bytes, need);
@@ -572,6 +593,13 @@ extern "C" int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int
 {
     return scan_checked(codes, n_codes, m, qtab, nq, r, cand_id, cand_qd, workspace, workspace_bytes,
                         DCPQ_SCAN_AUTO, stream);
+}
+
+extern "C" int dcpq_scan_candidates_packed(const uint8_t *plane, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+                                           uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,
+                                           size_t workspace_bytes, int mode, void *stream)
+{
+    return scan_checked(plane, n_codes, m, qtab, nq, r, cand_id, cand_qd, workspace, workspace_bytes, mode, stream);
 }
 
 extern "C" int dcpq_scan_candidates_mode(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab,

@@ -174,21 +174,26 @@ __global__ __launch_bounds__(256) void sample_threshold_kernel(const uint32_t *_
 }
 
 // Low bytes of the M sub-codes of one code, reordered by residue class: byte (j & 3) * CLS + (j >> 2).
-template <int M>
-__device__ inline void transposed_low_bytes(const uint32_t (&w)[M / 2], uint32_t (&out)[M / 4])
+// w: the code as stored -- uint16 sub-codes (sub-codes 2i and 2i+1 in w[i]; the low byte of j is byte
+// 2 * (j & 1) of w[j / 2]) or, for the low-byte plane, the bytes themselves (byte j & 3 of w[j / 4]).
+template <int M, typename CodeT>
+__device__ inline void transposed_low_bytes(const uint32_t (&w)[M * sizeof(CodeT) / 4], uint32_t (&out)[M / 4])
 {
-    // w[i] holds sub-codes 2i (bits 0..15) and 2i+1 (bits 16..31); low byte of j is byte 2*(j&1) of w[j/2]
+    constexpr bool WIDE = sizeof(CodeT) == 2;
     if constexpr (M == 4) {
-        out[0] = __builtin_amdgcn_perm(w[1], w[0], 0x06040200u);       // j = 0, 1, 2, 3
-    } else if constexpr (M == 8) {
+        out[0] = WIDE ? __builtin_amdgcn_perm(w[WIDE ? 1 : 0], w[0], 0x06040200u) : w[0];      // j = 0, 1, 2, 3
+    } else if constexpr (M == 8 && WIDE) {
         out[0] = __builtin_amdgcn_perm(w[2], w[0], 0x06020400u);       // j = 0, 4, 1, 5
         out[1] = __builtin_amdgcn_perm(w[3], w[1], 0x06020400u);       // j = 2, 6, 3, 7
+    } else if constexpr (M == 8) {
+        out[0] = __builtin_amdgcn_perm(w[1], w[0], 0x05010400u);       // j = 0, 4, 1, 5
+        out[1] = __builtin_amdgcn_perm(w[1], w[0], 0x07030602u);       // j = 2, 6, 3, 7
     } else {
 #pragma unroll
         for (int d = 0; d < M / 4; ++d) out[d] = 0;
 #pragma unroll
         for (int j = 0; j < M; ++j) {
-            const uint32_t b = (w[j >> 1] >> (16 * (j & 1))) & 255u;
+            const uint32_t b = WIDE ? (w[j >> 1] >> (16 * (j & 1))) & 255u : (w[j >> 2] >> (8 * (j & 3))) & 255u;
             const int p = (j & 3) * (M / 4) + (j >> 2);
             out[p >> 2] |= b << (8 * (p & 3));
         }
@@ -213,9 +218,9 @@ __device__ __noinline__ int append_candidate(uint64_t rec, int q0, uint32_t slic
     return (pos + 1) % upd == 0 ? static_cast<int>(q) : -1;
 }
 
-template <int M, int QT, int WAVES>
+template <int M, int QT, int WAVES, typename CodeT>
 __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
-    const uint16_t *__restrict__ codes, uint64_t code_begin, uint64_t code_end, uint32_t codes_per_block,
+    const CodeT *__restrict__ codes, uint64_t code_begin, uint64_t code_end, uint32_t codes_per_block,
     const uint8_t *__restrict__ qsw, int nq, uint32_t r, uint32_t nslices, uint32_t cap, uint32_t upd,
     uint32_t qflush, int *t_cur, uint32_t *count, uint32_t *chist, uint64_t *__restrict__ keys)
 {
@@ -335,26 +340,30 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     // This wavefront's groups are wave, wave + WAVES, ...; they are fetched PF at a time and one batch
     // ahead of their use, so that each wavefront keeps PF kilobytes of the code stream in flight.
     const uint32_t ng_w = ngroups > static_cast<uint32_t>(wave) ? (ngroups - wave + WAVES - 1) / WAVES : 0u;
-    auto load_group = [&](uint32_t g, uint32_t (&dst)[M / 2]) {
+    constexpr int RW = M * static_cast<int>(sizeof(CodeT)) / 4;     // words per code as stored
+    auto load_group = [&](uint32_t g, uint32_t (&dst)[RW]) {
         const uint32_t id = cbeg + g * 64u + lane;
         if (g < ngroups && id < cend) {
-            if constexpr (M % 8 == 0) {
-                const uint4 *p = reinterpret_cast<const uint4 *>(codes + static_cast<uint64_t>(id) * M);
+            const uint8_t *src = reinterpret_cast<const uint8_t *>(codes) + static_cast<uint64_t>(id) * (4 * RW);
+            if constexpr (RW % 4 == 0) {
 #pragma unroll
-                for (int v = 0; v < M / 8; ++v) {
-                    const uint4 x = p[v];
+                for (int v = 0; v < RW / 4; ++v) {
+                    const uint4 x = reinterpret_cast<const uint4 *>(src)[v];
                     dst[4 * v] = x.x; dst[4 * v + 1] = x.y; dst[4 * v + 2] = x.z; dst[4 * v + 3] = x.w;
                 }
-            } else {
-                const uint2 x = *reinterpret_cast<const uint2 *>(codes + static_cast<uint64_t>(id) * M);
+            } else if constexpr (RW == 2) {
+                const uint2 x = *reinterpret_cast<const uint2 *>(src);
                 dst[0] = x.x; dst[1] = x.y;
+            } else {
+                static_assert(RW == 1, "codes of 4, 8 or a multiple of 16 bytes");
+                dst[0] = *reinterpret_cast<const uint32_t *>(src);
             }
         } else {
 #pragma unroll
-            for (int v = 0; v < M / 2; ++v) dst[v] = 0;
+            for (int v = 0; v < RW; ++v) dst[v] = 0;
         }
     };
-    uint32_t wb[PF][M / 2];
+    uint32_t wb[PF][RW];
     auto load_batch = [&](uint32_t g0) {
 #pragma unroll
         for (int pf = 0; pf < PF; ++pf) load_group(g0 + pf * WAVES, wb[pf]);
@@ -400,7 +409,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
 #pragma unroll
             for (int pf = 0; pf < PF; ++pf) {
                 uint32_t tb[M / 4];
-                transposed_low_bytes<M>(wb[pf], tb);
+                transposed_low_bytes<M, CodeT>(wb[pf], tb);
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     uint8_t *d = dst + pf * (64 * M) + k * C::REGION;
@@ -708,8 +717,8 @@ __global__ __launch_bounds__(64) void collect_flags_kernel(const uint32_t *__res
 
 // ---- host side ------------------------------------------------------------------------------
 
-template <int M, int QT, int WAVES>
-static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t *qtab, int nq, uint32_t r,
+template <int M, int QT, int WAVES, typename CodeT>
+static int launch_fast_t(const CodeT *codes, uint64_t n_codes, const uint8_t *qtab, int nq, uint32_t r,
                          uint32_t *cand_id, uint8_t *cand_qd, uint8_t *base, const ScanPlan &p, hipStream_t st)
 {
     using C = FastCfg<M, QT, WAVES>;
@@ -724,17 +733,11 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     int *qlist = reinterpret_cast<int *>(base + p.off_qlist);
     uint32_t *nflag = reinterpret_cast<uint32_t *>(base + p.off_nflag);
 
-    static bool attr_done = false;          // LDS above 64 KiB must be requested once per kernel
-    if (!attr_done) {
-        // the kernel addresses its tables by LDS offset and assumes that they start at offset 0
-        hipFuncAttributes fa;
-        DCPQ_CHECK_HIP(hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(&scan_fast_kernel<M, QT, WAVES>)));
-        if (fa.sharedSizeBytes != 0)
-            return fail(DCPQ_EUNSUPPORTED, "single-pass scan: kernel has %zu bytes of static LDS, expected none",
-                        static_cast<size_t>(fa.sharedSizeBytes));
-        DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&scan_fast_kernel<M, QT, WAVES>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        attr_done = true;
+    // LDS above 64 KiB must be requested; the kernel addresses its tables by LDS offset and assumes that they
+    // start at offset 0
+    {
+        const int arc = allow_dynamic_lds(reinterpret_cast<const void *>(&scan_fast_kernel<M, QT, WAVES, CodeT>), C::LDS_BYTES, true);
+        if (arc) return arc;
     }
 
     // swizzled tables
@@ -747,7 +750,7 @@ static int launch_fast_t(const uint16_t *codes, uint64_t n_codes, const uint8_t 
     rc = launch_sample_threshold(shist, nq, r, n_codes, t_cur, st);
     if (rc) return rc;
     // the scan
-    DCPQ_LAUNCH(kStageScanFast, st, (scan_fast_kernel<M, QT, WAVES>), dim3(p.ntiles, p.fblocks), dim3(WAVES * 64),
+    DCPQ_LAUNCH(kStageScanFast, st, (scan_fast_kernel<M, QT, WAVES, CodeT>), dim3(p.ntiles, p.fblocks), dim3(WAVES * 64),
                 C::LDS_BYTES, codes, static_cast<uint64_t>(0), n_codes, p.codes_per_block, qsw, nq, r, p.slices, p.cap, p.upd,
                 p.qflush, t_cur, fcount, chist, fkeys);
     DCPQ_CHECK_LAUNCH("scan_fast_kernel");
@@ -770,12 +773,9 @@ int launch_fast_select(const uint64_t *keys, const uint32_t *count, const uint32
                        uint32_t nslices, uint32_t cap, uint32_t sortcap, uint64_t *spill, uint32_t *cand_id,
                        uint8_t *cand_qd, uint32_t *flags, hipStream_t st)
 {
-    static bool attr_done = false;          // LDS above 64 KiB must be requested once per kernel
-    if (!attr_done) {
-        DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&fast_select_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize,
-                                           static_cast<int>(kSelectLdsMost)));
-        attr_done = true;
+    {
+        const int arc = allow_dynamic_lds(reinterpret_cast<const void *>(&fast_select_kernel), static_cast<int>(kSelectLdsMost));
+        if (arc) return arc;
     }
     const int use_lds = sortcap <= kSortLdsKeys;
     const int rank_ok = rank_lds_bytes(sortcap) <= kSelectLdsMost;
@@ -801,18 +801,24 @@ size_t fast_table_bytes(int m, int qt)
     }
 }
 
-int launch_scan_fast(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
+template <typename CodeT>
+int launch_scan_fast(const CodeT *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq, uint32_t r,
                      uint32_t *cand_id, uint8_t *cand_qd, uint8_t *base, const ScanPlan &p, hipStream_t st)
 {
     switch (m * 1000 + static_cast<int>(p.fqt)) {
-        case 4064: return launch_fast_t<4, 64, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
-        case 8064: return launch_fast_t<8, 64, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
-        case 8032: return launch_fast_t<8, 32, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
-        case 8016: return launch_fast_t<8, 16, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
-        case 16032: return launch_fast_t<16, 32, 16>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
-        case 32016: return launch_fast_t<32, 16, 8>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 4064: return launch_fast_t<4, 64, 16, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 8064: return launch_fast_t<8, 64, 16, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 8032: return launch_fast_t<8, 32, 16, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 8016: return launch_fast_t<8, 16, 16, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 16032: return launch_fast_t<16, 32, 16, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
+        case 32016: return launch_fast_t<32, 16, 8, CodeT>(codes, n_codes, qtab, nq, r, cand_id, cand_qd, base, p, st);
         default: return fail(DCPQ_EUNSUPPORTED, "single-pass scan: m=%d with tiles of %u queries not supported", m, p.fqt);
     }
 }
+
+template int launch_scan_fast<uint16_t>(const uint16_t *, uint64_t, int, const uint8_t *, int, uint32_t, uint32_t *, uint8_t *,
+                                        uint8_t *, const ScanPlan &, hipStream_t);
+template int launch_scan_fast<uint8_t>(const uint8_t *, uint64_t, int, const uint8_t *, int, uint32_t, uint32_t *, uint8_t *,
+                                       uint8_t *, const ScanPlan &, hipStream_t);
 
 }  // namespace dcpq

@@ -64,9 +64,12 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode = 0);
 
 int fast_query_tile(int m, int nq, int mode);   // 0 when the single-pass path does not exist for this m (and tile)
 size_t fast_table_bytes(int m, int qt);
-int launch_sample_hist(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+// CodeT: uint16_t (the codes as stored) or uint8_t (their low-byte plane); both are instantiated.
+template <typename CodeT>
+int launch_sample_hist(const CodeT *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                        uint32_t r, uint32_t *shist, const ScanPlan &p, hipStream_t st);
-int launch_scan_fast(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
+template <typename CodeT>
+int launch_scan_fast(const CodeT *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                      uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, uint8_t *base, const ScanPlan &p,
                      hipStream_t st);
 

@@ -108,13 +108,16 @@ def scan_vs_oracle(codes_np, qtab_np, r, modes=(binding.SCAN_AUTO, binding.SCAN_
     for q in range(qtab_np.shape[0]):
         qd = oracle.adc_low_bits(codes_np, qtab_np[q])
         want.append(oracle.select(qd, r))
-    for mode in modes:
-        cid, cqd = binding.scan_candidates(codes, qtab, r, mode=mode)
-        torch.cuda.synchronize()
-        cid, cqd = to_np(cid), to_np(cqd)
-        for q, (wid, wqd) in enumerate(want):
-            np.testing.assert_array_equal(cid[q], wid, err_msg="mode %d query %d ids" % (mode, q))
-            np.testing.assert_array_equal(cqd[q], wqd, err_msg="mode %d query %d qd" % (mode, q))
+    # the codes as stored, and their low-byte plane (the only bytes pass one consumes): same candidates
+    plane = binding.pack_low_bytes(codes)
+    for src, what in ((codes, "codes"), (plane, "plane")):
+        for mode in modes:
+            cid, cqd = binding.scan_candidates(src, qtab, r, mode=mode)
+            torch.cuda.synchronize()
+            cid, cqd = to_np(cid), to_np(cqd)
+            for q, (wid, wqd) in enumerate(want):
+                np.testing.assert_array_equal(cid[q], wid, err_msg="%s mode %d query %d ids" % (what, mode, q))
+                np.testing.assert_array_equal(cqd[q], wqd, err_msg="%s mode %d query %d qd" % (what, mode, q))
 
 
 @pytest.mark.parametrize("m", [1, 2, 4, 8, 16, 32])
