@@ -156,6 +156,9 @@ def run_flat(w, args, steps, warmup, with_cpu, headline):
                 "bytes_per_launch": w.N * code_bytes, "traffic": committed_traffic("scan_fast_single_tile", w.name)}
             del ws_v, qtab_v
 
+    if args.compare:
+        out["comparison"] = compare_plain(w, cb, codes, queries, ms_per_step, steps, warmup, binding, torch)
+
     if with_cpu:
         import oracle
         threads = oracle.num_threads()
@@ -182,6 +185,48 @@ def run_flat(w, args, steps, warmup, with_cpu, headline):
     del data, cb, codes, queries, ws
     torch.cuda.empty_cache()
     return out
+
+
+def compare_plain(w, cb, codes, queries, two_pass_ms, steps, warmup, binding, torch):
+    """The conventional single-pass search (Alg. 1) on the same device, as context for the two-pass
+    figure (the shape of Table 1 and of the Sec. 4.3 slow-down ratios): once over the same 16-bit
+    codes with the full tables, once over an 8-bit product quantizer of the same code size (2m
+    sub-quantizers of 256 centroids, random codebook and codes: timing only).  Both comparison
+    kernels are plain and untuned."""
+    dev = queries.device
+    Q, k = w.Q, w.k
+    batch = min(Q, 256)            # the 16-bit tables of a batch: 256 KiB x m per query
+    ws16 = torch.empty(binding.plain_workspace_bytes(w.N, batch, k), dtype=torch.uint8, device=dev)
+
+    def plain16():
+        for q0 in range(0, Q, batch):
+            qs = queries[q0:q0 + batch]
+            binding.plain_search(binding.build_tables(qs, cb), codes, k, ws16)
+    e16, st16 = timed(plain16, steps, warmup, binding, torch)
+
+    m8, dsub8 = 2 * w.m, w.dsub // 2
+    g = torch.Generator(device=dev); g.manual_seed(w.seed + 8)
+    cb8 = 0.3 * torch.randn((m8, 256, dsub8), generator=g, device=dev, dtype=torch.float32)
+    codes8 = torch.empty((w.N, m8), dtype=torch.uint8, device=dev)
+    flat = codes8.view(-1)
+    for s0 in range(0, flat.numel(), 1 << 28):
+        e0 = min(flat.numel(), s0 + (1 << 28))
+        flat[s0:e0] = torch.randint(0, 256, (e0 - s0,), generator=g, device=dev, dtype=torch.uint8)
+    ws8 = torch.empty(binding.plain_workspace_bytes(w.N, Q, k), dtype=torch.uint8, device=dev)
+
+    def plain8():
+        binding.plain_search(binding.build_tables_n(queries, cb8), codes8, k, ws8)
+    e8, st8 = timed(plain8, steps, warmup, binding, torch)
+    ms16, ms8 = e16 / steps * 1e3, e8 / steps * 1e3
+    return {
+        "two_pass_16bit_ms": round(two_pass_ms, 3),
+        "plain_16bit_ms": round(ms16, 3), "plain_16bit_scan_ms": round(st16["plain_scan"][0] / steps, 3),
+        "plain_8bit_ms": round(ms8, 3), "plain_8bit_scan_ms": round(st8["plain_scan"][0] / steps, 3),
+        "plain_8bit_shape": "PQ %dx8, dsub %d" % (m8, dsub8),
+        "two_pass_over_plain_8bit": round(two_pass_ms / ms8, 3),
+        "plain_16bit_over_plain_8bit": round(ms16 / ms8, 3),
+        "plain_16bit_over_two_pass": round(ms16 / two_pass_ms, 3),
+    }
 
 
 def run_ivf(w, args, steps, warmup, with_cpu):
@@ -275,6 +320,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="headline workload only")
     ap.add_argument("--chunk", type=int, default=0, help="queries per chunk of the fused search (0 = default)")
+    ap.add_argument("--compare", action="store_true",
+                    help="also time the conventional single-pass search (plain 16-bit and plain 8-bit PQ, Alg. 1) "
+                         "on the same workload; flat workloads only")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also launch one 1 GiB calibration_copy_kernel (for scaling rocprofv3 --pmc traffic counters)")
     args = ap.parse_args()

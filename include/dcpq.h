@@ -88,6 +88,11 @@ int dcpq_build_small_tables(const float *queries, int nq, const float *derived, 
  * ------------------------------------------------------------------------------------------- */
 int dcpq_build_tables(const float *queries, int nq, const float *codebooks, int m, int dsub,
                       float *tables, void *stream);
+/* The same for codebooks of any size (n_entries centroids per sub-quantizer, e.g. the 256 of an 8-bit
+ * product quantizer):  codebooks : const float [m][n_entries][dsub]   tables : float [nq][m][n_entries] */
+int dcpq_build_tables_n(const float *queries, int nq, const float *codebooks, int m, int dsub, int n_entries,
+                        float *tables, void *stream);
+
 
 /* ---------------------------------------------------------------------------------------------
  * scan_candidates -- Sec. 3.3 "Scan step" (Alg. 3 scan / adc_low_bits, capped buckets).
@@ -180,6 +185,23 @@ int dcpq_search(const float *queries, int nq, const float *codebooks, const floa
                 int dsub, const uint16_t *codes, uint64_t n_codes, uint32_t r, uint32_t k,
                 uint32_t *ids, float *dist, int chunk_queries, void *workspace,
                 size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * plain_search -- Alg. 1 (Sec. 2.3): the conventional single-pass search the paper compares with:
+ * asymmetric distance of EVERY code from the full floating-point tables (Eq. 2), no derived
+ * codebooks, no candidate set:
+ *   d(q, i) = sum over j increasing of tables[q][j][codes[i][j]] (fp32 adds)
+ *   ids[q][:], dist[q][:] = the k smallest by (d, i), ascending.
+ * With n_entries = 65536 and 2-byte sub-codes this is "plain 16-bit" PQ (tables from
+ * dcpq_build_tables), with n_entries = 256 and 1-byte sub-codes "plain 8-bit" PQ (tables from
+ * dcpq_build_tables_n on an 8-bit codebook).  A comparison system: exact, not tuned.
+ *   tables : const float [nq][m][n_entries]   codes : [n_codes][m] sub-codes of code_bytes (1 or 2) each
+ *   workspace : dcpq_plain_workspace_bytes(n_codes, nq, k), 256-byte aligned.  1 <= k <= 768.
+ * ------------------------------------------------------------------------------------------- */
+size_t dcpq_plain_workspace_bytes(uint64_t n_codes, int nq, uint32_t k);
+int dcpq_plain_search(const float *tables, uint32_t n_entries, const void *codes, int code_bytes,
+                      uint64_t n_codes, int m, int nq, uint32_t k, uint32_t *ids, float *dist,
+                      void *workspace, size_t workspace_bytes, void *stream);
 
 /* =============================================================================================
  * Inverted-index variant (Sec. 2.2: inverted lists with residual encoding; Sec. 2.3: the Index step,

@@ -35,6 +35,9 @@ _SIGNATURES = {
     "dcpq_derive_codebooks": (_i, [_vp, _i, _i, _vp, _vp]),
     "dcpq_build_small_tables": (_i, [_vp, _i, _vp, _i, _i, _vp, _u64, _u32, _vp, _vp, _vp, _vp]),
     "dcpq_build_tables": (_i, [_vp, _i, _vp, _i, _i, _vp, _vp]),
+    "dcpq_build_tables_n": (_i, [_vp, _i, _vp, _i, _i, _i, _vp, _vp]),
+    "dcpq_plain_workspace_bytes": (_sz, [_u64, _i, _u32]),
+    "dcpq_plain_search": (_i, [_vp, _u32, _vp, _i, _u64, _i, _i, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_scan_workspace_bytes": (_sz, [_u64, _i, _i, _u32]),
     "dcpq_scan_candidates": (_i, [_vp, _u64, _i, _vp, _i, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_scan_query_tile": (_i, [_i]),
@@ -149,6 +152,37 @@ def build_tables(queries: torch.Tensor, codebooks: torch.Tensor, out: torch.Tens
                                    _dev(codebooks, torch.float32, "codebooks"), m, dsub,
                                    _dev(out, torch.float32, "tables"), _stream()))
     return out
+
+
+def build_tables_n(queries: torch.Tensor, codebooks: torch.Tensor) -> torch.Tensor:
+    """Eq. 1 for codebooks of any size: [nq][D] x [m][n_entries][dsub] -> [nq][m][n_entries] fp32"""
+    m, n_entries, dsub = codebooks.shape
+    nq = queries.shape[0]
+    assert queries.shape[1] == m * dsub
+    tables = torch.empty((nq, m, n_entries), dtype=torch.float32, device=queries.device)
+    _check(lib().dcpq_build_tables_n(_dev(queries, torch.float32, "queries"), nq, _dev(codebooks, torch.float32, "codebooks"),
+                                     m, dsub, n_entries, tables.data_ptr(), _stream()))
+    return tables
+
+
+def plain_workspace_bytes(n: int, nq: int, k: int) -> int:
+    return lib().dcpq_plain_workspace_bytes(n, nq, k)
+
+
+def plain_search(tables: torch.Tensor, codes: torch.Tensor, k: int, workspace: torch.Tensor | None = None):
+    """Alg. 1 with full floating-point tables over every code -> (ids u32 [nq][k], dist f32 [nq][k])"""
+    nq, m, n_entries = tables.shape
+    n = codes.shape[0]
+    assert codes.shape[1] == m and codes.dtype in (torch.uint8, torch.uint16)
+    dev = tables.device
+    ids = torch.empty((nq, k), dtype=torch.uint32, device=dev)
+    dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = _workspace(lib().dcpq_plain_workspace_bytes(n, nq, k), dev)
+    _check(lib().dcpq_plain_search(_dev(tables, torch.float32, "tables"), n_entries, _dev(codes, codes.dtype, "codes"),
+                                   codes.element_size(), n, m, nq, k, ids.data_ptr(), dist.data_ptr(),
+                                   workspace.data_ptr(), workspace.numel(), _stream()))
+    return ids, dist
 
 
 def scan_workspace_bytes(n_codes: int, m: int, nq: int, r: int) -> int:

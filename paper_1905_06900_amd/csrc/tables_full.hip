@@ -269,3 +269,16 @@ extern "C" int dcpq_build_tables(const float *queries, int nq, const float *code
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(tables) & 15) == 0, "build_tables: tables must be 16-byte aligned");
     return launch_full_tables(queries, nq, codebooks, m, dsub, tables, as_stream(stream));
 }
+
+extern "C" int dcpq_build_tables_n(const float *queries, int nq, const float *codebooks, int m, int dsub, int n_entries,
+                                   float *tables, void *stream)
+{
+    clear_error();
+    DCPQ_REQUIRE(nq >= 0, "build_tables_n: nq=%d", nq);
+    if (!dcpq_shape_supported(m, dsub)) return fail(DCPQ_EUNSUPPORTED, "build_tables_n: m=%d dsub=%d not supported", m, dsub);
+    DCPQ_REQUIRE(n_entries >= 1 && n_entries <= kFullSize, "build_tables_n: n_entries=%d", n_entries);
+    if (nq == 0) return DCPQ_OK;
+    DCPQ_REQUIRE(queries && codebooks && tables, "build_tables_n: null pointer");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(tables) & 15) == 0, "build_tables_n: tables must be 16-byte aligned");
+    return launch_distance_tables(queries, nq, codebooks, m, dsub, n_entries, tables, kStageFullTables, as_stream(stream));
+}

@@ -259,6 +259,18 @@ def test_exhaustive_search_matches_numpy_bruteforce():
     assert (np.diff(dist, axis=1) >= 0).all()
 
 
+def test_exhaustive_search_of_an_8_bit_quantizer_matches_numpy_bruteforce():
+    # the "plain 8-bit" comparison system: PQ 8x8, every sub-code below 256
+    C, codes, queries = tiny(19, m=8, dsub=2, b=8, N=700, nq=4)
+    assert codes.max() < 256 and C.shape == (8, 256, 2)
+    ids, dist = oracle.search_exhaustive(C, codes, queries, 25, b=8)
+    np.testing.assert_array_equal(ids, exhaustive_np(C, codes, queries, 25))
+    X = decode_np(C, codes)
+    for q in range(4):
+        want = ((X[ids[q]] - queries[q].astype(np.float64)[None, :]) ** 2).sum(1)
+        np.testing.assert_allclose(dist[q], want, rtol=1e-12)
+
+
 def test_two_pass_with_r_equal_N_is_exhaustive_adc():
     C, codes, queries = tiny(10, m=3, dsub=4, b=6, bbar=3, N=300, nq=6)
     Cbar = oracle.derive_codebooks(C, b=6, bbar=3)
