@@ -187,6 +187,38 @@ int dcpq_search(const float *queries, int nq, const float *codebooks, const floa
                 size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * The PQ m x bbar,b family (Sec. 3.1 notation; Sec. 6 names 4-, 5- and 6-bit derived codebooks for an
+ * 8-bit quantizer as the next step): the same stages with the two bit widths as arguments.
+ *   b    : bits of a sub-code, 16 (sub-codes stored as uint16) or 8 (stored as uint8); 2^b centroids
+ *   bbar : bits of a derived-codebook index, 1 <= bbar <= 8, bbar <= b; derived centroid l is the
+ *          mean of the 2^(b-bbar) centroids whose index has low bits l (sum in increasing index
+ *          order, one division), and a sub-code's derived code is its low bbar bits (P1).
+ * The calls above are these with b = 16, bbar = 8.  Layouts as above with 65536 -> 2^b and, for
+ * `derived` and `small`, 256 -> 2^bbar.  The QUANTIZED tables keep 256 entries per sub-quantizer
+ * for every bbar:  qtab[q][j][e] = quantized distance to derived centroid (e mod 2^bbar),  so the
+ * scan calls (which look up by the low byte of a sub-code) serve every bbar unchanged:
+ *   b = 16: dcpq_scan_candidates(codes, ...);   b = 8: dcpq_scan_candidates_packed(codes, ...)
+ *   (1-byte sub-codes are their own low-byte plane).  Full tables: dcpq_build_tables_n with
+ *   n_entries = 2^b.  dcpq_refine_topk_bits needs n_entries = 2^(8 code_bytes).
+ * Unsupported widths -> DCPQ_EUNSUPPORTED.
+ * ------------------------------------------------------------------------------------------- */
+int dcpq_bits_supported(int b, int bbar);
+int dcpq_derive_codebooks_bits(const float *codebooks, int m, int dsub, int b, int bbar, float *derived,
+                               void *stream);
+int dcpq_build_small_tables_bits(const float *queries, int nq, const float *derived, int m, int dsub,
+                                 int bbar, const void *codes, int code_bytes, uint64_t n_codes, uint32_t r,
+                                 uint8_t *qtab, float *bounds, float *small, void *stream);
+int dcpq_refine_topk_bits(const float *tables, uint32_t n_entries, const void *codes, int code_bytes,
+                          uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k,
+                          uint32_t *ids, float *dist, void *workspace, size_t workspace_bytes, void *stream);
+size_t dcpq_search_bits_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r, int b, int chunk_queries);
+int dcpq_search_bits_chunk(int m, int nq, int b, int chunk_queries);
+int dcpq_search_bits(const float *queries, int nq, const float *codebooks, const float *derived, int m,
+                     int dsub, int b, int bbar, const void *codes, uint64_t n_codes, uint32_t r, uint32_t k,
+                     uint32_t *ids, float *dist, int chunk_queries, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------------------------
  * plain_search -- Alg. 1 (Sec. 2.3): the conventional single-pass search the paper compares with:
  * asymmetric distance of EVERY code from the full floating-point tables (Eq. 2), no derived
  * codebooks, no candidate set:

@@ -34,6 +34,13 @@ _SIGNATURES = {
     "dcpq_shape_supported": (_i, [_i, _i]),
     "dcpq_derive_codebooks": (_i, [_vp, _i, _i, _vp, _vp]),
     "dcpq_build_small_tables": (_i, [_vp, _i, _vp, _i, _i, _vp, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "dcpq_bits_supported": (_i, [_i, _i]),
+    "dcpq_derive_codebooks_bits": (_i, [_vp, _i, _i, _i, _i, _vp, _vp]),
+    "dcpq_build_small_tables_bits": (_i, [_vp, _i, _vp, _i, _i, _i, _vp, _i, _u64, _u32, _vp, _vp, _vp, _vp]),
+    "dcpq_refine_topk_bits": (_i, [_vp, _u32, _vp, _i, _u64, _i, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_search_bits_chunk": (_i, [_i, _i, _i, _i]),
+    "dcpq_search_bits_workspace_bytes": (_sz, [_u64, _i, _i, _u32, _i, _i]),
+    "dcpq_search_bits": (_i, [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp, _u64, _u32, _u32, _vp, _vp, _i, _vp, _sz, _vp]),
     "dcpq_build_tables": (_i, [_vp, _i, _vp, _i, _i, _vp, _vp]),
     "dcpq_build_tables_n": (_i, [_vp, _i, _vp, _i, _i, _i, _vp, _vp]),
     "dcpq_plain_workspace_bytes": (_sz, [_u64, _i, _u32]),
@@ -116,29 +123,49 @@ def version() -> int:
     return int(lib().dcpq_version())
 
 
-def derive_codebooks(codebooks: torch.Tensor) -> torch.Tensor:
+def _bits_of(n_entries: int) -> int:
+    b = n_entries.bit_length() - 1
+    assert 1 << b == n_entries, "table / codebook sizes are powers of two"
+    return b
+
+
+def derive_codebooks(codebooks: torch.Tensor, bbar: int = 8) -> torch.Tensor:
+    """Sec. 3.2: [m][2^b][dsub] -> [m][2^bbar][dsub], the means of the centroids sharing their low bbar bits"""
     m, k, dsub = codebooks.shape
-    assert k == 65536
-    out = torch.empty((m, 256, dsub), dtype=torch.float32, device=codebooks.device)
-    _check(lib().dcpq_derive_codebooks(_dev(codebooks, torch.float32, "codebooks"), m, dsub,
-                                       out.data_ptr(), _stream()))
+    b = _bits_of(k)
+    out = torch.empty((m, 1 << bbar, dsub), dtype=torch.float32, device=codebooks.device)
+    if (b, bbar) == (16, 8):
+        _check(lib().dcpq_derive_codebooks(_dev(codebooks, torch.float32, "codebooks"), m, dsub,
+                                           out.data_ptr(), _stream()))
+    else:
+        _check(lib().dcpq_derive_codebooks_bits(_dev(codebooks, torch.float32, "codebooks"), m, dsub, b, bbar,
+                                                out.data_ptr(), _stream()))
     return out
 
 
 def build_small_tables(queries: torch.Tensor, derived: torch.Tensor, codes: torch.Tensor, r: int,
                        want_small: bool = False):
-    """-> (qtab u8 [nq][m][256], bounds f32 [nq][2], small f32 [nq][m][256] or None)"""
-    m, _, dsub = derived.shape
+    """-> (qtab u8 [nq][m][256], bounds f32 [nq][2], small f32 [nq][m][2^bbar] or None); bbar from `derived`,
+    the sub-code width from the dtype of `codes` (uint16 or uint8)"""
+    m, ks, dsub = derived.shape
+    bbar = _bits_of(ks)
     nq = queries.shape[0]
     assert queries.shape[1] == m * dsub and codes.shape[1] == m
     dev = queries.device
     qtab = torch.empty((nq, m, 256), dtype=torch.uint8, device=dev)
     bounds = torch.empty((nq, 2), dtype=torch.float32, device=dev)
-    small = torch.empty((nq, m, 256), dtype=torch.float32, device=dev) if want_small else None
-    _check(lib().dcpq_build_small_tables(
-        _dev(queries, torch.float32, "queries"), nq, _dev(derived, torch.float32, "derived"), m, dsub,
-        _dev(codes, torch.uint16, "codes"), codes.shape[0], r, qtab.data_ptr(), bounds.data_ptr(),
-        small.data_ptr() if small is not None else None, _stream()))
+    small = torch.empty((nq, m, ks), dtype=torch.float32, device=dev) if want_small else None
+    if bbar == 8 and codes.dtype == torch.uint16:
+        _check(lib().dcpq_build_small_tables(
+            _dev(queries, torch.float32, "queries"), nq, _dev(derived, torch.float32, "derived"), m, dsub,
+            _dev(codes, torch.uint16, "codes"), codes.shape[0], r, qtab.data_ptr(), bounds.data_ptr(),
+            small.data_ptr() if small is not None else None, _stream()))
+    else:
+        assert codes.dtype in (torch.uint8, torch.uint16)
+        _check(lib().dcpq_build_small_tables_bits(
+            _dev(queries, torch.float32, "queries"), nq, _dev(derived, torch.float32, "derived"), m, dsub, bbar,
+            _dev(codes, codes.dtype, "codes"), codes.element_size(), codes.shape[0], r, qtab.data_ptr(),
+            bounds.data_ptr(), small.data_ptr() if small is not None else None, _stream()))
     return qtab, bounds, small
 
 
@@ -251,44 +278,64 @@ def scan_candidates_static(codes: torch.Tensor, qtab: torch.Tensor, r: int, cand
 
 def refine_topk(tables: torch.Tensor, codes: torch.Tensor, cand_id: torch.Tensor, k: int,
                 workspace: torch.Tensor | None = None):
-    """-> (ids u32 [nq][k], dist f32 [nq][k]) ascending by (dist, id)"""
+    """-> (ids u32 [nq][k], dist f32 [nq][k]) ascending by (dist, id); tables [nq][m][2^b], codes uint16 (b = 16)
+    or uint8 (b = 8)"""
     n, m = codes.shape
     nq, r = cand_id.shape
-    assert tables.shape == (nq, m, 65536)
+    n_entries = tables.shape[2]
+    assert tables.shape == (nq, m, n_entries)
     dev = codes.device
     ids = torch.empty((nq, k), dtype=torch.uint32, device=dev)
     dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
     if workspace is None:
         workspace = _workspace(lib().dcpq_refine_workspace_bytes(nq, r), dev)
-    _check(lib().dcpq_refine_topk(_dev(tables, torch.float32, "tables"), _dev(codes, torch.uint16, "codes"), n, m,
-                                  _dev(cand_id, torch.uint32, "cand_id"), nq, r, k, ids.data_ptr(),
-                                  dist.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    if n_entries == 65536 and codes.dtype == torch.uint16:
+        _check(lib().dcpq_refine_topk(_dev(tables, torch.float32, "tables"), _dev(codes, torch.uint16, "codes"), n, m,
+                                      _dev(cand_id, torch.uint32, "cand_id"), nq, r, k, ids.data_ptr(),
+                                      dist.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream()))
+    else:
+        assert codes.dtype in (torch.uint8, torch.uint16)
+        _check(lib().dcpq_refine_topk_bits(_dev(tables, torch.float32, "tables"), n_entries, _dev(codes, codes.dtype, "codes"),
+                                           codes.element_size(), n, m, _dev(cand_id, torch.uint32, "cand_id"), nq, r, k,
+                                           ids.data_ptr(), dist.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                           _stream()))
     return ids, dist
 
 
-def search_workspace_bytes(n_codes: int, m: int, nq: int, r: int, chunk_queries: int = 0) -> int:
-    return int(lib().dcpq_search_workspace_bytes(n_codes, m, nq, r, chunk_queries))
+def search_workspace_bytes(n_codes: int, m: int, nq: int, r: int, chunk_queries: int = 0, b: int = 16) -> int:
+    if b == 16:
+        return int(lib().dcpq_search_workspace_bytes(n_codes, m, nq, r, chunk_queries))
+    return int(lib().dcpq_search_bits_workspace_bytes(n_codes, m, nq, r, b, chunk_queries))
 
 
 def search(queries: torch.Tensor, codebooks: torch.Tensor, derived: torch.Tensor, codes: torch.Tensor,
            r: int, k: int, chunk_queries: int = 0, workspace: torch.Tensor | None = None,
            ids: torch.Tensor | None = None, dist: torch.Tensor | None = None):
-    """Alg. 3 end to end without an index -> (ids u32 [nq][k], dist f32 [nq][k])"""
-    m, _, dsub = codebooks.shape
+    """Alg. 3 end to end without an index -> (ids u32 [nq][k], dist f32 [nq][k]); b from `codebooks`
+    ([m][2^b][dsub]), bbar from `derived` ([m][2^bbar][dsub])"""
+    m, kf, dsub = codebooks.shape
+    b, bbar = _bits_of(kf), _bits_of(derived.shape[1])
     n = codes.shape[0]
     nq = queries.shape[0]
-    assert queries.shape[1] == m * dsub and codes.shape[1] == m and derived.shape == (m, 256, dsub)
+    assert queries.shape[1] == m * dsub and codes.shape[1] == m and derived.shape == (m, 1 << bbar, dsub)
+    assert codes.element_size() * 8 == b, "sub-codes of b bits are stored in b / 8 bytes"
     dev = queries.device
     if ids is None:
         ids = torch.empty((nq, k), dtype=torch.uint32, device=dev)
     if dist is None:
         dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
     if workspace is None:
-        workspace = _workspace(search_workspace_bytes(n, m, nq, r, chunk_queries), dev)
-    _check(lib().dcpq_search(_dev(queries, torch.float32, "queries"), nq,
-                             _dev(codebooks, torch.float32, "codebooks"), _dev(derived, torch.float32, "derived"),
-                             m, dsub, _dev(codes, torch.uint16, "codes"), n, r, k, ids.data_ptr(), dist.data_ptr(),
-                             chunk_queries, workspace.data_ptr(), workspace.numel(), _stream()))
+        workspace = _workspace(search_workspace_bytes(n, m, nq, r, chunk_queries, b), dev)
+    if (b, bbar) == (16, 8):
+        _check(lib().dcpq_search(_dev(queries, torch.float32, "queries"), nq,
+                                 _dev(codebooks, torch.float32, "codebooks"), _dev(derived, torch.float32, "derived"),
+                                 m, dsub, _dev(codes, torch.uint16, "codes"), n, r, k, ids.data_ptr(), dist.data_ptr(),
+                                 chunk_queries, workspace.data_ptr(), workspace.numel(), _stream()))
+    else:
+        _check(lib().dcpq_search_bits(_dev(queries, torch.float32, "queries"), nq,
+                                      _dev(codebooks, torch.float32, "codebooks"), _dev(derived, torch.float32, "derived"),
+                                      m, dsub, b, bbar, _dev(codes, codes.dtype, "codes"), n, r, k, ids.data_ptr(),
+                                      dist.data_ptr(), chunk_queries, workspace.data_ptr(), workspace.numel(), _stream()))
     return ids, dist
 
 

@@ -77,9 +77,11 @@ __host__ __device__ inline uint64_t make_key(uint32_t major, uint32_t id)
 }
 
 // Internal launchers used by dcpq_search (same contracts as the public calls, no validation).
-int launch_small_tables(const float *queries, int nq, const float *derived, int m, int dsub,
-                        const uint16_t *codes, uint64_t n_codes, uint32_t r, uint8_t *qtab,
+// small_bits = bbar; codes: uint8 (code_bytes 1) or uint16 (2) sub-codes
+int launch_small_tables(const float *queries, int nq, const float *derived, int m, int dsub, int small_bits,
+                        const void *codes, int code_bytes, uint64_t n_codes, uint32_t r, uint8_t *qtab,
                         float *bounds, float *small, hipStream_t st);
+int launch_derive(const float *codebooks, int m, int dsub, int full_bits, int small_bits, float *derived, hipStream_t st);
 int launch_full_tables(const float *queries, int nq, const float *codebooks, int m, int dsub,
                        float *tables, hipStream_t st);
 // Same kernel for any number of centroids (the coarse quantizer: m = 1, dsub = D, ncent = nlist).
@@ -91,8 +93,8 @@ int launch_scan(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *q
 // the same reading the low-byte plane of the codes (uint8 [n_codes][m])
 int launch_scan(const uint8_t *plane, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                 uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *ws, int mode, hipStream_t st);
-int launch_refine(const float *tables, const uint16_t *codes, uint64_t n_codes, int m,
-                  const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist,
-                  void *ws, hipStream_t st);
+int launch_refine(const float *tables, uint32_t table_size, const void *codes, int code_bytes, uint64_t n_codes, int m,
+                  const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws,
+                  hipStream_t st);
 
 }  // namespace dcpq

@@ -184,20 +184,6 @@ __global__ __launch_bounds__(1024) void ivf_select_probe_kernel(const float *__r
 // ------------------------------------------------------------------------------------------------
 // Tables step.  All arithmetic fp32, one rounding per operation, fixed order (feeds integers).
 // ------------------------------------------------------------------------------------------------
-__device__ inline float ivf_block_reduce(float v, bool want_max, float *red)
-{
-    for (int off = 32; off > 0; off >>= 1) {
-        const float o = __shfl_xor(v, off, kWave);
-        v = want_max ? fmaxf(v, o) : fminf(v, o);
-    }
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    __syncthreads();
-    if (lane == 0) red[wave] = v;
-    __syncthreads();
-    float out = red[0];
-    for (int w = 1; w < 4; ++w) out = want_max ? fmaxf(out, red[w]) : fminf(out, red[w]);
-    return out;
-}
 
 // MODE 0: smallest entry of the (query, list) tables -> atomic min into qmin_bits[q].
 // MODE 1: quantize with the query's bounds -> qtab[q][p][m][256].
@@ -225,10 +211,10 @@ __global__ __launch_bounds__(256) void ivf_tables_kernel(const float *__restrict
             lds[pp * D + t] = __fsub_rn(queries[static_cast<size_t>(q) * D + t], coarse[static_cast<size_t>(l) * D + t]);
     }
     __syncthreads();
-    float qmin = 0.0f, den = 0.0f;
+    float qmin = 0.0f, qmax = 0.0f;
     if (MODE == 1) {
         qmin = bounds[2 * q];
-        den = __fsub_rn(bounds[2 * q + 1], qmin);
+        qmax = bounds[2 * q + 1];
     }
     float lo = INFINITY;
     for (int j = 0; j < m; ++j) {
@@ -252,17 +238,13 @@ __global__ __launch_bounds__(256) void ivf_tables_kernel(const float *__restrict
             if (MODE == 0) {
                 lo = fminf(lo, acc[pp]);
             } else {
-                uint8_t code = 0;
-                if (den > 0.0f) {
-                    const float u = __fmul_rn(__fdiv_rn(__fsub_rn(acc[pp], qmin), den), 255.0f);
-                    code = (u >= 255.0f) ? static_cast<uint8_t>(255) : static_cast<uint8_t>(floorf(u));
-                }
-                qtab[((static_cast<size_t>(q) * nprobe + p0 + pp) * m + j) * kSmallSize + tid] = code;
+                qtab[((static_cast<size_t>(q) * nprobe + p0 + pp) * m + j) * kSmallSize + tid] =
+                    quantize_entry(acc[pp], qmin, qmax);
             }
         }
     }
     if (MODE == 0) {
-        lo = ivf_block_reduce(lo, false, red);
+        lo = block_reduce(lo, false, red);
         if (tid == 0) atomicMin(&qmin_bits[q], __float_as_uint(lo));    // entries are >= +0
     }
 }
@@ -317,7 +299,7 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(const float *__restrict__
         }
         hi = fmaxf(hi, d);
     }
-    hi = ivf_block_reduce(hi, true, red);
+    hi = block_reduce(hi, true, red);
     if (tid == 0) {
         if (total == 0) { bounds[2 * q] = 0.0f; bounds[2 * q + 1] = 0.0f; }
         else { bounds[2 * q] = __uint_as_float(qmin_bits[q]); bounds[2 * q + 1] = hi; }

@@ -8,6 +8,7 @@
 // key.  When that superset is large (many equal distances) all r keys are sorted instead.
 // Squared distances are non-negative, so their fp32 bit patterns order like the values.
 #include "common.h"
+#include "device_util.h"
 
 namespace dcpq {
 
@@ -22,26 +23,10 @@ static uint32_t next_pow2_r(uint32_t x)
     return p;
 }
 
-__device__ inline void bitonic_sort_keys(uint64_t *a, uint32_t n_pow2)
-{
-    for (uint32_t size = 2; size <= n_pow2; size <<= 1) {
-        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (uint32_t t = threadIdx.x; t < (n_pow2 >> 1); t += blockDim.x) {
-                const uint32_t lo = 2 * t - (t & (stride - 1));
-                const uint32_t hi = lo + stride;
-                const bool up = (lo & size) == 0;
-                const uint64_t x = a[lo], y = a[hi];
-                if ((x > y) == up) { a[lo] = y; a[hi] = x; }
-            }
-        }
-    }
-    __syncthreads();
-}
-
-template <int M>
-__global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restrict__ tables,
-                                                          const uint16_t *__restrict__ codes, uint32_t n_codes,
+// CodeT: uint16_t or uint8_t sub-codes; table_size = 2^b entries per sub-quantizer.
+template <int M, typename CodeT>
+__global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restrict__ tables, uint32_t table_size,
+                                                          const CodeT *__restrict__ codes, uint32_t n_codes,
                                                           const uint32_t *__restrict__ cand_id, uint32_t r,
                                                           uint32_t k, uint32_t n_pow2, int use_lds,
                                                           uint64_t *__restrict__ spill,
@@ -50,16 +35,16 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
     extern __shared__ __align__(16) uint8_t smem[];
     const int q = blockIdx.x;
     uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(q) * n_pow2;
-    const float *tq = tables + static_cast<size_t>(q) * M * kFullSize;
+    const float *tq = tables + static_cast<size_t>(q) * M * table_size;
     for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x) {
         uint64_t key = ~0ull;
         if (t < r) {
             const uint32_t id = cand_id[static_cast<size_t>(q) * r + t];
             if (id < n_codes) {                 // pad slots (and anything out of range) sort last
-                const uint16_t *c = codes + static_cast<size_t>(id) * M;
+                const CodeT *c = codes + static_cast<size_t>(id) * M;
                 float d = tq[c[0]];
 #pragma unroll
-                for (int j = 1; j < M; ++j) d = __fadd_rn(d, tq[static_cast<size_t>(j) * kFullSize + c[j]]);
+                for (int j = 1; j < M; ++j) d = __fadd_rn(d, tq[static_cast<size_t>(j) * table_size + c[j]]);
                 key = make_key(__float_as_uint(d), id);
             }
         }
@@ -138,10 +123,10 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
                 if (pos < nf) few[pos] = key;
             }
         }
-        bitonic_sort_keys(few, nf);
+        bitonic_sort(few, nf);
         a = few;
     } else {
-        bitonic_sort_keys(a, n_pow2);
+        bitonic_sort(a, n_pow2);
     }
     for (uint32_t t = threadIdx.x; t < k; t += blockDim.x) {
         const uint64_t key = a[t];
@@ -150,18 +135,20 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
     }
 }
 
-int launch_refine(const float *tables, const uint16_t *codes, uint64_t n_codes, int m, const uint32_t *cand_id,
-                  int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws, hipStream_t st)
+template <typename CodeT>
+static int launch_refine_t(const float *tables, uint32_t table_size, const CodeT *codes, uint64_t n_codes, int m,
+                           const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws,
+                           hipStream_t st)
 {
     if (nq == 0) return DCPQ_OK;
     const uint32_t np2 = next_pow2_r(r);
     const int use_lds = np2 <= kRefineLdsKeys;
     const size_t lds = use_lds ? sizeof(uint64_t) * np2 : 0;
     uint64_t *spill = static_cast<uint64_t *>(ws);
-#define DCPQ_LAUNCH_REFINE(MV)                                                                            \
-    case MV:                                                                                              \
-        DCPQ_LAUNCH(kStageRefine, st, refine_topk_kernel<MV>, dim3(nq), dim3(1024), lds, tables, codes,   \
-                    static_cast<uint32_t>(n_codes), cand_id, r, k, np2, use_lds, spill, ids, dist);       \
+#define DCPQ_LAUNCH_REFINE(MV)                                                                                     \
+    case MV:                                                                                                       \
+        DCPQ_LAUNCH(kStageRefine, st, (refine_topk_kernel<MV, CodeT>), dim3(nq), dim3(1024), lds, tables, table_size, \
+                    codes, static_cast<uint32_t>(n_codes), cand_id, r, k, np2, use_lds, spill, ids, dist);         \
         break;
     switch (m) {
         DCPQ_LAUNCH_REFINE(1) DCPQ_LAUNCH_REFINE(2) DCPQ_LAUNCH_REFINE(4) DCPQ_LAUNCH_REFINE(8)
@@ -171,6 +158,17 @@ int launch_refine(const float *tables, const uint16_t *codes, uint64_t n_codes, 
 #undef DCPQ_LAUNCH_REFINE
     DCPQ_CHECK_LAUNCH("refine_topk_kernel");
     return DCPQ_OK;
+}
+
+int launch_refine(const float *tables, uint32_t table_size, const void *codes, int code_bytes, uint64_t n_codes, int m,
+                  const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws,
+                  hipStream_t st)
+{
+    if (code_bytes == 1)
+        return launch_refine_t(tables, table_size, static_cast<const uint8_t *>(codes), n_codes, m, cand_id, nq, r, k, ids,
+                               dist, ws, st);
+    return launch_refine_t(tables, table_size, static_cast<const uint16_t *>(codes), n_codes, m, cand_id, nq, r, k, ids,
+                           dist, ws, st);
 }
 
 }  // namespace dcpq
@@ -184,13 +182,16 @@ extern "C" size_t dcpq_refine_workspace_bytes(int nq, uint32_t r)
     return np2 <= kRefineLdsKeys ? 0 : sizeof(uint64_t) * static_cast<size_t>(nq) * np2;
 }
 
-extern "C" int dcpq_refine_topk(const float *tables, const uint16_t *codes, uint64_t n_codes, int m,
-                                const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
-                                float *dist, void *workspace, size_t workspace_bytes, void *stream)
+extern "C" int dcpq_refine_topk_bits(const float *tables, uint32_t n_entries, const void *codes, int code_bytes,
+                                     uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k,
+                                     uint32_t *ids, float *dist, void *workspace, size_t workspace_bytes, void *stream)
 {
     clear_error();
     DCPQ_REQUIRE(nq >= 0, "refine_topk: nq=%d", nq);
     if (!m_supported(m)) return fail(DCPQ_EUNSUPPORTED, "refine_topk: m=%d not supported", m);
+    DCPQ_REQUIRE(code_bytes == 1 || code_bytes == 2, "refine_topk: code_bytes=%d (1 or 2)", code_bytes);
+    DCPQ_REQUIRE(n_entries == (code_bytes == 1 ? 256u : 65536u),
+                 "refine_topk: tables of %u entries do not cover every value of a %d-byte sub-code", n_entries, code_bytes);
     DCPQ_REQUIRE(k >= 1 && k <= r, "refine_topk: needs 1 <= k <= r (k=%u r=%u)", k, r);
     DCPQ_REQUIRE(n_codes >= 1 && n_codes < (1ull << 32), "refine_topk: n_codes out of range");
     if (nq == 0) return DCPQ_OK;
@@ -198,5 +199,14 @@ extern "C" int dcpq_refine_topk(const float *tables, const uint16_t *codes, uint
     const size_t need = dcpq_refine_workspace_bytes(nq, r);
     if (need && (!workspace || workspace_bytes < need))
         return fail(DCPQ_EWORKSPACE, "refine_topk: workspace %zu < %zu bytes", workspace_bytes, need);
-    return launch_refine(tables, codes, n_codes, m, cand_id, nq, r, k, ids, dist, workspace, as_stream(stream));
+    return launch_refine(tables, n_entries, codes, code_bytes, n_codes, m, cand_id, nq, r, k, ids, dist, workspace,
+                         as_stream(stream));
+}
+
+extern "C" int dcpq_refine_topk(const float *tables, const uint16_t *codes, uint64_t n_codes, int m,
+                                const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
+                                float *dist, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return dcpq_refine_topk_bits(tables, kFullSize, codes, 2, n_codes, m, cand_id, nq, r, k, ids, dist, workspace,
+                                 workspace_bytes, stream);
 }

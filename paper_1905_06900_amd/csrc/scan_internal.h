@@ -90,6 +90,9 @@ int launch_sort_candidates(const uint64_t *keys, int nq, uint32_t r, uint64_t *s
                            uint8_t *cand_qd, hipStream_t st, const uint32_t *flags = nullptr);
 
 #ifdef __HIPCC__
+}  // namespace dcpq
+#include "device_util.h"
+namespace dcpq {
 // Low bytes of the m sub-codes of code i (property P1: the derived index is the low 8 bits).
 template <int M>
 __device__ inline void load_low_bytes(const uint16_t *__restrict__ codes, uint64_t i, uint32_t (&low)[M])
@@ -172,24 +175,6 @@ __device__ inline void load_low_bytes(const uint8_t *__restrict__ plane, uint64_
     } else {
         low[0] = plane[i];
     }
-}
-
-// In-place bitonic sort of n_pow2 64-bit keys by one workgroup (array in LDS or global memory).
-__device__ inline void bitonic_sort(uint64_t *a, uint32_t n_pow2)
-{
-    for (uint32_t size = 2; size <= n_pow2; size <<= 1) {
-        for (uint32_t stride = size >> 1; stride > 0; stride >>= 1) {
-            __syncthreads();
-            for (uint32_t t = threadIdx.x; t < (n_pow2 >> 1); t += blockDim.x) {
-                const uint32_t lo = 2 * t - (t & (stride - 1));
-                const uint32_t hi = lo + stride;
-                const bool up = (lo & size) == 0;
-                const uint64_t x = a[lo], y = a[hi];
-                if ((x > y) == up) { a[lo] = y; a[hi] = x; }
-            }
-        }
-    }
-    __syncthreads();
 }
 #endif
 

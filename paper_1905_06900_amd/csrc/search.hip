@@ -1,5 +1,7 @@
 // Alg. 3 nns_derived end to end (no index): Tables -> Scan -> Refine for a batch of queries,
-// in chunks so that the full 2^16-entry tables of one chunk fit the workspace.
+// in chunks so that the full 2^b-entry tables of one chunk fit the workspace.  b (bits of a sub-code,
+// 16 or 8) and bbar (bits of a derived-codebook index, 1..8) are run-time parameters (the PQ m x bbar,b
+// family of Sec. 3.1); sub-codes are stored in 2 bytes for b = 16 and in 1 byte for b = 8.
 #include "common.h"
 
 namespace dcpq {
@@ -9,13 +11,13 @@ struct SearchPlan {
     size_t off_qtab, off_bounds, off_cand_id, off_cand_qd, off_tables, off_scan, off_refine, total;
 };
 
-static SearchPlan plan_search(uint64_t n_codes, int m, int nq, uint32_t r, int chunk_queries)
+static SearchPlan plan_search(uint64_t n_codes, int m, int nq, uint32_t r, int full_bits, int chunk_queries)
 {
     SearchPlan p{};
     int chunk = chunk_queries;
     if (chunk <= 0) {   // default: about 8 GiB of full tables per chunk (sized for a 288 GB device; the larger
                         // the chunk, the fewer launches share the scan's start-up and tail)
-        const size_t per_q = sizeof(float) * static_cast<size_t>(m) * kFullSize;
+        const size_t per_q = sizeof(float) * (static_cast<size_t>(m) << full_bits);
         chunk = static_cast<int>((static_cast<size_t>(8) << 30) / per_q);
         if (chunk < 64) chunk = 64;
     }
@@ -26,7 +28,7 @@ static SearchPlan plan_search(uint64_t n_codes, int m, int nq, uint32_t r, int c
     p.off_bounds = off;  off = align_up(off + sizeof(float) * 2 * static_cast<size_t>(chunk), 256);
     p.off_cand_id = off; off = align_up(off + sizeof(uint32_t) * static_cast<size_t>(chunk) * r, 256);
     p.off_cand_qd = off; off = align_up(off + static_cast<size_t>(chunk) * r, 256);
-    p.off_tables = off;  off = align_up(off + sizeof(float) * static_cast<size_t>(chunk) * m * kFullSize, 256);
+    p.off_tables = off;  off = align_up(off + sizeof(float) * ((static_cast<size_t>(chunk) * m) << full_bits), 256);
     // The scan and the refinement lay their scratch out for the number of queries they are given, and
     // a smaller batch does not always need less (fewer queries can mean more units or slices), so
     // the regions hold the larger of what a full chunk and what the ragged last chunk need: those
@@ -49,26 +51,34 @@ static SearchPlan plan_search(uint64_t n_codes, int m, int nq, uint32_t r, int c
 
 using namespace dcpq;
 
-extern "C" int dcpq_search_chunk(int m, int nq, int chunk_queries)
+extern "C" int dcpq_search_bits_chunk(int m, int nq, int b, int chunk_queries)
 {
-    if (nq <= 0 || !m_supported(m)) return 0;
-    return plan_search(1, m, nq, 1, chunk_queries).chunk;
+    if (nq <= 0 || !m_supported(m) || !dcpq_bits_supported(b, 1)) return 0;
+    return plan_search(1, m, nq, 1, b, chunk_queries).chunk;
+}
+
+extern "C" int dcpq_search_chunk(int m, int nq, int chunk_queries) { return dcpq_search_bits_chunk(m, nq, kFullBits, chunk_queries); }
+
+extern "C" size_t dcpq_search_bits_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r, int b, int chunk_queries)
+{
+    if (nq <= 0 || !m_supported(m) || n_codes == 0 || r == 0 || r > (1u << 26) || !dcpq_bits_supported(b, 1)) return 0;
+    return plan_search(n_codes, m, nq, r, b, chunk_queries).total;
 }
 
 extern "C" size_t dcpq_search_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r, int chunk_queries)
 {
-    if (nq <= 0 || !m_supported(m) || n_codes == 0 || r == 0 || r > (1u << 26)) return 0;
-    return plan_search(n_codes, m, nq, r, chunk_queries).total;
+    return dcpq_search_bits_workspace_bytes(n_codes, m, nq, r, kFullBits, chunk_queries);
 }
 
-extern "C" int dcpq_search(const float *queries, int nq, const float *codebooks, const float *derived, int m,
-                           int dsub, const uint16_t *codes, uint64_t n_codes, uint32_t r, uint32_t k,
-                           uint32_t *ids, float *dist, int chunk_queries, void *workspace,
-                           size_t workspace_bytes, void *stream)
+extern "C" int dcpq_search_bits(const float *queries, int nq, const float *codebooks, const float *derived, int m,
+                                int dsub, int b, int bbar, const void *codes, uint64_t n_codes, uint32_t r, uint32_t k,
+                                uint32_t *ids, float *dist, int chunk_queries, void *workspace,
+                                size_t workspace_bytes, void *stream)
 {
     clear_error();
     DCPQ_REQUIRE(nq >= 0, "search: nq=%d", nq);
     if (!dcpq_shape_supported(m, dsub)) return fail(DCPQ_EUNSUPPORTED, "search: m=%d dsub=%d not supported", m, dsub);
+    if (!dcpq_bits_supported(b, bbar)) return fail(DCPQ_EUNSUPPORTED, "search: b=%d bbar=%d not supported", b, bbar);
     DCPQ_REQUIRE(n_codes >= 1 && n_codes < (1ull << 32), "search: n_codes out of range");
     DCPQ_REQUIRE(r >= 1 && r <= n_codes && k >= 1 && k <= r, "search: needs 1 <= k <= r <= n_codes");
     DCPQ_REQUIRE(r <= (1u << 26), "search: r=%u above the supported 2^26", r);
@@ -76,7 +86,7 @@ extern "C" int dcpq_search(const float *queries, int nq, const float *codebooks,
     DCPQ_REQUIRE(queries && codebooks && derived && codes && ids && dist && workspace, "search: null pointer");
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "search: workspace must be 256-byte aligned");
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(codes) & 15) == 0, "search: codes must be 16-byte aligned");
-    const SearchPlan p = plan_search(n_codes, m, nq, r, chunk_queries);
+    const SearchPlan p = plan_search(n_codes, m, nq, r, b, chunk_queries);
     if (workspace_bytes < p.total)
         return fail(DCPQ_EWORKSPACE, "search: workspace %zu < %zu bytes", workspace_bytes, p.total);
     uint8_t *base = static_cast<uint8_t *>(workspace);
@@ -87,18 +97,34 @@ extern "C" int dcpq_search(const float *queries, int nq, const float *codebooks,
     float *tables = reinterpret_cast<float *>(base + p.off_tables);
     hipStream_t st = as_stream(stream);
     const int D = m * dsub;
+    const int code_bytes = b / 8;
     for (int q0 = 0; q0 < nq; q0 += p.chunk) {
         const int nc = (nq - q0 < p.chunk) ? nq - q0 : p.chunk;
         const float *y = queries + static_cast<size_t>(q0) * D;
-        int rc = launch_small_tables(y, nc, derived, m, dsub, codes, n_codes, r, qtab, bounds, nullptr, st);
+        int rc = launch_small_tables(y, nc, derived, m, dsub, bbar, codes, code_bytes, n_codes, r, qtab, bounds, nullptr, st);
         if (rc) return rc;
-        rc = launch_scan(codes, n_codes, m, qtab, nc, r, cand_id, cand_qd, base + p.off_scan, DCPQ_SCAN_AUTO, st);
+        // the quantized tables have 256 entries whatever bbar is, and 1-byte sub-codes are their own low-byte plane
+        if (code_bytes == 1)
+            rc = launch_scan(static_cast<const uint8_t *>(codes), n_codes, m, qtab, nc, r, cand_id, cand_qd, base + p.off_scan,
+                             DCPQ_SCAN_AUTO, st);
+        else
+            rc = launch_scan(static_cast<const uint16_t *>(codes), n_codes, m, qtab, nc, r, cand_id, cand_qd,
+                             base + p.off_scan, DCPQ_SCAN_AUTO, st);
         if (rc) return rc;
-        rc = launch_full_tables(y, nc, codebooks, m, dsub, tables, st);
+        rc = launch_distance_tables(y, nc, codebooks, m, dsub, 1 << b, tables, kStageFullTables, st);
         if (rc) return rc;
-        rc = launch_refine(tables, codes, n_codes, m, cand_id, nc, r, k, ids + static_cast<size_t>(q0) * k,
-                           dist + static_cast<size_t>(q0) * k, base + p.off_refine, st);
+        rc = launch_refine(tables, 1u << b, codes, code_bytes, n_codes, m, cand_id, nc, r, k,
+                           ids + static_cast<size_t>(q0) * k, dist + static_cast<size_t>(q0) * k, base + p.off_refine, st);
         if (rc) return rc;
     }
     return DCPQ_OK;
+}
+
+extern "C" int dcpq_search(const float *queries, int nq, const float *codebooks, const float *derived, int m,
+                           int dsub, const uint16_t *codes, uint64_t n_codes, uint32_t r, uint32_t k,
+                           uint32_t *ids, float *dist, int chunk_queries, void *workspace,
+                           size_t workspace_bytes, void *stream)
+{
+    return dcpq_search_bits(queries, nq, codebooks, derived, m, dsub, kFullBits, kSmallBits, codes, n_codes, r, k, ids, dist,
+                            chunk_queries, workspace, workspace_bytes, stream);
 }

@@ -1,0 +1,82 @@
+"""GPU parity tests of the PQ m x bbar,b family (Sec. 3.1 notation): the two-pass search with b-bit
+sub-codes (16 or 8) and bbar-bit derived codebooks (4, 5, 6, 8), stage by stage and fused, against
+the oracle run with the same widths."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1905_06900_amd import binding, synth
+from parity import to_np, assert_topk_matches
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda"
+
+
+def make_case(m, dsub, b, bbar, N, Q, seed):
+    g = torch.Generator(device=DEV); g.manual_seed(seed)
+    pbits = min(4, bbar)
+    cb = synth.hierarchical_codebooks(m, dsub, b, pbits, lambda shape, gg: 0.3 * torch.randn(
+        shape, generator=gg, device=DEV, dtype=torch.float32), 0.05, DEV, seed + 1)
+    if b == 16:
+        codes = synth.random_codes(N, m, DEV, seed + 2).view(torch.uint16)
+    else:
+        codes = torch.randint(0, 256, (N, m), generator=g, device=DEV, dtype=torch.uint8)
+    queries = 0.3 * torch.randn((Q, m * dsub), generator=g, device=DEV, dtype=torch.float32)
+    return cb, codes, queries
+
+
+CASES = [  # (b, bbar, m, dsub, N, Q, r)
+    (16, 8, 4, 8, 60_003, 19, 400),
+    (16, 6, 4, 8, 60_003, 19, 400),
+    (16, 4, 8, 6, 50_001, 21, 300),
+    (8, 4, 8, 6, 70_001, 37, 500),
+    (8, 5, 4, 8, 40_003, 9, 300),
+    (8, 6, 16, 4, 30_001, 11, 200),
+    (8, 8, 8, 6, 30_001, 11, 200),
+    (8, 4, 2, 16, 30_001, 5, 100),
+]
+
+
+@pytest.mark.parametrize("b,bbar,m,dsub,N,Q,r", CASES)
+def test_two_pass_search_with_these_bit_widths(b, bbar, m, dsub, N, Q, r):
+    print("PQ %dx%d,%d dsub=%d N=%d Q=%d r=%d" % (m, bbar, b, dsub, N, Q, r), flush=True)
+    k = 50
+    cb, codes, queries = make_case(m, dsub, b, bbar, N, Q, 7000 + 10 * b + bbar)
+    derived = binding.derive_codebooks(cb, bbar)
+    qtab, bounds, small = binding.build_small_tables(queries, derived, codes, r, want_small=True)
+    cand_id, cand_qd = binding.scan_candidates(codes, qtab, r)
+    tables = binding.build_tables_n(queries, cb)
+    ids, dist = binding.refine_topk(tables, codes, cand_id, k)
+    fids, fdist = binding.search(queries, cb, derived, codes, r, k)
+    torch.cuda.synchronize()
+
+    cb_np, q_np = to_np(cb), to_np(queries)
+    codes_np = to_np(codes).astype(np.uint16)
+    der_ref = oracle.derive_codebooks(cb_np, b=b, bbar=bbar)
+    ref = oracle.search_flat(cb_np, der_ref, codes_np, q_np, r, k, b=b, bbar=bbar)
+    ks = 1 << bbar
+    np.testing.assert_array_equal(to_np(derived), der_ref, err_msg="derived codebooks")
+    np.testing.assert_array_equal(to_np(small), ref["small"], err_msg="small tables")
+    np.testing.assert_array_equal(to_np(bounds), ref["bounds"], err_msg="qmin/qmax")
+    qt = to_np(qtab)
+    np.testing.assert_array_equal(qt[:, :, :ks], ref["qtab"], err_msg="quantized tables")
+    np.testing.assert_array_equal(qt, np.tile(ref["qtab"], (1, 1, 256 // ks)), err_msg="quantized tables, replicas")
+    np.testing.assert_array_equal(to_np(cand_id), ref["cand_id"], err_msg="candidate ids")
+    np.testing.assert_array_equal(to_np(cand_qd), ref["cand_qd"], err_msg="candidate qd")
+    ids, dist = to_np(ids), to_np(dist)
+    for q in range(Q):
+        exact = oracle.refine(q_np[q], cb_np, codes_np, ids[q], b=b)
+        assert_topk_matches(ids[q], dist[q], ref["ids"][q], ref["dist"][q], exact, cand_ref=ref["cand_id"][q],
+                            tag="query %d" % q)
+    np.testing.assert_array_equal(to_np(fids), ids, err_msg="fused search ids")
+    np.testing.assert_array_equal(to_np(fdist), dist, err_msg="fused search distances")
+
+
+def test_unsupported_widths_are_refused():
+    assert binding.lib().dcpq_bits_supported(16, 8) == 1 and binding.lib().dcpq_bits_supported(8, 4) == 1
+    assert binding.lib().dcpq_bits_supported(12, 8) == 0 and binding.lib().dcpq_bits_supported(8, 9) == 0
+    cb = torch.zeros((2, 4096, 4), dtype=torch.float32, device=DEV)      # b = 12
+    with pytest.raises(binding.DcpqError):
+        binding.derive_codebooks(cb, 8)
