@@ -335,7 +335,9 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode)
         p.ntiles = static_cast<uint32_t>((Q + p.fqt - 1) / p.fqt);
         // workgroups along the codes, about 8 rounds of the 256 CUs in total, at least 16 Ki codes each
         const uint64_t rest = n_codes;
-        const uint64_t want = (2048 + p.ntiles - 1) / p.ntiles;
+        // (a single tile does the same work in every workgroup, and one round of the 256 CUs measured
+        // fastest for it; with several tiles the work per workgroup varies and more rounds even it out)
+        const uint64_t want = p.ntiles == 1 ? 256 : (2048 + p.ntiles - 1) / p.ntiles;
         const uint64_t most = (rest + 16383) / 16384;
         uint64_t fb = want < most ? want : most;
         if (fb < 1) fb = 1;

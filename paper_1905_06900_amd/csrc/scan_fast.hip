@@ -453,7 +453,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     // The accumulations over the rows of the iteration at position p of group g (independent chains,
     // UC steps at a time so that few accumulators are live at once), the sign test of each such
     // chunk, and (for a few per cent of the chunks) the hits
-    constexpr int UC = U < 2 ? U : 2;
+    constexpr int UC = U < 4 ? U : 4;
     auto compute = [&](const v4i (&a)[U][C::NMF], const v4i acc0, uint32_t g, int p) {
 #pragma unroll
         for (int uc = 0; uc < U; uc += UC) {
@@ -475,20 +475,22 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
                     for (int u = 0; u < UC; ++u)
                         acc[u] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[uc + u][f], bsel, acc[u], 0, 0, 0);
             }
-            int sign = acc[0][0] | acc[0][1] | acc[0][2];
-            sign = sign | acc[0][3];
+            // OR of all 4 UC results, two new values per three-input OR
+            int sign = acc[0][0];
 #pragma unroll
-            for (int u = 1; u < UC; ++u) {
-                sign = sign | acc[u][0] | acc[u][1];
-                sign = sign | acc[u][2] | acc[u][3];
-            }
+            for (int x = 1; x + 1 < 4 * UC; x += 2) sign = sign | acc[x >> 2][x & 3] | acc[(x + 1) >> 2][(x + 1) & 3];
+            sign = sign | acc[UC - 1][3];
             if (!__builtin_amdgcn_ballot_w64(sign < 0)) continue;    // uniform
             // codes in this group: fewer than 64 in the last group of the stretch, none past it
             const uint32_t gbase = cbeg + g * 64u;
             const int nlive = g < ngroups ? static_cast<int>(min(64u, cend - gbase)) : 0;
 #pragma unroll
             for (int u = 0; u < UC; ++u) {
-                const int su = acc[u][0] | acc[u][1] | acc[u][2] | acc[u][3];
+                // (taken apart from the OR above on purpose: sharing sub-terms with it would put one more
+                // instruction on the path of the chunks without a hit, which are nearly all)
+                int su = acc[u][0];
+                asm volatile("" : "+v"(su));
+                su = su | acc[u][1] | acc[u][2] | acc[u][3];
                 if (!__builtin_amdgcn_ballot_w64(su < 0)) continue;      // uniform: no hit in this step
                 const int first = (p * U + uc + u) * C::CPS;    // first code of the step within the group
 #pragma unroll
@@ -520,14 +522,20 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
         }
     };
 
+    // With 64-query tiles the rows of the next iteration are in flight while this one is summed (two
+    // register sets).  The smaller tiles keep one set: they are used where few queries face the code
+    // stream, the memory system rather than the LDS sets their pace, and the second set would push
+    // per-lane constants out of the register file into scratch memory, whose reloads wait behind
+    // (and so serialize with) the prefetched code loads.
+    constexpr bool DEEP = C::NSLOT == 4;
     if (ng_w) {
-        v4i ra[U][C::NMF], rb[U][C::NMF];
+        v4i ra[U][C::NMF], rb[DEEP ? U : 1][C::NMF];
         uint2 w[2];
         next_group();
         w[0] = read_word(0);
         if constexpr (NI == 1) next_group();
         w[1] = read_word(NI == 1 ? 0 : 1);
-        issue_rows(w[0], ra);
+        if constexpr (DEEP) issue_rows(w[0], ra);
 #pragma unroll 1
         for (uint32_t gi = 0; gi < ng_w; gi += GB) {
             if (gi % PF == 0) {                                  // uniform
@@ -553,11 +561,18 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
             for (int t = 0; t < GB * NI; ++t) {
                 // code bytes of the iteration after the next (into the word whose rows are already
                 // on their way), then the rows of the next iteration
-                if ((t + 2) % NI == 0) next_group();
-                w[t % 2] = read_word((t + 2) % NI);
-                if (t % 2 == 0) issue_rows(w[1], rb); else issue_rows(w[0], ra);
-                if (t % 2 == 0) compute(ra, acc0, g + (t / NI) * WAVES, t % NI);
-                else compute(rb, acc0, g + (t / NI) * WAVES, t % NI);
+                if constexpr (DEEP) {
+                    if ((t + 2) % NI == 0) next_group();
+                    w[t % 2] = read_word((t + 2) % NI);
+                    if (t % 2 == 0) issue_rows(w[1], rb); else issue_rows(w[0], ra);
+                    if (t % 2 == 0) compute(ra, acc0, g + (t / NI) * WAVES, t % NI);
+                    else compute(rb, acc0, g + (t / NI) * WAVES, t % NI);
+                } else {
+                    issue_rows(w[t % 2], ra);
+                    if ((t + 2) % NI == 0) next_group();
+                    w[t % 2] = read_word((t + 2) % NI);
+                    compute(ra, acc0, g + (t / NI) * WAVES, t % NI);
+                }
             }
         }
     }
