@@ -213,10 +213,29 @@ int dcpq_refine_topk_bits(const float *tables, uint32_t n_entries, const void *c
                           uint32_t *ids, float *dist, void *workspace, size_t workspace_bytes, void *stream);
 size_t dcpq_search_bits_workspace_bytes(uint64_t n_codes, int m, int nq, uint32_t r, int b, int chunk_queries);
 int dcpq_search_bits_chunk(int m, int nq, int b, int chunk_queries);
+/* refine_mode: how pass two gets its table entries (Sec. 3.3, Refine step: the entries of the full
+ * tables are computed on demand, since a query uses a small part of them).
+ *   DCPQ_REFINE_TABLES  build the full tables of the chunk first, then look entries up
+ *   DCPQ_REFINE_DIRECT  compute every entry a candidate needs from the codebooks (fp64, rounded to
+ *                       fp32 once: the value the tables would hold, up to the last bit); no tables
+ *   DCPQ_REFINE_AUTO    DIRECT while r <= 2^b / 8, else TABLES (dcpq_search uses this);
+ *                       dcpq_search_refine_mode reports the choice
+ * Both give the fp32 sum, j increasing, of the M entries; results agree within the 1e-5 bar and may
+ * differ in the last bit (and then in the order of near-ties). */
+#define DCPQ_REFINE_AUTO 0
+#define DCPQ_REFINE_TABLES 1
+#define DCPQ_REFINE_DIRECT 2
+int dcpq_search_refine_mode(int b, int dsub, uint32_t r, int refine_mode);
 int dcpq_search_bits(const float *queries, int nq, const float *codebooks, const float *derived, int m,
                      int dsub, int b, int bbar, const void *codes, uint64_t n_codes, uint32_t r, uint32_t k,
-                     uint32_t *ids, float *dist, int chunk_queries, void *workspace,
+                     int refine_mode, uint32_t *ids, float *dist, int chunk_queries, void *workspace,
                      size_t workspace_bytes, void *stream);
+/* Pass two on its own with on-demand entries:  queries [nq][m*dsub], codebooks [m][2^b][dsub] (16-byte
+ * aligned), codes of b/8 bytes per sub-code; otherwise as dcpq_refine_topk. */
+int dcpq_refine_direct_topk(const float *queries, const float *codebooks, int m, int dsub, int b,
+                            const void *codes, uint64_t n_codes, const uint32_t *cand_id, int nq, uint32_t r,
+                            uint32_t k, uint32_t *ids, float *dist, void *workspace, size_t workspace_bytes,
+                            void *stream);
 
 /* ---------------------------------------------------------------------------------------------
  * plain_search -- Alg. 1 (Sec. 2.3): the conventional single-pass search the paper compares with:

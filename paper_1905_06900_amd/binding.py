@@ -40,7 +40,9 @@ _SIGNATURES = {
     "dcpq_refine_topk_bits": (_i, [_vp, _u32, _vp, _i, _u64, _i, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_search_bits_chunk": (_i, [_i, _i, _i, _i]),
     "dcpq_search_bits_workspace_bytes": (_sz, [_u64, _i, _i, _u32, _i, _i]),
-    "dcpq_search_bits": (_i, [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp, _u64, _u32, _u32, _vp, _vp, _i, _vp, _sz, _vp]),
+    "dcpq_search_bits": (_i, [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp, _u64, _u32, _u32, _i, _vp, _vp, _i, _vp, _sz, _vp]),
+    "dcpq_search_refine_mode": (_i, [_i, _i, _u32, _i]),
+    "dcpq_refine_direct_topk": (_i, [_vp, _vp, _i, _i, _i, _vp, _u64, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_build_tables": (_i, [_vp, _i, _vp, _i, _i, _vp, _vp]),
     "dcpq_build_tables_n": (_i, [_vp, _i, _vp, _i, _i, _i, _vp, _vp]),
     "dcpq_plain_workspace_bytes": (_sz, [_u64, _i, _u32]),
@@ -302,6 +304,33 @@ def refine_topk(tables: torch.Tensor, codes: torch.Tensor, cand_id: torch.Tensor
     return ids, dist
 
 
+REFINE_AUTO, REFINE_TABLES, REFINE_DIRECT = 0, 1, 2
+
+
+def search_refine_mode(b: int, dsub: int, r: int, refine_mode: int = REFINE_AUTO) -> int:
+    return int(lib().dcpq_search_refine_mode(b, dsub, r, refine_mode))
+
+
+def refine_direct_topk(queries: torch.Tensor, codebooks: torch.Tensor, codes: torch.Tensor, cand_id: torch.Tensor,
+                       k: int, workspace: torch.Tensor | None = None):
+    """Pass two with table entries computed on demand -> (ids u32 [nq][k], dist f32 [nq][k])"""
+    n, m = codes.shape
+    nq, r = cand_id.shape
+    _, kf, dsub = codebooks.shape
+    b = _bits_of(kf)
+    assert codes.element_size() * 8 == b and queries.shape == (nq, m * dsub)
+    dev = codes.device
+    ids = torch.empty((nq, k), dtype=torch.uint32, device=dev)
+    dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = _workspace(lib().dcpq_refine_workspace_bytes(nq, r), dev)
+    _check(lib().dcpq_refine_direct_topk(_dev(queries, torch.float32, "queries"), _dev(codebooks, torch.float32, "codebooks"),
+                                         m, dsub, b, _dev(codes, codes.dtype, "codes"), n,
+                                         _dev(cand_id, torch.uint32, "cand_id"), nq, r, k, ids.data_ptr(), dist.data_ptr(),
+                                         workspace.data_ptr(), workspace.numel(), _stream()))
+    return ids, dist
+
+
 def search_workspace_bytes(n_codes: int, m: int, nq: int, r: int, chunk_queries: int = 0, b: int = 16) -> int:
     if b == 16:
         return int(lib().dcpq_search_workspace_bytes(n_codes, m, nq, r, chunk_queries))
@@ -310,7 +339,7 @@ def search_workspace_bytes(n_codes: int, m: int, nq: int, r: int, chunk_queries:
 
 def search(queries: torch.Tensor, codebooks: torch.Tensor, derived: torch.Tensor, codes: torch.Tensor,
            r: int, k: int, chunk_queries: int = 0, workspace: torch.Tensor | None = None,
-           ids: torch.Tensor | None = None, dist: torch.Tensor | None = None):
+           ids: torch.Tensor | None = None, dist: torch.Tensor | None = None, refine_mode: int = REFINE_AUTO):
     """Alg. 3 end to end without an index -> (ids u32 [nq][k], dist f32 [nq][k]); b from `codebooks`
     ([m][2^b][dsub]), bbar from `derived` ([m][2^bbar][dsub])"""
     m, kf, dsub = codebooks.shape
@@ -326,7 +355,7 @@ def search(queries: torch.Tensor, codebooks: torch.Tensor, derived: torch.Tensor
         dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
     if workspace is None:
         workspace = _workspace(search_workspace_bytes(n, m, nq, r, chunk_queries, b), dev)
-    if (b, bbar) == (16, 8):
+    if (b, bbar) == (16, 8) and refine_mode == REFINE_AUTO:
         _check(lib().dcpq_search(_dev(queries, torch.float32, "queries"), nq,
                                  _dev(codebooks, torch.float32, "codebooks"), _dev(derived, torch.float32, "derived"),
                                  m, dsub, _dev(codes, torch.uint16, "codes"), n, r, k, ids.data_ptr(), dist.data_ptr(),
@@ -334,8 +363,8 @@ def search(queries: torch.Tensor, codebooks: torch.Tensor, derived: torch.Tensor
     else:
         _check(lib().dcpq_search_bits(_dev(queries, torch.float32, "queries"), nq,
                                       _dev(codebooks, torch.float32, "codebooks"), _dev(derived, torch.float32, "derived"),
-                                      m, dsub, b, bbar, _dev(codes, codes.dtype, "codes"), n, r, k, ids.data_ptr(),
-                                      dist.data_ptr(), chunk_queries, workspace.data_ptr(), workspace.numel(), _stream()))
+                                      m, dsub, b, bbar, _dev(codes, codes.dtype, "codes"), n, r, k, refine_mode,
+                                      ids.data_ptr(), dist.data_ptr(), chunk_queries, workspace.data_ptr(), workspace.numel(), _stream()))
     return ids, dist
 
 

@@ -96,5 +96,9 @@ int launch_scan(const uint8_t *plane, uint64_t n_codes, int m, const uint8_t *qt
 int launch_refine(const float *tables, uint32_t table_size, const void *codes, int code_bytes, uint64_t n_codes, int m,
                   const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws,
                   hipStream_t st);
+// the same with every table entry computed on demand from the codebooks (no tables)
+int launch_refine_direct(const float *queries, const float *codebooks, int dsub, uint32_t table_size, const void *codes,
+                         int code_bytes, uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k,
+                         uint32_t *ids, float *dist, void *ws, hipStream_t st);
 
 }  // namespace dcpq

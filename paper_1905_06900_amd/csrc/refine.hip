@@ -24,8 +24,17 @@ static uint32_t next_pow2_r(uint32_t x)
 }
 
 // CodeT: uint16_t or uint8_t sub-codes; table_size = 2^b entries per sub-quantizer.
-template <int M, typename CodeT>
-__global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restrict__ tables, uint32_t table_size,
+// DIRECT = false: `src` = the full tables [nq][M][table_size], an entry is looked up.
+// DIRECT = true:  `src` = the queries [nq][M * dsub]; an entry (Eq. 1: squared distance between the
+//   query's sub-vector and the centroid the sub-code names) is computed when a candidate asks for it,
+//   straight from the codebook `cb` [M][table_size][dsub] -- the refinement of Alg. 3 computes table
+//   entries on demand because only a small part of a 2^16-entry table is ever used (Sec. 3.3,
+//   Refine step); here nothing is memoized, the entry is recomputed in double precision and rounded
+//   to fp32 once, which is what the tables hold.  Either way the distance is the fp32 sum of the M
+//   entries, j increasing.
+template <int M, typename CodeT, bool DIRECT>
+__global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restrict__ src, uint32_t table_size,
+                                                          const float *__restrict__ cb, int dsub,
                                                           const CodeT *__restrict__ codes, uint32_t n_codes,
                                                           const uint32_t *__restrict__ cand_id, uint32_t r,
                                                           uint32_t k, uint32_t n_pow2, int use_lds,
@@ -35,20 +44,71 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
     extern __shared__ __align__(16) uint8_t smem[];
     const int q = blockIdx.x;
     uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(q) * n_pow2;
-    const float *tq = tables + static_cast<size_t>(q) * M * table_size;
-    for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x) {
-        uint64_t key = ~0ull;
-        if (t < r) {
-            const uint32_t id = cand_id[static_cast<size_t>(q) * r + t];
-            if (id < n_codes) {                 // pad slots (and anything out of range) sort last
-                const CodeT *c = codes + static_cast<size_t>(id) * M;
-                float d = tq[c[0]];
-#pragma unroll
-                for (int j = 1; j < M; ++j) d = __fadd_rn(d, tq[static_cast<size_t>(j) * table_size + c[j]]);
-                key = make_key(__float_as_uint(d), id);
+    const float *tq = nullptr;
+    float *ly = nullptr;
+    if constexpr (DIRECT) {
+        const int D = M * dsub;
+        ly = reinterpret_cast<float *>(smem + (use_lds ? sizeof(uint64_t) * n_pow2 : 0));     // the query
+        for (int t = threadIdx.x; t < D; t += blockDim.x) ly[t] = src[static_cast<size_t>(q) * D + t];
+        __syncthreads();
+    } else {
+        tq = src + static_cast<size_t>(q) * M * table_size;
+    }
+    if constexpr (DIRECT) {
+        // One lane per (candidate, sub-quantizer): the M lanes of a candidate are neighbours in a
+        // wavefront, each computes one entry, and the first of them adds the M entries up in order.
+        const bool vec4 = (dsub & 3) == 0;                               // rows of whole 16-byte vectors
+        const uint32_t lane = threadIdx.x & 63u;
+        const int j = static_cast<int>(threadIdx.x % M);
+        const float *yj = ly + j * dsub;
+        for (uint32_t base = 0; base < n_pow2; base += blockDim.x / M) {  // uniform trip count
+            const uint32_t t = base + threadIdx.x / M;
+            uint32_t id = 0xFFFFFFFFu;
+            if (t < r) id = cand_id[static_cast<size_t>(q) * r + t];
+            float e = 0.0f;
+            if (id < n_codes) {                                          // pad slots (and anything out of range) sort last
+                const uint32_t cj = codes[static_cast<size_t>(id) * M + j];
+                const float *cen = cb + (static_cast<size_t>(j) * table_size + cj) * dsub;
+                double dj = 0.0;
+                if (vec4) {
+#pragma unroll 4
+                    for (int tt = 0; tt < dsub; tt += 4) {
+                        const float4 cv = *reinterpret_cast<const float4 *>(cen + tt);
+                        const float4 yv = *reinterpret_cast<const float4 *>(yj + tt);
+                        const double d0 = static_cast<double>(yv.x) - static_cast<double>(cv.x);
+                        const double d1 = static_cast<double>(yv.y) - static_cast<double>(cv.y);
+                        const double d2 = static_cast<double>(yv.z) - static_cast<double>(cv.z);
+                        const double d3 = static_cast<double>(yv.w) - static_cast<double>(cv.w);
+                        dj = fma(d0, d0, dj); dj = fma(d1, d1, dj); dj = fma(d2, d2, dj); dj = fma(d3, d3, dj);
+                    }
+                } else {
+                    for (int tt = 0; tt < dsub; ++tt) {
+                        const double df = static_cast<double>(yj[tt]) - static_cast<double>(cen[tt]);
+                        dj = fma(df, df, dj);
+                    }
+                }
+                e = static_cast<float>(dj);
             }
+            float d = __shfl(e, static_cast<int>(lane - j));
+#pragma unroll
+            for (int jj = 1; jj < M; ++jj) d = __fadd_rn(d, __shfl(e, static_cast<int>(lane - j + jj)));
+            if (j == 0 && t < n_pow2) a[t] = id < n_codes ? make_key(__float_as_uint(d), id) : ~0ull;
         }
-        a[t] = key;
+    } else {
+        for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x) {
+            uint64_t key = ~0ull;
+            if (t < r) {
+                const uint32_t id = cand_id[static_cast<size_t>(q) * r + t];
+                if (id < n_codes) {                 // pad slots (and anything out of range) sort last
+                    const CodeT *c = codes + static_cast<size_t>(id) * M;
+                    float d = tq[c[0]];
+#pragma unroll
+                    for (int j = 1; j < M; ++j) d = __fadd_rn(d, tq[static_cast<size_t>(j) * table_size + c[j]]);
+                    key = make_key(__float_as_uint(d), id);
+                }
+            }
+            a[t] = key;
+        }
     }
     __syncthreads();
     // ---- cut down by value ----------------------------------------------------------------
@@ -135,29 +195,37 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
     }
 }
 
-template <typename CodeT>
-static int launch_refine_t(const float *tables, uint32_t table_size, const CodeT *codes, uint64_t n_codes, int m,
-                           const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws,
-                           hipStream_t st)
+template <int M, typename CodeT, bool DIRECT>
+static int launch_refine_m(const float *src, uint32_t table_size, const float *cb, int dsub, const CodeT *codes,
+                           uint64_t n_codes, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
+                           float *dist, void *ws, hipStream_t st)
 {
-    if (nq == 0) return DCPQ_OK;
     const uint32_t np2 = next_pow2_r(r);
     const int use_lds = np2 <= kRefineLdsKeys;
-    const size_t lds = use_lds ? sizeof(uint64_t) * np2 : 0;
-    uint64_t *spill = static_cast<uint64_t *>(ws);
-#define DCPQ_LAUNCH_REFINE(MV)                                                                                     \
-    case MV:                                                                                                       \
-        DCPQ_LAUNCH(kStageRefine, st, (refine_topk_kernel<MV, CodeT>), dim3(nq), dim3(1024), lds, tables, table_size, \
-                    codes, static_cast<uint32_t>(n_codes), cand_id, r, k, np2, use_lds, spill, ids, dist);         \
-        break;
+    const size_t lds = (use_lds ? sizeof(uint64_t) * np2 : 0) + (DIRECT ? sizeof(float) * M * dsub : 0);
+    const int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&refine_topk_kernel<M, CodeT, DIRECT>), static_cast<int>(lds));
+    if (rc) return rc;
+    DCPQ_LAUNCH(kStageRefine, st, (refine_topk_kernel<M, CodeT, DIRECT>), dim3(nq), dim3(1024), lds, src, table_size, cb, dsub,
+                codes, static_cast<uint32_t>(n_codes), cand_id, r, k, np2, use_lds, static_cast<uint64_t *>(ws), ids, dist);
+    DCPQ_CHECK_LAUNCH("refine_topk_kernel");
+    return DCPQ_OK;
+}
+
+template <typename CodeT, bool DIRECT>
+static int launch_refine_t(const float *src, uint32_t table_size, const float *cb, int dsub, const CodeT *codes,
+                           uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
+                           float *dist, void *ws, hipStream_t st)
+{
+    if (nq == 0) return DCPQ_OK;
+#define DCPQ_LAUNCH_REFINE(MV)                                                                                      \
+    case MV:                                                                                                        \
+        return launch_refine_m<MV, CodeT, DIRECT>(src, table_size, cb, dsub, codes, n_codes, cand_id, nq, r, k, ids, dist, ws, st);
     switch (m) {
         DCPQ_LAUNCH_REFINE(1) DCPQ_LAUNCH_REFINE(2) DCPQ_LAUNCH_REFINE(4) DCPQ_LAUNCH_REFINE(8)
         DCPQ_LAUNCH_REFINE(16) DCPQ_LAUNCH_REFINE(32)
         default: return fail(DCPQ_EUNSUPPORTED, "m=%d not supported", m);
     }
 #undef DCPQ_LAUNCH_REFINE
-    DCPQ_CHECK_LAUNCH("refine_topk_kernel");
-    return DCPQ_OK;
 }
 
 int launch_refine(const float *tables, uint32_t table_size, const void *codes, int code_bytes, uint64_t n_codes, int m,
@@ -165,10 +233,21 @@ int launch_refine(const float *tables, uint32_t table_size, const void *codes, i
                   hipStream_t st)
 {
     if (code_bytes == 1)
-        return launch_refine_t(tables, table_size, static_cast<const uint8_t *>(codes), n_codes, m, cand_id, nq, r, k, ids,
-                               dist, ws, st);
-    return launch_refine_t(tables, table_size, static_cast<const uint16_t *>(codes), n_codes, m, cand_id, nq, r, k, ids,
-                           dist, ws, st);
+        return launch_refine_t<uint8_t, false>(tables, table_size, nullptr, 0, static_cast<const uint8_t *>(codes), n_codes, m,
+                                               cand_id, nq, r, k, ids, dist, ws, st);
+    return launch_refine_t<uint16_t, false>(tables, table_size, nullptr, 0, static_cast<const uint16_t *>(codes), n_codes, m,
+                                            cand_id, nq, r, k, ids, dist, ws, st);
+}
+
+int launch_refine_direct(const float *queries, const float *codebooks, int dsub, uint32_t table_size, const void *codes,
+                         int code_bytes, uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k,
+                         uint32_t *ids, float *dist, void *ws, hipStream_t st)
+{
+    if (code_bytes == 1)
+        return launch_refine_t<uint8_t, true>(queries, table_size, codebooks, dsub, static_cast<const uint8_t *>(codes), n_codes,
+                                              m, cand_id, nq, r, k, ids, dist, ws, st);
+    return launch_refine_t<uint16_t, true>(queries, table_size, codebooks, dsub, static_cast<const uint16_t *>(codes), n_codes, m,
+                                           cand_id, nq, r, k, ids, dist, ws, st);
 }
 
 }  // namespace dcpq
@@ -201,6 +280,27 @@ extern "C" int dcpq_refine_topk_bits(const float *tables, uint32_t n_entries, co
         return fail(DCPQ_EWORKSPACE, "refine_topk: workspace %zu < %zu bytes", workspace_bytes, need);
     return launch_refine(tables, n_entries, codes, code_bytes, n_codes, m, cand_id, nq, r, k, ids, dist, workspace,
                          as_stream(stream));
+}
+
+extern "C" int dcpq_refine_direct_topk(const float *queries, const float *codebooks, int m, int dsub, int b,
+                                       const void *codes, uint64_t n_codes, const uint32_t *cand_id, int nq, uint32_t r,
+                                       uint32_t k, uint32_t *ids, float *dist, void *workspace, size_t workspace_bytes,
+                                       void *stream)
+{
+    clear_error();
+    DCPQ_REQUIRE(nq >= 0, "refine_direct_topk: nq=%d", nq);
+    if (!dcpq_shape_supported(m, dsub)) return fail(DCPQ_EUNSUPPORTED, "refine_direct_topk: m=%d dsub=%d not supported", m, dsub);
+    if (!dcpq_bits_supported(b, 1)) return fail(DCPQ_EUNSUPPORTED, "refine_direct_topk: b=%d not supported", b);
+    DCPQ_REQUIRE(k >= 1 && k <= r, "refine_direct_topk: needs 1 <= k <= r (k=%u r=%u)", k, r);
+    DCPQ_REQUIRE(n_codes >= 1 && n_codes < (1ull << 32), "refine_direct_topk: n_codes out of range");
+    if (nq == 0) return DCPQ_OK;
+    DCPQ_REQUIRE(queries && codebooks && codes && cand_id && ids && dist, "refine_direct_topk: null pointer");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(codebooks) & 15) == 0, "refine_direct_topk: codebooks must be 16-byte aligned");
+    const size_t need = dcpq_refine_workspace_bytes(nq, r);
+    if (need && (!workspace || workspace_bytes < need))
+        return fail(DCPQ_EWORKSPACE, "refine_direct_topk: workspace %zu < %zu bytes", workspace_bytes, need);
+    return launch_refine_direct(queries, codebooks, dsub, 1u << b, codes, b / 8, n_codes, m, cand_id, nq, r, k, ids, dist,
+                                workspace, as_stream(stream));
 }
 
 extern "C" int dcpq_refine_topk(const float *tables, const uint16_t *codes, uint64_t n_codes, int m,

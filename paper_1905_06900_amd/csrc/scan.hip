@@ -363,8 +363,12 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode)
         }
         const uint32_t want_sort = next_pow2(2 * r);
         p.sortcap = want_sort < kSortLdsKeys ? kSortLdsKeys : want_sort;
-        // sample: runs of 256 codes spread evenly over the array, about 64 r codes (at least 64 Ki)
-        uint64_t s_codes = 64ull * r < 65536 ? 65536 : 64ull * r;
+        // sample: runs of 256 codes spread evenly over the array, 32 r to 256 r codes (at least 64 Ki)
+        // (the larger the sample, the closer the starting bound and the fewer candidates are appended,
+        // but its cost grows with the number of queries: 256 r codes for 16 queries, 32 r from 128 on)
+        uint64_t mul = 4096 / (Q ? Q : 1);
+        mul = mul < 32 ? 32 : mul > 256 ? 256 : mul;
+        uint64_t s_codes = mul * r < 65536 ? 65536 : mul * r;
         if (s_codes > n_codes) s_codes = n_codes;
         p.s_unit = 256;
         p.s_nunits = static_cast<uint32_t>((s_codes + 255) / 256);

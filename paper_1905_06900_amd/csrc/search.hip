@@ -70,9 +70,22 @@ extern "C" size_t dcpq_search_workspace_bytes(uint64_t n_codes, int m, int nq, u
     return dcpq_search_bits_workspace_bytes(n_codes, m, nq, r, kFullBits, chunk_queries);
 }
 
+// Whether pass two computes its table entries on demand (DCPQ_REFINE_DIRECT) or looks them up in full
+// tables built first (DCPQ_REFINE_TABLES).  On demand a query gathers r m centroid rows; with tables it
+// writes 2^b m entries and then makes r m scattered 4-byte lookups.  Measured on MI355X a gathered row
+// costs about 8 ps more than a table lookup (27 against 19 ps for random 16-bit sub-codes, dsub = 12)
+// and a 2^16-entry table 60 to 200 ns to build (dsub = 12 to 60), which puts the break-even near
+// r = 8000 for b = 16; the rule below scales that with the table size.
+static int refine_mode_for(int requested, int b, int dsub, uint32_t r)
+{
+    (void)dsub;
+    if (requested == DCPQ_REFINE_TABLES || requested == DCPQ_REFINE_DIRECT) return requested;
+    return r <= (1u << b) / 8 ? DCPQ_REFINE_DIRECT : DCPQ_REFINE_TABLES;
+}
+
 extern "C" int dcpq_search_bits(const float *queries, int nq, const float *codebooks, const float *derived, int m,
                                 int dsub, int b, int bbar, const void *codes, uint64_t n_codes, uint32_t r, uint32_t k,
-                                uint32_t *ids, float *dist, int chunk_queries, void *workspace,
+                                int refine_mode, uint32_t *ids, float *dist, int chunk_queries, void *workspace,
                                 size_t workspace_bytes, void *stream)
 {
     clear_error();
@@ -82,8 +95,11 @@ extern "C" int dcpq_search_bits(const float *queries, int nq, const float *codeb
     DCPQ_REQUIRE(n_codes >= 1 && n_codes < (1ull << 32), "search: n_codes out of range");
     DCPQ_REQUIRE(r >= 1 && r <= n_codes && k >= 1 && k <= r, "search: needs 1 <= k <= r <= n_codes");
     DCPQ_REQUIRE(r <= (1u << 26), "search: r=%u above the supported 2^26", r);
+    DCPQ_REQUIRE(refine_mode == DCPQ_REFINE_AUTO || refine_mode == DCPQ_REFINE_TABLES || refine_mode == DCPQ_REFINE_DIRECT,
+                 "search: refine_mode=%d", refine_mode);
     if (nq == 0) return DCPQ_OK;
     DCPQ_REQUIRE(queries && codebooks && derived && codes && ids && dist && workspace, "search: null pointer");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(codebooks) & 15) == 0, "search: codebooks must be 16-byte aligned");
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "search: workspace must be 256-byte aligned");
     DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(codes) & 15) == 0, "search: codes must be 16-byte aligned");
     const SearchPlan p = plan_search(n_codes, m, nq, r, b, chunk_queries);
@@ -98,6 +114,7 @@ extern "C" int dcpq_search_bits(const float *queries, int nq, const float *codeb
     hipStream_t st = as_stream(stream);
     const int D = m * dsub;
     const int code_bytes = b / 8;
+    const bool direct = refine_mode_for(refine_mode, b, dsub, r) == DCPQ_REFINE_DIRECT;
     for (int q0 = 0; q0 < nq; q0 += p.chunk) {
         const int nc = (nq - q0 < p.chunk) ? nq - q0 : p.chunk;
         const float *y = queries + static_cast<size_t>(q0) * D;
@@ -111,10 +128,17 @@ extern "C" int dcpq_search_bits(const float *queries, int nq, const float *codeb
             rc = launch_scan(static_cast<const uint16_t *>(codes), n_codes, m, qtab, nc, r, cand_id, cand_qd,
                              base + p.off_scan, DCPQ_SCAN_AUTO, st);
         if (rc) return rc;
-        rc = launch_distance_tables(y, nc, codebooks, m, dsub, 1 << b, tables, kStageFullTables, st);
-        if (rc) return rc;
-        rc = launch_refine(tables, 1u << b, codes, code_bytes, n_codes, m, cand_id, nc, r, k,
-                           ids + static_cast<size_t>(q0) * k, dist + static_cast<size_t>(q0) * k, base + p.off_refine, st);
+        uint32_t *ids_c = ids + static_cast<size_t>(q0) * k;
+        float *dist_c = dist + static_cast<size_t>(q0) * k;
+        if (direct) {
+            rc = launch_refine_direct(y, codebooks, dsub, 1u << b, codes, code_bytes, n_codes, m, cand_id, nc, r, k, ids_c,
+                                      dist_c, base + p.off_refine, st);
+        } else {
+            rc = launch_distance_tables(y, nc, codebooks, m, dsub, 1 << b, tables, kStageFullTables, st);
+            if (rc) return rc;
+            rc = launch_refine(tables, 1u << b, codes, code_bytes, n_codes, m, cand_id, nc, r, k, ids_c, dist_c,
+                               base + p.off_refine, st);
+        }
         if (rc) return rc;
     }
     return DCPQ_OK;
@@ -125,6 +149,11 @@ extern "C" int dcpq_search(const float *queries, int nq, const float *codebooks,
                            uint32_t *ids, float *dist, int chunk_queries, void *workspace,
                            size_t workspace_bytes, void *stream)
 {
-    return dcpq_search_bits(queries, nq, codebooks, derived, m, dsub, kFullBits, kSmallBits, codes, n_codes, r, k, ids, dist,
-                            chunk_queries, workspace, workspace_bytes, stream);
+    return dcpq_search_bits(queries, nq, codebooks, derived, m, dsub, kFullBits, kSmallBits, codes, n_codes, r, k,
+                            DCPQ_REFINE_AUTO, ids, dist, chunk_queries, workspace, workspace_bytes, stream);
+}
+
+extern "C" int dcpq_search_refine_mode(int b, int dsub, uint32_t r, int refine_mode)
+{
+    return refine_mode_for(refine_mode, b, dsub, r);
 }

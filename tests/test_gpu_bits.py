@@ -49,7 +49,8 @@ def test_two_pass_search_with_these_bit_widths(b, bbar, m, dsub, N, Q, r):
     cand_id, cand_qd = binding.scan_candidates(codes, qtab, r)
     tables = binding.build_tables_n(queries, cb)
     ids, dist = binding.refine_topk(tables, codes, cand_id, k)
-    fids, fdist = binding.search(queries, cb, derived, codes, r, k)
+    fids, fdist = binding.search(queries, cb, derived, codes, r, k, refine_mode=binding.REFINE_TABLES)
+    dids, ddist = binding.search(queries, cb, derived, codes, r, k, refine_mode=binding.REFINE_DIRECT)
     torch.cuda.synchronize()
 
     cb_np, q_np = to_np(cb), to_np(queries)
@@ -72,6 +73,11 @@ def test_two_pass_search_with_these_bit_widths(b, bbar, m, dsub, N, Q, r):
                             tag="query %d" % q)
     np.testing.assert_array_equal(to_np(fids), ids, err_msg="fused search ids")
     np.testing.assert_array_equal(to_np(fdist), dist, err_msg="fused search distances")
+    dids, ddist = to_np(dids), to_np(ddist)
+    for q in range(Q):
+        exact = oracle.refine(q_np[q], cb_np, codes_np, dids[q], b=b)
+        assert_topk_matches(dids[q], ddist[q], ref["ids"][q], ref["dist"][q], exact, cand_ref=ref["cand_id"][q],
+                            tag="on-demand refinement, query %d" % q)
 
 
 def test_unsupported_widths_are_refused():

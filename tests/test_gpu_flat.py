@@ -37,10 +37,27 @@ def test_cfg0_scaled_pass_two(case0):
 
 def test_cfg0_scaled_fused_search_matches_staged(case0):
     c = case0
-    ids, dist = binding.search(c.queries, c.cb, c.derived, c.codes, c.w.r, c.w.k, chunk_queries=16)
+    ids, dist = binding.search(c.queries, c.cb, c.derived, c.codes, c.w.r, c.w.k, chunk_queries=16,
+                               refine_mode=binding.REFINE_TABLES)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(to_np(ids), to_np(c.ids))
     np.testing.assert_array_equal(to_np(dist), to_np(c.dist))
+
+
+def test_cfg0_scaled_on_demand_refinement(case0):
+    # pass two with table entries computed on demand: staged and fused agree bit for bit, both match the
+    # oracle, and the default mode of the fused search is this one for the shape (r <= 2^16 / 8)
+    c = case0
+    assert binding.search_refine_mode(16, c.w.dsub, c.w.r) == binding.REFINE_DIRECT
+    assert binding.search_refine_mode(16, c.w.dsub, 10_000) == binding.REFINE_TABLES
+    sids, sdist = binding.refine_direct_topk(c.queries, c.cb, c.codes, c.cand_id, c.w.k)
+    fids, fdist = binding.search(c.queries, c.cb, c.derived, c.codes, c.w.r, c.w.k, chunk_queries=16)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(fids), to_np(sids))
+    np.testing.assert_array_equal(to_np(fdist), to_np(sdist))
+    c.check_pass_two(sids, sdist)
+    # against the table mode: the same distances up to the last bit
+    np.testing.assert_allclose(to_np(sdist), to_np(c.dist), rtol=2e-7)
 
 
 def test_fused_search_m2_with_a_ragged_last_chunk():
