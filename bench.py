@@ -65,6 +65,17 @@ def hbm_roofline(kernel, bytes_per_launch, total_ms, launches, steps, workload, 
     return r
 
 
+def calibration_copy(binding, torch, dev):
+    """One launch of the library's 1 GiB copy kernel: its known traffic scales what rocprofv3 --pmc
+    reports for FETCH_SIZE and WRITE_SIZE in the same run."""
+    a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    b = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    a.zero_()
+    binding.profile_copy(a, b)
+    torch.cuda.synchronize()
+    del a, b
+
+
 def run_flat(w, args, steps, warmup, with_cpu, headline):
     import torch
     from paper_1905_06900_amd import binding, synth
@@ -85,12 +96,7 @@ def run_flat(w, args, steps, warmup, with_cpu, headline):
         binding.search(queries, cb, derived, codes, w.r, w.k, args.chunk, ws, ids, dist, refine_mode)
 
     if args.calibration_copy:
-        a = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        b = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
-        a.zero_()
-        binding.profile_copy(a, b)
-        torch.cuda.synchronize()
-        del a, b
+        calibration_copy(binding, torch, dev)
     elapsed, stages = timed(step, steps, warmup, binding, torch)
     ms_per_step = elapsed / steps * 1e3
     qps = w.Q * steps / elapsed
@@ -259,6 +265,8 @@ def run_ivf(w, args, steps, warmup, with_cpu):
         binding.ivf_search(queries, coarse, cb, derived, codes, offsets, w.nprobe, w.r, w.k, plane=plane,
                            workspace=ws, ids=ids, dist=dist)
 
+    if args.calibration_copy:
+        calibration_copy(binding, torch, dev)
     elapsed, stages = timed(step, steps, warmup, binding, torch)
     qps = w.Q * steps / elapsed
     # codes in the probed lists of the batch: what one pass of the scan streams (no two queries share them)
@@ -280,8 +288,6 @@ def run_ivf(w, args, steps, warmup, with_cpu):
                    "seed": w.seed},
         "roofline": roofline,
         "stage_ms_per_step": {s: round(v[0] / steps, 3) for s, v in stages.items() if v[1]},
-        "refine_mode": {binding.REFINE_TABLES: "tables", binding.REFINE_DIRECT: "direct"}[
-            binding.search_refine_mode(w.b, w.dsub, w.r, refine_mode)],
         "setup_s": round(setup_s, 2),
     }
     if with_cpu:

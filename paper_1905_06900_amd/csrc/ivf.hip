@@ -807,7 +807,7 @@ static int ivf_scan_m(const CodeT *codes, const int64_t *offsets, const int32_t 
                 lds_tab + 4 * 64 * 8, codes, units, nunits, qtab, nprobe, r, p.cap, p.upd, p.qflush, t_cur, fcount, chist,
                 fkeys);
     DCPQ_CHECK_LAUNCH("ivf_scan_single_kernel");
-    rc = launch_fast_select(fkeys, fcount, chist, nq, r, kFastSlices, p.cap, p.sortcap, fsort, cand_id, cand_qd, flags, st);
+    rc = launch_fast_select(fkeys, fcount, chist, nq, r, kFastSlices, p.cap, p.sortcap, 0, fsort, cand_id, cand_qd, flags, st);
     if (rc) return rc;
     // the queries it flagged (a full slice, or fewer than r codes in the probed lists): three passes
     DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist, CodeT>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,

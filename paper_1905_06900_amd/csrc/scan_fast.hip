@@ -579,39 +579,43 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     flush();
 }
 
-// Largest bucket the selection orders by counting ranks (the work grows with the square of the bucket
-// size); queries with a larger bucket at or below the bound go through the bitonic network instead.
-constexpr uint32_t kRankBucket = 2048;
-constexpr uint32_t kRankPad = 1024;          // room for rounding every bucket up to a multiple of 4 ids
-constexpr size_t kSelectLdsMost = 96 * 1024;
+// The selection orders candidates by counting ranks inside small groups (the work grows with the
+// square of the group size); a query with a group larger than this goes through the bitonic network.
+constexpr uint32_t kRankGroup = 2048;
+constexpr int kSubBits = 3, kSub = 1 << kSubBits;      // id ranges per bucket
+constexpr uint32_t kGroups = 256 * kSub;
+constexpr size_t kSelectLdsMost = 120 * 1024;
 
-// LDS of the rank-counting selection: ids (uint32) and their buckets (uint8) for sortcap + kRankPad entries.
-static size_t rank_lds_bytes(uint32_t sortcap) { return 5 * (static_cast<size_t>(sortcap) + kRankPad); }
+// LDS of the rank-counting selection: group counters and group starts (uint32 each), then the ids
+// (uint32) and group numbers (uint16) of up to sortcap candidates.
+static size_t rank_lds_bytes(uint32_t sortcap) { return 8 * static_cast<size_t>(kGroups) + 6 * static_cast<size_t>(sortcap); }
 
 // One workgroup per query: pick the exact r smallest (qd, id) out of the appended superset.
 // flags[q] = 1 when the query must be redone (buffer overflow, fewer than r candidates, or more
 // candidates at or below the bound than the sort area holds).
-// The exact per-bucket counts of the appended candidates give every bucket its place in the output.
-// The candidates at or below the bound are therefore dealt into their buckets (a counting sort by qd)
-// and ordered by id inside the bucket: a candidate's rank is the number of ids of its bucket below its
-// own, counted four ids per LDS read (buckets start at multiples of four and are filled up with the
-// id 2^32 - 1, which no code has).  With r spread over tens of buckets this is several times cheaper
-// than a sorting network over the whole set, which remains for queries with a very large bucket.
+// The candidates at or below the bound are dealt into groups -- (bucket, one of 8 equal ranges of the
+// ids) -- by a counting sort: one pass over the buffer counts the groups, a prefix sum gives every group
+// its place in the output (groups ordered by bucket, then by id range, are already in (qd, id) order),
+// a second pass deals the ids out, and inside a group a candidate's rank is the number of ids below its
+// own.  With r spread over tens of buckets and the ids spread over the array the groups hold a few
+// dozen ids, so this is several times cheaper than a sorting network over the whole set, which remains
+// for queries with a very large group (many equal qd in one stretch of ids).
+// id_mul: the id range of an id is the high word of id * id_mul (below 8 for every id of the array, and
+// non-decreasing in the id, which is all the order needs).
 __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__restrict__ keys,
                                                           const uint32_t *__restrict__ count,
                                                           const uint32_t *__restrict__ chist, uint32_t r, uint32_t nslices,
                                                           uint32_t cap, uint32_t sortcap, int use_lds, int rank_ok,
-                                                          uint64_t *__restrict__ spill,
+                                                          uint32_t id_mul, uint64_t *__restrict__ spill,
                                                           uint32_t *__restrict__ cand_id,
                                                           uint8_t *__restrict__ cand_qd,
                                                           uint32_t *__restrict__ flags)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     __shared__ uint32_t cum[256];                // inclusive prefix of the bucket counts
-    __shared__ uint32_t pcum[256];               // the same with every count rounded up to a multiple of 4
-    __shared__ uint32_t cursor[256];
+    __shared__ uint32_t wsum[16];
     __shared__ uint32_t s_t, s_keep, s_pos, s_big;
-    const int q = blockIdx.x, tid = threadIdx.x;
+    const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t n = 0;
     bool over = false;
     for (uint32_t sl = 0; sl < nslices; ++sl) {
@@ -623,24 +627,19 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
         if (tid == 0) flags[q] = 1;
         return;
     }
-    uint32_t mine = 0;
-    if (tid < 256) {
-        mine = chist[static_cast<size_t>(q) * 256 + tid];
-        cum[tid] = mine; pcum[tid] = (mine + 3u) & ~3u; cursor[tid] = 0;
-    }
+    if (tid < 256) cum[tid] = chist[static_cast<size_t>(q) * 256 + tid];
     if (tid == 0) { s_t = 255; s_keep = n; s_pos = 0; s_big = 0; }
     __syncthreads();
     for (int off = 1; off < 256; off <<= 1) {
-        uint32_t add = 0, padd = 0;
-        if (tid < 256 && tid >= off) { add = cum[tid - off]; padd = pcum[tid - off]; }
+        uint32_t add = 0;
+        if (tid < 256 && tid >= off) add = cum[tid - off];
         __syncthreads();
-        if (tid < 256) { cum[tid] += add; pcum[tid] += padd; }
+        if (tid < 256) cum[tid] += add;
         __syncthreads();
     }
     if (tid < 256) {
         const uint32_t before = tid ? cum[tid - 1] : 0u;
         if (before < r && cum[tid] >= r) { s_t = tid; s_keep = cum[tid]; }
-        if (before < r && mine > kRankBucket) s_big = 1;         // a large bucket at or below the bound
     }
     __syncthreads();
     const uint32_t T = s_t, keep = s_keep;
@@ -648,46 +647,76 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
         if (tid == 0) flags[q] = 1;
         return;
     }
-    if (rank_ok && !s_big) {
-        uint32_t *ids = reinterpret_cast<uint32_t *>(smem);
-        uint8_t *qds = smem + 4 * (static_cast<size_t>(sortcap) + kRankPad);
-        const uint32_t ptotal = pcum[T];                         // <= keep + 3 * 256 <= sortcap + kRankPad
-        for (uint32_t t = tid; t < ptotal; t += 1024) ids[t] = 0xFFFFFFFFu;
+    if (rank_ok) {
+        uint32_t *gcnt = reinterpret_cast<uint32_t *>(smem);              // [kGroups] count, later the deal-out cursor
+        uint32_t *gstart = gcnt + kGroups;                                // [kGroups] first output position of the group
+        uint32_t *ids = gstart + kGroups;                                 // [sortcap]
+        uint16_t *grp = reinterpret_cast<uint16_t *>(ids + sortcap);      // [sortcap]
+        const uint32_t ngroups = (T + 1) * kSub;
+        for (uint32_t t = tid; t < ngroups; t += 1024) gcnt[t] = 0;
         __syncthreads();
-        // one wavefront per slice at a time, so that the slices' loads are in flight together
-        for (uint32_t sl = tid >> 6; sl < nslices; sl += 16) {
+        // count the groups: one wavefront per slice at a time, so that the slices' loads are in flight together
+        for (uint32_t sl = wave; sl < nslices; sl += 16) {
             const size_t cell = static_cast<size_t>(q) * nslices + sl;
             const uint32_t c = count[cell];
 #pragma unroll 4
-            for (uint32_t t = tid & 63; t < c; t += 64) {
+            for (uint32_t t = lane; t < c; t += 64) {
                 const uint64_t key = keys[cell * cap + t];
                 const uint32_t qd = static_cast<uint32_t>(key >> 32);
-                if (qd <= T) {
-                    const uint32_t pos = (qd ? pcum[qd - 1] : 0u) + atomicAdd(&cursor[qd], 1u);
-                    if (pos < pcum[qd]) { ids[pos] = static_cast<uint32_t>(key); qds[pos] = static_cast<uint8_t>(qd); }
-                }
+                if (qd <= T) atomicAdd(&gcnt[qd * kSub + __umulhi(static_cast<uint32_t>(key), id_mul)], 1u);
             }
         }
         __syncthreads();
-        for (uint32_t t = tid; t < ptotal; t += 1024) {
-            const uint32_t id = ids[t];
-            if (id == 0xFFFFFFFFu) continue;                     // filler
-            const uint32_t qd = qds[t];
-            const uint32_t lo4 = (qd ? pcum[qd - 1] : 0u) >> 2, hi4 = pcum[qd] >> 2;
-            const uint4 *v4 = reinterpret_cast<const uint4 *>(ids);
-            uint32_t rank = 0;
-            for (uint32_t k = lo4; k < hi4; ++k) {
-                const uint4 v = v4[k];
-                rank += (v.x < id ? 1u : 0u) + (v.y < id ? 1u : 0u) + (v.z < id ? 1u : 0u) + (v.w < id ? 1u : 0u);
+        // exclusive prefix over the groups (two per thread), and the largest group
+        {
+            const uint32_t g0 = 2 * tid, g1 = 2 * tid + 1;
+            const uint32_t c0 = g0 < ngroups ? gcnt[g0] : 0u, c1 = g1 < ngroups ? gcnt[g1] : 0u;
+            uint32_t incl = c0 + c1;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t other = __shfl(incl, lane >= d ? lane - d : lane);
+                if (lane >= d) incl += other;
             }
-            const uint32_t out = (qd ? cum[qd - 1] : 0u) + rank;
-            if (out < r) {
-                cand_id[static_cast<size_t>(q) * r + out] = id;
-                cand_qd[static_cast<size_t>(q) * r + out] = static_cast<uint8_t>(qd);
-            }
+            if (lane == 63) wsum[wave] = incl;
+            if (c0 > kRankGroup || c1 > kRankGroup) s_big = 1;            // benign race: every writer stores 1
+            __syncthreads();
+            uint32_t before = incl - (c0 + c1);
+            for (int w2 = 0; w2 < wave; ++w2) before += wsum[w2];
+            if (g0 < ngroups) { gstart[g0] = before; gcnt[g0] = 0; }
+            if (g1 < ngroups) { gstart[g1] = before + c0; gcnt[g1] = 0; }
+            __syncthreads();
         }
-        if (tid == 0) flags[q] = 0;
-        return;
+        if (!s_big) {
+            for (uint32_t sl = wave; sl < nslices; sl += 16) {
+                const size_t cell = static_cast<size_t>(q) * nslices + sl;
+                const uint32_t c = count[cell];
+#pragma unroll 4
+                for (uint32_t t = lane; t < c; t += 64) {
+                    const uint64_t key = keys[cell * cap + t];
+                    const uint32_t qd = static_cast<uint32_t>(key >> 32);
+                    if (qd <= T) {
+                        const uint32_t g = qd * kSub + __umulhi(static_cast<uint32_t>(key), id_mul);
+                        const uint32_t pos = gstart[g] + atomicAdd(&gcnt[g], 1u);
+                        if (pos < sortcap) { ids[pos] = static_cast<uint32_t>(key); grp[pos] = static_cast<uint16_t>(g); }
+                    }
+                }
+            }
+            __syncthreads();
+            for (uint32_t t = tid; t < keep; t += 1024) {
+                const uint32_t id = ids[t], g = grp[t];
+                const uint32_t lo = gstart[g], hi = g + 1 < ngroups ? gstart[g + 1] : keep;
+                uint32_t rank = 0;
+                for (uint32_t k = lo; k < hi; ++k) rank += ids[k] < id ? 1u : 0u;
+                const uint32_t out = lo + rank;
+                if (out < r) {
+                    cand_id[static_cast<size_t>(q) * r + out] = id;
+                    cand_qd[static_cast<size_t>(q) * r + out] = static_cast<uint8_t>(g >> kSubBits);
+                }
+            }
+            if (tid == 0) flags[q] = 0;
+            return;
+        }
+        __syncthreads();
     }
     uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(q) * sortcap;
     uint32_t np2 = 1;
@@ -770,7 +799,7 @@ static int launch_fast_t(const CodeT *codes, uint64_t n_codes, const uint8_t *qt
                 p.qflush, t_cur, fcount, chist, fkeys);
     DCPQ_CHECK_LAUNCH("scan_fast_kernel");
     // exact selection + list of queries to redo
-    rc = launch_fast_select(fkeys, fcount, chist, nq, r, p.slices, p.cap, p.sortcap, fsort, cand_id, cand_qd, flags, st);
+    rc = launch_fast_select(fkeys, fcount, chist, nq, r, p.slices, p.cap, p.sortcap, n_codes, fsort, cand_id, cand_qd, flags, st);
     if (rc) return rc;
     DCPQ_LAUNCH(kStageSelect, st, collect_flags_kernel, dim3(1), dim3(64), 0, flags, nq, qlist, nflag);
     DCPQ_CHECK_LAUNCH("collect_flags_kernel");
@@ -785,7 +814,7 @@ int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, uint64_t 
 }
 
 int launch_fast_select(const uint64_t *keys, const uint32_t *count, const uint32_t *chist, int nq, uint32_t r,
-                       uint32_t nslices, uint32_t cap, uint32_t sortcap, uint64_t *spill, uint32_t *cand_id,
+                       uint32_t nslices, uint32_t cap, uint32_t sortcap, uint64_t n_ids, uint64_t *spill, uint32_t *cand_id,
                        uint8_t *cand_qd, uint32_t *flags, hipStream_t st)
 {
     {
@@ -796,8 +825,12 @@ int launch_fast_select(const uint64_t *keys, const uint32_t *count, const uint32
     const int rank_ok = rank_lds_bytes(sortcap) <= kSelectLdsMost;
     size_t lds = use_lds ? sizeof(uint64_t) * sortcap : 0;
     if (rank_ok && rank_lds_bytes(sortcap) > lds) lds = rank_lds_bytes(sortcap);
+    // eight equal id ranges: high word of id * floor(8 * 2^32 / n_ids); ids are below n_ids (2^32 when unknown)
+    const uint64_t n = n_ids ? n_ids : (1ull << 32);
+    const uint64_t mul64 = (8ull << 32) / n;
+    const uint32_t id_mul = mul64 > 0xFFFFFFFFull ? 0xFFFFFFFFu : static_cast<uint32_t>(mul64);
     DCPQ_LAUNCH(kStageSelect, st, fast_select_kernel, dim3(nq), dim3(1024), lds,
-                keys, count, chist, r, nslices, cap, sortcap, use_lds, rank_ok, spill, cand_id, cand_qd, flags);
+                keys, count, chist, r, nslices, cap, sortcap, use_lds, rank_ok, id_mul, spill, cand_id, cand_qd, flags);
     DCPQ_CHECK_LAUNCH("fast_select_kernel");
     return DCPQ_OK;
 }
