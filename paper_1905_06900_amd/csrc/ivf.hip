@@ -8,10 +8,12 @@
 //                               query -- qmin over all its lists' tables, qmax over the first
 //                               min(r, total) codes met walking its lists in probe order -- so that
 //                               integer distances from different lists are comparable
-//   Scan    ivf_scan            the r smallest (qd, id) over the union of the probed lists: the
-//                               three-pass selection of scan.hip over a per-query list of "units"
-//                               (runs of codes inside one list, in increasing id order), one
-//                               wavefront per unit with that (query, list)'s 8-bit tables in LDS
+//   Scan    ivf_scan            the r smallest (qd, id) over the union of the probed lists, over a
+//                               per-query list of "units" (runs of codes inside one list, in
+//                               increasing id order), one wavefront per unit with that (query,
+//                               list)'s 8-bit tables in LDS: one streaming pass with a running
+//                               bucket bound and an exact selection (as in scan_fast.hip), the
+//                               three-pass selection of scan.hip for the queries it flags
 //   Refine  ivf_refine_topk     Eq. 3 on the residual of each candidate's own list, directly from
 //                               the full codebooks in double precision (per-list 2^16-entry tables
 //                               would cost nprobe table builds per query), then the k best
