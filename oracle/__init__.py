@@ -207,3 +207,69 @@ def search_ivf(C_full, Cbar, codes, offsets, coarse, queries, probe, r: int, k: 
     if rc != 0:
         raise ValueError("dcpq_oracle_search_ivf failed: %d" % rc)
     return out
+
+
+# ---- training (Alg. 2) and encoding ---------------------------------------------------------------
+
+def assign(X, Cb, want_dist: bool = False):
+    """Nearest centroid of every row of X ([n][d], may be a strided view of a wider array) in Cb ([k][d])."""
+    Cb = _f32(Cb)
+    X = np.asarray(X, dtype=np.float32)
+    assert X.ndim == 2 and X.strides[1] == 4 and X.strides[0] % 4 == 0
+    n, d = X.shape
+    label = np.empty(n, np.uint32)
+    dist = np.empty(n, np.float64) if want_dist else None
+    lib().dcpq_oracle_assign(C.c_void_p(X.ctypes.data), C.c_uint64(n), d, X.strides[0] // 4, _p(Cb), Cb.shape[0],
+                             _p(label), _p(dist))
+    return (label, dist) if want_dist else label
+
+
+def kmeans(X, C_init, iters: int):
+    """Alg. 2 step 1 from given initial centroids -> (centroids [k][d], labels [n])."""
+    X = _f32(X); Cb = _f32(C_init).copy()
+    n, d = X.shape
+    label = np.empty(n, np.uint32)
+    lib().dcpq_oracle_kmeans(_p(X), C.c_uint64(n), d, d, Cb.shape[0], iters, _p(Cb), _p(label))
+    return Cb, label
+
+
+def balanced_assign(D):
+    """[n][kbar] fp32 distances -> (labels [n] with n / kbar members per cluster, rounds)."""
+    D = _f32(D)
+    n, kbar = D.shape
+    label = np.empty(n, np.uint32)
+    rounds = lib().dcpq_oracle_balanced_assign(_p(D), n, kbar, _p(label))
+    if rounds < 0:
+        raise ValueError("balanced_assign: n must be a positive multiple of kbar")
+    return label, rounds
+
+
+def kmeans_same_size(P, Cbar_init, iters: int):
+    """Alg. 2 step 2 -> (centroids [kbar][d] = means of the groups, labels [n])."""
+    P = _f32(P); Cbar = _f32(Cbar_init).copy()
+    n, d = P.shape
+    label = np.empty(n, np.uint32)
+    if lib().dcpq_oracle_kmeans_same_size(_p(P), n, d, Cbar.shape[0], iters, _p(Cbar), _p(label)) != 0:
+        raise ValueError("kmeans_same_size: bad sizes")
+    return Cbar, label
+
+
+def build_final_codebook(Ct, label, bbar: int):
+    """Alg. 2 step 3 -> (final codebook [k][d], perm [k] with perm[final index] = temporary index)."""
+    Ct = _f32(Ct); label = np.ascontiguousarray(label, np.uint32)
+    k, d = Ct.shape
+    Cf = np.empty_like(Ct); perm = np.empty(k, np.uint32)
+    if lib().dcpq_oracle_build_final_codebook(_p(Ct), k, d, _p(label), bbar, _p(Cf), _p(perm)) != 0:
+        raise ValueError("build_final_codebook: groups are not of equal size")
+    return Cf, perm
+
+
+def encode(X, C_full):
+    """[n][m*dsub] vectors -> [n][m] uint16 codes (nearest centroid per sub-vector)."""
+    X = _f32(X); C_full = _f32(C_full)
+    m, kc, dsub = C_full.shape
+    n = X.shape[0]
+    assert X.shape[1] == m * dsub
+    codes = np.empty((n, m), np.uint16)
+    lib().dcpq_oracle_encode(_p(X), C.c_uint64(n), _p(C_full), m, kc, dsub, _p(codes))
+    return codes

@@ -20,8 +20,10 @@
  *   - Ties are always broken by the smaller id.
  *
  * Parity pins: every function below is pinned by tests/test_oracle_*.py (brute force in
- * numpy/fractions, closed forms, the paper's printed index example, and the reduction of the
- * two-pass search to exhaustive 16-bit ADC when r = N).  Unpinned: none of the paper's
+ * numpy/fractions, closed forms, the paper's printed index example, the reduction of the
+ * two-pass search to exhaustive 16-bit ADC when r = N; for the training functions at the end
+ * of the file also scikit-learn's Lloyd iteration, a hand-worked balanced assignment and the
+ * invariants of Alg. 2).  Unpinned: none of the paper's
  * recall or latency figures (its datasets and trained codebooks are not available).
  */
 #include <math.h>
@@ -446,4 +448,178 @@ int dcpq_oracle_num_threads(void)
 #else
     return 1;
 #endif
+}
+
+/* ==========================================================================================
+ * Training (Sec. 3.2, Alg. 2: build_quantizers) and encoding (Sec. 3.2, last paragraph).
+ *
+ * The paper names its three steps and leaves their insides to "a standard implementation of
+ * k-means" and to a same-size k-means variant it cites; the readings taken here:
+ *   - distances are double precision from the fp32 inputs, components added in increasing
+ *     order; the nearest centroid is the one with the smallest (distance, index);
+ *   - a k-means iteration is: assign every point, then replace each centroid by the mean of
+ *     its members (double precision sum in increasing point order, one division, rounded to
+ *     fp32); a centroid without members keeps its value; the initial centroids are an input;
+ *     after the last iteration the points are assigned once more, to the final centroids;
+ *   - same-size k-means: an iteration assigns the points to clusters of exactly n / kbar
+ *     members each (balanced assignment, below) and then takes the means as above; the
+ *     labels returned are those of the last assignment, so that the returned centroids are
+ *     the means of the returned groups (Sec. 3.2, step 2);
+ *   - balanced assignment, in rounds: every point without a cluster proposes to the cluster
+ *     with the smallest (distance, index) among those that still have room; every cluster
+ *     takes, among its proposers, the ones with the smallest (distance, point) up to the room
+ *     it has; repeat until no point is left.  Distances are rounded to fp32 first (they are
+ *     compared as fp32 by the GPU library, which reads them from a table of floats).
+ * ======================================================================================== */
+
+/* squared distance between an fp32 point and an fp32 centroid, double precision */
+static double dist2_f64(const float *x, const float *c, int d)
+{
+    double acc = 0.0;
+    for (int t = 0; t < d; ++t) {
+        const double diff = (double)x[t] - (double)c[t];
+        acc += diff * diff;
+    }
+    return acc;
+}
+
+/* X : n rows of d floats, row stride ld floats.   C : [k][d].   label : [n]   dist2 : [n] or NULL */
+void dcpq_oracle_assign(const float *X, uint64_t n, int d, int ld, const float *C, int k, uint32_t *label,
+                        double *dist2)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < (int64_t)n; ++i) {
+        double best = INFINITY;
+        uint32_t arg = 0;
+        for (int c = 0; c < k; ++c) {
+            const double dd = dist2_f64(X + (size_t)i * ld, C + (size_t)c * d, d);
+            if (dd < best) { best = dd; arg = (uint32_t)c; }      /* strict: the smaller index wins a tie */
+        }
+        label[i] = arg;
+        if (dist2) dist2[i] = best;
+    }
+}
+
+/* means of the members of every cluster; a cluster without members keeps its centroid */
+static void update_means(const float *X, uint64_t n, int d, int ld, const uint32_t *label, int k, float *C)
+{
+    double *sum = (double *)calloc((size_t)k * d, sizeof(double));
+    uint64_t *cnt = (uint64_t *)calloc((size_t)k, sizeof(uint64_t));
+    for (uint64_t i = 0; i < n; ++i) {
+        const uint32_t c = label[i];
+        cnt[c] += 1;
+        for (int t = 0; t < d; ++t) sum[(size_t)c * d + t] += (double)X[(size_t)i * ld + t];
+    }
+    for (int c = 0; c < k; ++c)
+        if (cnt[c])
+            for (int t = 0; t < d; ++t) C[(size_t)c * d + t] = (float)(sum[(size_t)c * d + t] / (double)cnt[c]);
+    free(sum); free(cnt);
+}
+
+/* Alg. 2 step 1.  C : [k][d], initial centroids in, final centroids out.  label : [n] out. */
+void dcpq_oracle_kmeans(const float *X, uint64_t n, int d, int ld, int k, int iters, float *C, uint32_t *label)
+{
+    for (int it = 0; it < iters; ++it) {
+        dcpq_oracle_assign(X, n, d, ld, C, k, label, NULL);
+        update_means(X, n, d, ld, label, k, C);
+    }
+    dcpq_oracle_assign(X, n, d, ld, C, k, label, NULL);
+}
+
+typedef struct { float d; uint32_t i; } prop_t;
+static int prop_cmp(const void *a, const void *b)
+{
+    const prop_t *x = (const prop_t *)a, *y = (const prop_t *)b;
+    if (x->d < y->d) return -1;
+    if (x->d > y->d) return 1;
+    return x->i < y->i ? -1 : (x->i > y->i ? 1 : 0);
+}
+
+/* Balanced assignment of n points to kbar clusters of n / kbar members each (n % kbar == 0).
+ * D : [n][kbar] fp32 distances.  label : [n] out.  Returns the number of rounds, -1 on bad sizes. */
+int dcpq_oracle_balanced_assign(const float *D, int n, int kbar, uint32_t *label)
+{
+    if (kbar <= 0 || n <= 0 || n % kbar) return -1;
+    int *room = (int *)malloc(sizeof(int) * kbar);
+    int *prop = (int *)malloc(sizeof(int) * n);
+    prop_t *list = (prop_t *)malloc(sizeof(prop_t) * n);
+    for (int l = 0; l < kbar; ++l) room[l] = n / kbar;
+    for (int i = 0; i < n; ++i) label[i] = 0xFFFFFFFFu;
+    int left = n, rounds = 0;
+    while (left > 0) {
+        ++rounds;
+        for (int i = 0; i < n; ++i) {
+            prop[i] = -1;
+            if (label[i] != 0xFFFFFFFFu) continue;
+            float best = INFINITY;
+            for (int l = 0; l < kbar; ++l)
+                if (room[l] > 0 && (prop[i] < 0 || D[(size_t)i * kbar + l] < best)) { best = D[(size_t)i * kbar + l]; prop[i] = l; }
+        }
+        for (int l = 0; l < kbar; ++l) {
+            if (room[l] == 0) continue;
+            int p = 0;
+            for (int i = 0; i < n; ++i)
+                if (prop[i] == l) { list[p].d = D[(size_t)i * kbar + l]; list[p].i = (uint32_t)i; ++p; }
+            qsort(list, (size_t)p, sizeof(prop_t), prop_cmp);
+            const int take = p < room[l] ? p : room[l];
+            for (int t = 0; t < take; ++t) label[list[t].i] = (uint32_t)l;
+            room[l] -= take;
+            left -= take;
+        }
+    }
+    free(room); free(prop); free(list);
+    return rounds;
+}
+
+/* Alg. 2 step 2.  P : [n][d] (the centroids of the temporary codebook), Cbar : [kbar][d] initial in, final out.
+ * label : [n] out, the groups whose means Cbar holds.  Returns 0, -1 on bad sizes. */
+int dcpq_oracle_kmeans_same_size(const float *P, int n, int d, int kbar, int iters, float *Cbar, uint32_t *label)
+{
+    if (kbar <= 0 || n <= 0 || n % kbar || iters < 1) return -1;
+    float *D = (float *)malloc(sizeof(float) * (size_t)n * kbar);
+    for (int it = 0; it < iters; ++it) {
+        for (int i = 0; i < n; ++i)
+            for (int l = 0; l < kbar; ++l)
+                D[(size_t)i * kbar + l] = (float)dist2_f64(P + (size_t)i * d, Cbar + (size_t)l * d, d);
+        dcpq_oracle_balanced_assign(D, n, kbar, label);
+        update_means(P, (uint64_t)n, d, d, label, kbar, Cbar);
+    }
+    free(D);
+    return 0;
+}
+
+/* Alg. 2 step 3 (build_final_codebook): the members of group l, taken in increasing index of the
+ * temporary codebook, get the final indices (0 << bbar) | l, (1 << bbar) | l, ... (property P1).
+ * Ct : [k][d] temporary codebook, label : [k] group of each of its centroids (2^bbar groups of equal size).
+ * Cf : [k][d] final codebook out, perm : [k] out, perm[final index] = temporary index.  Returns 0, -1 if
+ * the groups are not of equal size. */
+int dcpq_oracle_build_final_codebook(const float *Ct, int k, int d, const uint32_t *label, int bbar, float *Cf,
+                                     uint32_t *perm)
+{
+    const int kbar = 1 << bbar;
+    if (k % kbar) return -1;
+    int *seen = (int *)calloc((size_t)kbar, sizeof(int));
+    int rc = 0;
+    for (int i = 0; i < k && !rc; ++i) {
+        const uint32_t l = label[i];
+        if (l >= (uint32_t)kbar || seen[l] >= k / kbar) { rc = -1; break; }
+        const uint32_t f = ((uint32_t)seen[l] << bbar) | l;
+        seen[l] += 1;
+        perm[f] = (uint32_t)i;
+        memcpy(Cf + (size_t)f * d, Ct + (size_t)i * d, sizeof(float) * d);
+    }
+    free(seen);
+    return rc;
+}
+
+/* Encoding: sub-code j of vector i = index of the centroid of C_j nearest to the j-th sub-vector.
+ * X : [n][m*dsub]   C : [m][kc][dsub]   codes : [n][m] */
+void dcpq_oracle_encode(const float *X, uint64_t n, const float *C, int m, int kc, int dsub, uint16_t *codes)
+{
+    uint32_t *lab = (uint32_t *)malloc(sizeof(uint32_t) * n);
+    for (int j = 0; j < m; ++j) {
+        dcpq_oracle_assign(X + (size_t)j * dsub, n, dsub, m * dsub, C + (size_t)j * kc * dsub, kc, lab, NULL);
+        for (uint64_t i = 0; i < n; ++i) codes[i * m + j] = (uint16_t)lab[i];
+    }
+    free(lab);
 }
