@@ -254,6 +254,57 @@ int dcpq_plain_search(const float *tables, uint32_t n_entries, const void *codes
                       uint64_t n_codes, int m, int nq, uint32_t k, uint32_t *ids, float *dist,
                       void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Training and encoding -- Sec. 3.2, Alg. 2 (build_quantizers) and the encoding rule of the last
+ * paragraph of Sec. 3.2.  The paper names the steps and leaves their insides to standard algorithms;
+ * what these calls compute:
+ *   nearest centroid    the smallest (squared distance, index), distances in double precision from
+ *                       the fp32 inputs (matrix cores);
+ *   k-means (step 1)    `iters` times { assign every point; centroid = mean of its members, double
+ *                       precision sums rounded to fp32 once; a centroid without members keeps its
+ *                       value }, then one more assignment; the initial centroids are an input;
+ *   same-size k-means   (step 2) `iters` times { balanced assignment into groups of exactly n / kbar
+ *                       points; means }; the labels are those of the last assignment, whose means
+ *                       the centroids are.  Balanced assignment, in rounds: every point without a
+ *                       group proposes to the group with the smallest (distance, index) among those
+ *                       with room, every group keeps the proposers with the smallest (distance,
+ *                       point) up to its room, until no point is left; distances as fp32;
+ *   final codebook      (step 3) the members of group l in increasing temporary index get the final
+ *                       indices (0 << bbar) | l, (1 << bbar) | l, ...  (property P1).
+ * dcpq_kmeans_same_size (and dcpq_build_quantizers, which calls it) reads a counter back after every
+ * round and so SYNCHRONIZES the stream; the other calls only enqueue.  Workspaces 256-byte aligned.
+ *
+ *   dcpq_assign   points: n rows of ld floats, sub-vector j in columns j*dsub .. (j+1)*dsub-1;
+ *                 codebooks [m][n_entries][dsub]; labels [n][m] of label_bytes (1, 2 or 4) each;
+ *                 dist (NULL or float [n][m]): squared distance to the chosen centroid.
+ *   dcpq_encode   = dcpq_assign on [n][m*dsub] vectors with 2^b centroids, codes of b/8 bytes per sub-code.
+ *   dcpq_kmeans   points as above with one sub-vector (ld >= d); centroids float [k][d] in/out; labels uint32 [n].
+ *   dcpq_kmeans_same_size   points float [n][d] (the temporary codebook), n a multiple of kbar <= 256;
+ *                 centroids float [kbar][d] in/out; labels uint32 [n].
+ *   dcpq_build_final_codebook   temp/final float [k][d] (distinct), labels uint32 [k] with groups of equal
+ *                 size (not checked), perm uint32 [k]: perm[final index] = temporary index.
+ *   dcpq_build_quantizers   all of Alg. 2 for m sub-quantizers: train float [n_train][m*dsub]; codebooks
+ *                 float [m][2^b][dsub] hold the INITIAL centroids on entry and the final codebooks on
+ *                 return; step 2 starts from the first 2^bbar temporary centroids; derived float
+ *                 [m][2^bbar][dsub] = dcpq_derive_codebooks_bits of the result.
+ * ------------------------------------------------------------------------------------------- */
+int dcpq_assign(const float *points, uint64_t n, int ld, const float *codebooks, int m, int dsub, int n_entries,
+                void *labels, int label_bytes, float *dist, void *stream);
+int dcpq_encode(const float *vectors, uint64_t n, const float *codebooks, int m, int dsub, int b, void *codes,
+                void *stream);
+size_t dcpq_kmeans_workspace_bytes(int k, int d);
+int dcpq_kmeans(const float *points, uint64_t n, int ld, int d, int k, int iters, float *centroids,
+                uint32_t *labels, void *workspace, size_t workspace_bytes, void *stream);
+size_t dcpq_kmeans_same_size_workspace_bytes(int n, int d, int kbar);
+int dcpq_kmeans_same_size(const float *points, int n, int d, int kbar, int iters, float *centroids,
+                          uint32_t *labels, void *workspace, size_t workspace_bytes, void *stream);
+int dcpq_build_final_codebook(const float *temp_codebook, int k, int d, const uint32_t *labels, int bbar,
+                              float *final_codebook, uint32_t *perm, void *stream);
+size_t dcpq_build_quantizers_workspace_bytes(uint64_t n_train, int dsub, int b, int bbar);
+int dcpq_build_quantizers(const float *train, uint64_t n_train, int m, int dsub, int b, int bbar, int iters,
+                          int iters_same_size, float *codebooks, float *derived, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
 /* =============================================================================================
  * Inverted-index variant (Sec. 2.2: inverted lists with residual encoding; Sec. 2.3: the Index step,
  * and every later step done once per probed list; Sec. 3.3 with derived codebooks).

@@ -43,6 +43,15 @@ _SIGNATURES = {
     "dcpq_search_bits": (_i, [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp, _u64, _u32, _u32, _i, _vp, _vp, _i, _vp, _sz, _vp]),
     "dcpq_search_refine_mode": (_i, [_i, _i, _u32, _i]),
     "dcpq_refine_direct_topk": (_i, [_vp, _vp, _i, _i, _i, _vp, _u64, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_assign": (_i, [_vp, _u64, _i, _vp, _i, _i, _i, _vp, _i, _vp, _vp]),
+    "dcpq_encode": (_i, [_vp, _u64, _vp, _i, _i, _i, _vp, _vp]),
+    "dcpq_kmeans_workspace_bytes": (_sz, [_i, _i]),
+    "dcpq_kmeans": (_i, [_vp, _u64, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_kmeans_same_size_workspace_bytes": (_sz, [_i, _i, _i]),
+    "dcpq_kmeans_same_size": (_i, [_vp, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
+    "dcpq_build_final_codebook": (_i, [_vp, _i, _i, _vp, _i, _vp, _vp, _vp]),
+    "dcpq_build_quantizers_workspace_bytes": (_sz, [_u64, _i, _i, _i]),
+    "dcpq_build_quantizers": (_i, [_vp, _u64, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_build_tables": (_i, [_vp, _i, _vp, _i, _i, _vp, _vp]),
     "dcpq_build_tables_n": (_i, [_vp, _i, _vp, _i, _i, _i, _vp, _vp]),
     "dcpq_plain_workspace_bytes": (_sz, [_u64, _i, _u32]),
@@ -366,6 +375,81 @@ def search(queries: torch.Tensor, codebooks: torch.Tensor, derived: torch.Tensor
                                       m, dsub, b, bbar, _dev(codes, codes.dtype, "codes"), n, r, k, refine_mode,
                                       ids.data_ptr(), dist.data_ptr(), chunk_queries, workspace.data_ptr(), workspace.numel(), _stream()))
     return ids, dist
+
+
+# ---- training and encoding (Alg. 2) ------------------------------------------------------------
+
+def assign(points: torch.Tensor, codebooks: torch.Tensor, want_dist: bool = False, label_dtype=torch.int32):
+    """Nearest centroid per sub-vector: points [n][m*dsub], codebooks [m][n_entries][dsub] -> labels [n][m]"""
+    m, ne, dsub = codebooks.shape
+    n = points.shape[0]
+    assert points.shape[1] == m * dsub
+    labels = torch.empty((n, m), dtype=label_dtype, device=points.device)
+    dist = torch.empty((n, m), dtype=torch.float32, device=points.device) if want_dist else None
+    _check(lib().dcpq_assign(_dev(points, torch.float32, "points"), n, m * dsub, _dev(codebooks, torch.float32, "codebooks"),
+                             m, dsub, ne, labels.data_ptr(), labels.element_size(),
+                             dist.data_ptr() if dist is not None else None, _stream()))
+    return (labels, dist) if want_dist else labels
+
+
+def encode(vectors: torch.Tensor, codebooks: torch.Tensor) -> torch.Tensor:
+    """[n][m*dsub] vectors -> [n][m] codes (uint16 for 2^16 centroids, uint8 for 2^8)"""
+    m, kf, dsub = codebooks.shape
+    b = _bits_of(kf)
+    n = vectors.shape[0]
+    codes = torch.empty((n, m), dtype=torch.uint16 if b == 16 else torch.uint8, device=vectors.device)
+    _check(lib().dcpq_encode(_dev(vectors, torch.float32, "vectors"), n, _dev(codebooks, torch.float32, "codebooks"),
+                             m, dsub, b, codes.data_ptr(), _stream()))
+    return codes
+
+
+def kmeans(points: torch.Tensor, init: torch.Tensor, iters: int):
+    """Alg. 2 step 1 from given initial centroids -> (centroids [k][d], labels int32 [n])"""
+    n, d = points.shape
+    k = init.shape[0]
+    cent = init.clone()
+    labels = torch.empty(n, dtype=torch.int32, device=points.device)
+    ws = _workspace(lib().dcpq_kmeans_workspace_bytes(k, d), points.device)
+    _check(lib().dcpq_kmeans(_dev(points, torch.float32, "points"), n, d, d, k, iters, _dev(cent, torch.float32, "centroids"),
+                             labels.data_ptr(), ws.data_ptr(), ws.numel(), _stream()))
+    return cent, labels
+
+
+def kmeans_same_size(points: torch.Tensor, init: torch.Tensor, iters: int):
+    """Alg. 2 step 2 -> (centroids [kbar][d] = means of the groups, labels int32 [n]); synchronizes"""
+    n, d = points.shape
+    kbar = init.shape[0]
+    cent = init.clone()
+    labels = torch.empty(n, dtype=torch.int32, device=points.device)
+    ws = _workspace(lib().dcpq_kmeans_same_size_workspace_bytes(n, d, kbar), points.device)
+    _check(lib().dcpq_kmeans_same_size(_dev(points, torch.float32, "points"), n, d, kbar, iters,
+                                       _dev(cent, torch.float32, "centroids"), labels.data_ptr(), ws.data_ptr(), ws.numel(),
+                                       _stream()))
+    return cent, labels
+
+
+def build_final_codebook(temp: torch.Tensor, labels: torch.Tensor, bbar: int):
+    """Alg. 2 step 3 -> (final codebook [k][d], perm int32 [k], perm[final index] = temporary index)"""
+    k, d = temp.shape
+    final = torch.empty_like(temp)
+    perm = torch.empty(k, dtype=torch.int32, device=temp.device)
+    _check(lib().dcpq_build_final_codebook(_dev(temp, torch.float32, "temp"), k, d, _dev(labels, torch.int32, "labels"), bbar,
+                                           final.data_ptr(), perm.data_ptr(), _stream()))
+    return final, perm
+
+
+def build_quantizers(train: torch.Tensor, init_codebooks: torch.Tensor, bbar: int, iters: int, iters_same_size: int):
+    """All of Alg. 2: train [n][m*dsub], init_codebooks [m][2^b][dsub] -> (codebooks, derived [m][2^bbar][dsub])"""
+    m, kf, dsub = init_codebooks.shape
+    b = _bits_of(kf)
+    n = train.shape[0]
+    cb = init_codebooks.clone()
+    derived = torch.empty((m, 1 << bbar, dsub), dtype=torch.float32, device=train.device)
+    ws = _workspace(lib().dcpq_build_quantizers_workspace_bytes(n, dsub, b, bbar), train.device)
+    _check(lib().dcpq_build_quantizers(_dev(train, torch.float32, "train"), n, m, dsub, b, bbar, iters, iters_same_size,
+                                       _dev(cb, torch.float32, "codebooks"), derived.data_ptr(), ws.data_ptr(), ws.numel(),
+                                       _stream()))
+    return cb, derived
 
 
 def stream_read_gbs(t: torch.Tensor, reps: int = 3) -> float:

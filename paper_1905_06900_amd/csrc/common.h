@@ -47,7 +47,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 enum Stage {
     kStageSmallTables = 0, kStageScanHist, kStageScanTieCount, kStageScanCollect, kStageScanFast,
     kStageSelect, kStageFullTables, kStageRefine, kStageIvf, kStageMisc,
-    kStageIvfProbe, kStageIvfTables, kStageIvfScan, kStageIvfRefine, kStagePlainScan, kNumStages
+    kStageIvfProbe, kStageIvfTables, kStageIvfScan, kStageIvfRefine, kStagePlainScan, kStageTrain, kNumStages
 };
 namespace prof {
 bool enabled();

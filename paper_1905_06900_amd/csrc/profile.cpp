@@ -13,7 +13,7 @@ static const char *const kNames[kNumStages] = {
     "small_tables", "scan_hist", "scan_tiecount", "scan_collect", "scan_fast", "select",
     "full_tables",
     "refine_topk", "ivf", "misc",
-    "ivf_probe", "ivf_tables", "ivf_scan", "ivf_refine", "plain_scan",
+    "ivf_probe", "ivf_tables", "ivf_scan", "ivf_refine", "plain_scan", "train",
 };
 
 struct Pending { int stage; hipEvent_t a, b; };
