@@ -185,6 +185,25 @@ def test_scan_giant_ties_and_saturation():
     scan_vs_oracle(codes, qtab, r)
 
 
+def test_scan_selection_with_one_large_group_of_equal_candidates():
+    # 2500 identical codes in the first stretch of the array share qd = 0: one (bucket, id range) group of the
+    # selection exceeds what it ranks by counting, so the query is ordered by the sorting network instead;
+    # a second query has the same run spread over the whole array (small groups)
+    rng = np.random.default_rng(2024)
+    N, r = 200_000, 3000
+    codes = rng.integers(0, 65536, size=(N, 8)).astype(np.uint16)
+    qtab = rng.integers(10, 58, size=(2, 8, 256)).astype(np.uint8)
+    same = np.array([3, 300, 77, 1025, 9, 4242, 513, 65535], np.uint16)
+    qtab[:, np.arange(8), same & 255] = 0
+    codes[100:2600] = same
+    print("scan with a large group of equal candidates", flush=True)
+    scan_vs_oracle(codes, qtab, r)
+    codes2 = codes.copy()
+    codes2[100:2600] = rng.integers(0, 65536, size=(2500, 8)).astype(np.uint16)
+    codes2[rng.permutation(N)[:2500]] = same
+    scan_vs_oracle(codes2, qtab[1:], r)
+
+
 def test_small_tables_edges_degenerate_range_and_r_beyond_n():
     rng = np.random.default_rng(5)
     m, dsub = 8, 16
