@@ -27,15 +27,21 @@ METRIC = "queries/sec at k=100 + scan GB/s vs HBM peak (PQ 8x16, N=100M, 1 GPU)"
 
 
 def timed(step, steps, warmup, binding, torch):
+    """W warm-up steps, then exactly K timed steps between synchronizations (-> elapsed); then the same K steps
+    once more with the library's per-stage HIP events switched on (-> stage times: the events cost a few
+    microseconds per kernel, which the timed steps should not carry)."""
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
-    binding.profile_enable(True)
     t0 = time.perf_counter()
     for _ in range(steps):
         step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    binding.profile_enable(True)
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
     stages = binding.profile_read()
     binding.profile_enable(False)
     return elapsed, stages
@@ -174,6 +180,27 @@ def run_flat(w, args, steps, warmup, with_cpu, headline):
                 "frac_of_stream_read": round(gbs / out["hbm_stream_read_gbs"], 4), "avg_launch_ms": round(ms_v, 4),
                 "bytes_per_launch": w.N * code_bytes, "traffic": committed_traffic("scan_fast_single_tile", w.name)}
             del ws_v, qtab_v
+
+    if ms_per_step < 5.0:
+        # a step this short is mostly launch latency (25 kernels); the calls are capture-safe, so a caller that
+        # repeats a shape can replay a graph: reported beside `value`, which stays the eager figure
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        reps = 20
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            graph.replay()
+        torch.cuda.synchronize()
+        out["graph_replay_ms_per_step"] = round((time.perf_counter() - t0) / reps * 1e3, 3)
+        del graph
 
     if args.compare:
         out["comparison"] = compare_plain(w, cb, codes, queries, ms_per_step, steps, warmup, binding, torch)

@@ -582,8 +582,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
 // The selection orders candidates by counting ranks inside small groups (the work grows with the
 // square of the group size); a query with a group larger than this goes through the bitonic network.
 constexpr uint32_t kRankGroup = 2048;
-constexpr int kSubBits = 3, kSub = 1 << kSubBits;      // id ranges per bucket
-constexpr uint32_t kGroups = 256 * kSub;
+constexpr int kRangeBits = 11;                          // finest split of the ids: 2048 equal ranges
+constexpr uint32_t kGroups = 2048;                      // (bucket, id range) groups the counting sort holds
 constexpr size_t kSelectLdsMost = 120 * 1024;
 
 // LDS of the rank-counting selection: group counters and group starts (uint32 each), then the ids
@@ -593,15 +593,16 @@ static size_t rank_lds_bytes(uint32_t sortcap) { return 8 * static_cast<size_t>(
 // One workgroup per query: pick the exact r smallest (qd, id) out of the appended superset.
 // flags[q] = 1 when the query must be redone (buffer overflow, fewer than r candidates, or more
 // candidates at or below the bound than the sort area holds).
-// The candidates at or below the bound are dealt into groups -- (bucket, one of 8 equal ranges of the
-// ids) -- by a counting sort: one pass over the buffer counts the groups, a prefix sum gives every group
+// The candidates at or below the bound are dealt into groups -- (bucket, one of 2^s equal ranges of the
+// ids, s as large as 2048 groups allow: 8 ranges when all 256 buckets are in play, 2048 when everything
+// ties in bucket 0) -- by a counting sort: one pass over the buffer counts the groups, a prefix sum gives every group
 // its place in the output (groups ordered by bucket, then by id range, are already in (qd, id) order),
 // a second pass deals the ids out, and inside a group a candidate's rank is the number of ids below its
 // own.  With r spread over tens of buckets and the ids spread over the array the groups hold a few
 // dozen ids, so this is several times cheaper than a sorting network over the whole set, which remains
 // for queries with a very large group (many equal qd in one stretch of ids).
-// id_mul: the id range of an id is the high word of id * id_mul (below 8 for every id of the array, and
-// non-decreasing in the id, which is all the order needs).
+// id_mul: the finest id range of an id is the high word of id * id_mul (below 2048 for every id of the
+// array, and non-decreasing in the id, which is all the order needs); coarser ranges are its top bits.
 __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__restrict__ keys,
                                                           const uint32_t *__restrict__ count,
                                                           const uint32_t *__restrict__ chist, uint32_t r, uint32_t nslices,
@@ -652,7 +653,10 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
         uint32_t *gstart = gcnt + kGroups;                                // [kGroups] first output position of the group
         uint32_t *ids = gstart + kGroups;                                 // [sortcap]
         uint16_t *grp = reinterpret_cast<uint16_t *>(ids + sortcap);      // [sortcap]
-        const uint32_t ngroups = (T + 1) * kSub;
+        int sub_bits = 0;
+        while (sub_bits < kRangeBits && ((T + 1) << (sub_bits + 1)) <= kGroups) ++sub_bits;
+        const int range_shift = kRangeBits - sub_bits;
+        const uint32_t ngroups = (T + 1) << sub_bits;
         for (uint32_t t = tid; t < ngroups; t += 1024) gcnt[t] = 0;
         __syncthreads();
         // count the groups: one wavefront per slice at a time, so that the slices' loads are in flight together
@@ -663,7 +667,7 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
             for (uint32_t t = lane; t < c; t += 64) {
                 const uint64_t key = keys[cell * cap + t];
                 const uint32_t qd = static_cast<uint32_t>(key >> 32);
-                if (qd <= T) atomicAdd(&gcnt[qd * kSub + __umulhi(static_cast<uint32_t>(key), id_mul)], 1u);
+                if (qd <= T) atomicAdd(&gcnt[(qd << sub_bits) + (__umulhi(static_cast<uint32_t>(key), id_mul) >> range_shift)], 1u);
             }
         }
         __syncthreads();
@@ -695,7 +699,7 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
                     const uint64_t key = keys[cell * cap + t];
                     const uint32_t qd = static_cast<uint32_t>(key >> 32);
                     if (qd <= T) {
-                        const uint32_t g = qd * kSub + __umulhi(static_cast<uint32_t>(key), id_mul);
+                        const uint32_t g = (qd << sub_bits) + (__umulhi(static_cast<uint32_t>(key), id_mul) >> range_shift);
                         const uint32_t pos = gstart[g] + atomicAdd(&gcnt[g], 1u);
                         if (pos < sortcap) { ids[pos] = static_cast<uint32_t>(key); grp[pos] = static_cast<uint16_t>(g); }
                     }
@@ -710,7 +714,7 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
                 const uint32_t out = lo + rank;
                 if (out < r) {
                     cand_id[static_cast<size_t>(q) * r + out] = id;
-                    cand_qd[static_cast<size_t>(q) * r + out] = static_cast<uint8_t>(g >> kSubBits);
+                    cand_qd[static_cast<size_t>(q) * r + out] = static_cast<uint8_t>(g >> sub_bits);
                 }
             }
             if (tid == 0) flags[q] = 0;
@@ -825,9 +829,9 @@ int launch_fast_select(const uint64_t *keys, const uint32_t *count, const uint32
     const int rank_ok = rank_lds_bytes(sortcap) <= kSelectLdsMost;
     size_t lds = use_lds ? sizeof(uint64_t) * sortcap : 0;
     if (rank_ok && rank_lds_bytes(sortcap) > lds) lds = rank_lds_bytes(sortcap);
-    // eight equal id ranges: high word of id * floor(8 * 2^32 / n_ids); ids are below n_ids (2^32 when unknown)
+    // 2048 equal id ranges: high word of id * floor(2048 * 2^32 / n_ids); ids are below n_ids (2^32 when unknown)
     const uint64_t n = n_ids ? n_ids : (1ull << 32);
-    const uint64_t mul64 = (8ull << 32) / n;
+    const uint64_t mul64 = (2048ull << 32) / n;
     const uint32_t id_mul = mul64 > 0xFFFFFFFFull ? 0xFFFFFFFFu : static_cast<uint32_t>(mul64);
     DCPQ_LAUNCH(kStageSelect, st, fast_select_kernel, dim3(nq), dim3(1024), lds,
                 keys, count, chist, r, nslices, cap, sortcap, use_lds, rank_ok, id_mul, spill, cand_id, cand_qd, flags);
