@@ -332,6 +332,10 @@ int dcpq_ivf_probe(const float *queries, int nq, int D, const float *coarse, int
  *   qtab : uint8_t [nq][nprobe][m][256] (output)   bounds : float [nq][2] (output)
  *   workspace : dcpq_ivf_tables_workspace_bytes(nq) */
 size_t dcpq_ivf_tables_workspace_bytes(int nq);
+/* Optional: with at least this much workspace dcpq_ivf_build_small_tables keeps the table entries of its
+ * first pass (float [nq][nprobe][m][256]) and quantizes them from memory instead of computing them twice;
+ * the results are the same bit for bit. */
+size_t dcpq_ivf_tables_workspace_bytes_fast(int nq, int nprobe, int m);
 int dcpq_ivf_build_small_tables(const float *queries, int nq, const float *coarse, int nlist,
                                 const int32_t *probe, int nprobe, const float *derived, int m, int dsub,
                                 const uint16_t *codes, const int64_t *offsets, uint32_t r, uint8_t *qtab,

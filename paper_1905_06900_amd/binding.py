@@ -71,6 +71,7 @@ _SIGNATURES = {
     "dcpq_ivf_probe_workspace_bytes": (_sz, [_i, _i]),
     "dcpq_ivf_probe": (_i, [_vp, _i, _i, _vp, _i, _i, _vp, _vp, _sz, _vp]),
     "dcpq_ivf_tables_workspace_bytes": (_sz, [_i]),
+    "dcpq_ivf_tables_workspace_bytes_fast": (_sz, [_i, _i, _i]),
     "dcpq_ivf_build_small_tables": (_i, [_vp, _i, _vp, _i, _vp, _i, _vp, _i, _i, _vp, _vp, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_ivf_scan_workspace_bytes": (_sz, [_i, _u32]),
     "dcpq_ivf_scan_candidates": (_i, [_vp, _vp, _i, _i, _vp, _i, _vp, _i, _u32, _vp, _vp, _vp, _vp, _sz, _vp]),
@@ -495,8 +496,9 @@ def ivf_probe(queries: torch.Tensor, coarse: torch.Tensor, nprobe: int) -> torch
     return probe
 
 
-def ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r: int):
-    """-> (qtab u8 [nq][nprobe][m][256], bounds f32 [nq][2])"""
+def ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r: int, keep_entries: bool = False):
+    """-> (qtab u8 [nq][nprobe][m][256], bounds f32 [nq][2]); keep_entries: give the call the workspace with which
+    it keeps the table entries between its two passes instead of computing them twice (same results)"""
     m, _, dsub = derived.shape
     nq, nprobe = probe.shape
     nlist = coarse.shape[0]
@@ -504,7 +506,8 @@ def ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r: i
     dev = queries.device
     qtab = torch.empty((nq, nprobe, m, 256), dtype=torch.uint8, device=dev)
     bounds = torch.empty((nq, 2), dtype=torch.float32, device=dev)
-    ws = _workspace(lib().dcpq_ivf_tables_workspace_bytes(nq), dev)
+    ws = _workspace(lib().dcpq_ivf_tables_workspace_bytes_fast(nq, nprobe, m) if keep_entries
+                    else lib().dcpq_ivf_tables_workspace_bytes(nq), dev)
     _check(lib().dcpq_ivf_build_small_tables(
         _dev(queries, torch.float32, "queries"), nq, _dev(coarse, torch.float32, "coarse"), nlist,
         _dev(probe, torch.int32, "probe"), nprobe, _dev(derived, torch.float32, "derived"), m, dsub,

@@ -97,7 +97,9 @@ int launch_refine(const float *tables, uint32_t table_size, const void *codes, i
                   const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids, float *dist, void *ws,
                   hipStream_t st);
 // the same with every table entry computed on demand from the codebooks (no tables)
-int launch_refine_direct(const float *queries, const float *codebooks, int dsub, uint32_t table_size, const void *codes,
+// codebooks: rows of dsub floats, cstride floats apart (16-byte aligned rows when dsub is a multiple of 4)
+int launch_pad_rows(const float *src, size_t nrows, int dsub, int cstride, float *dst, hipStream_t st);
+int launch_refine_direct(const float *queries, const float *codebooks, int dsub, int cstride, uint32_t table_size, const void *codes,
                          int code_bytes, uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k,
                          uint32_t *ids, float *dist, void *ws, hipStream_t st);
 

@@ -200,8 +200,10 @@ __global__ __launch_bounds__(256) void ivf_tables_kernel(const float *__restrict
                                                         const int32_t *__restrict__ probe, int nprobe,
                                                         const float *__restrict__ derived, int m, int dsub,
                                                         uint32_t *__restrict__ qmin_bits, const float *__restrict__ bounds,
-                                                        uint8_t *__restrict__ qtab)
+                                                        uint8_t *__restrict__ qtab, float *__restrict__ keep)
 {
+    // keep (MODE 0, optional): the entries themselves, [nq][nprobe][m][256], for the quantization to read back
+    // instead of computing them a second time
     extern __shared__ float lds[];         // rho [kIvfTabProbes][m*dsub]
     __shared__ float red[4];
     const int p0 = blockIdx.x * kIvfTabProbes, q = blockIdx.y, tid = threadIdx.x;
@@ -239,6 +241,7 @@ __global__ __launch_bounds__(256) void ivf_tables_kernel(const float *__restrict
             if (pp >= np) continue;                               // uniform
             if (MODE == 0) {
                 lo = fminf(lo, acc[pp]);
+                if (keep) keep[((static_cast<size_t>(q) * nprobe + p0 + pp) * m + j) * kSmallSize + tid] = acc[pp];
             } else {
                 qtab[((static_cast<size_t>(q) * nprobe + p0 + pp) * m + j) * kSmallSize + tid] =
                     quantize_entry(acc[pp], qmin, qmax);
@@ -249,6 +252,22 @@ __global__ __launch_bounds__(256) void ivf_tables_kernel(const float *__restrict
         lo = block_reduce(lo, false, red);
         if (tid == 0) atomicMin(&qmin_bits[q], __float_as_uint(lo));    // entries are >= +0
     }
+}
+
+// The quantization of entries kept by the first pass: qtab[e] = quantizer(keep[e]) with the bounds of the
+// entry's query (per_query = nprobe * m * 256 entries each).
+__global__ __launch_bounds__(256) void ivf_quantize_kept_kernel(const float *__restrict__ keep, size_t n, size_t per_query,
+                                                               const float *__restrict__ bounds, uint8_t *__restrict__ qtab)
+{
+    const size_t e = (static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x) * 4;
+    if (e >= n) return;                                         // n is a multiple of 256
+    const size_t q = e / per_query;
+    const float qmin = bounds[2 * q], qmax = bounds[2 * q + 1];
+    const float4 v = *reinterpret_cast<const float4 *>(keep + e);
+    uchar4 o;
+    o.x = quantize_entry(v.x, qmin, qmax); o.y = quantize_entry(v.y, qmin, qmax);
+    o.z = quantize_entry(v.z, qmin, qmax); o.w = quantize_entry(v.w, qmin, qmax);
+    *reinterpret_cast<uchar4 *>(qtab + e) = o;
 }
 
 // qmax: largest small-table distance over the first min(r, total) codes met walking the probed
@@ -870,6 +889,14 @@ extern "C" int dcpq_ivf_probe(const float *queries, int nq, int D, const float *
 
 extern "C" size_t dcpq_ivf_tables_workspace_bytes(int nq) { return nq > 0 ? align_up(sizeof(uint32_t) * static_cast<size_t>(nq), 256) : 0; }
 
+// With this much workspace (or more) dcpq_ivf_build_small_tables keeps the entries of its first pass and
+// quantizes them from memory instead of computing them twice.
+extern "C" size_t dcpq_ivf_tables_workspace_bytes_fast(int nq, int nprobe, int m)
+{
+    if (nq <= 0 || nprobe <= 0 || !m_supported(m)) return 0;
+    return dcpq_ivf_tables_workspace_bytes(nq) + align_up(sizeof(float) * static_cast<size_t>(nq) * nprobe * m * kSmallSize, 256);
+}
+
 extern "C" int dcpq_ivf_build_small_tables(const float *queries, int nq, const float *coarse, int nlist,
                                            const int32_t *probe, int nprobe, const float *derived, int m, int dsub,
                                            const uint16_t *codes, const int64_t *offsets, uint32_t r, uint8_t *qtab,
@@ -892,25 +919,32 @@ extern "C" int dcpq_ivf_build_small_tables(const float *queries, int nq, const f
     const size_t lds = sizeof(float) * static_cast<size_t>(kIvfTabProbes) * m * dsub;
     const dim3 tgrid((nprobe + kIvfTabProbes - 1) / kIvfTabProbes, nq);
     if (lds > 64 * 1024) {                  // LDS above 64 KiB must be requested per kernel (at most 128 KiB here)
-        static bool attr_done = false;
-        if (!attr_done) {
-            const int most = static_cast<int>(sizeof(float) * kIvfTabProbes * 32 * 128);
-            DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&ivf_tables_kernel<0>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, most));
-            DCPQ_CHECK_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&ivf_tables_kernel<1>),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, most));
-            attr_done = true;
-        }
+        const int most = static_cast<int>(sizeof(float) * kIvfTabProbes * 32 * 128);
+        rc = allow_dynamic_lds(reinterpret_cast<const void *>(&ivf_tables_kernel<0>), most);
+        if (rc) return rc;
+        rc = allow_dynamic_lds(reinterpret_cast<const void *>(&ivf_tables_kernel<1>), most);
+        if (rc) return rc;
     }
+    // with room for them, the entries are kept by the first pass and quantized from memory
+    const size_t n_entries = static_cast<size_t>(nq) * nprobe * m * kSmallSize;
+    float *keep = nullptr;
+    if (workspace_bytes >= dcpq_ivf_tables_workspace_bytes_fast(nq, nprobe, m))
+        keep = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + dcpq_ivf_tables_workspace_bytes(nq));
     DCPQ_LAUNCH(kStageIvfTables, st, ivf_tables_kernel<0>, tgrid, dim3(256), lds, queries, coarse, probe, nprobe,
-                derived, m, dsub, qmin_bits, bounds, qtab);
+                derived, m, dsub, qmin_bits, bounds, qtab, keep);
     DCPQ_CHECK_LAUNCH("ivf_tables_kernel<min>");
     DCPQ_LAUNCH(kStageIvfTables, st, ivf_qmax_kernel, dim3(nq), dim3(256), 0, queries, coarse, probe, nprobe, derived, m, dsub,
                 codes, offsets, r, qmin_bits, bounds);
     DCPQ_CHECK_LAUNCH("ivf_qmax_kernel");
-    DCPQ_LAUNCH(kStageIvfTables, st, ivf_tables_kernel<1>, tgrid, dim3(256), lds, queries, coarse, probe, nprobe,
-                derived, m, dsub, qmin_bits, bounds, qtab);
-    DCPQ_CHECK_LAUNCH("ivf_tables_kernel<quantize>");
+    if (keep) {
+        DCPQ_LAUNCH(kStageIvfTables, st, ivf_quantize_kept_kernel, dim3(static_cast<unsigned>((n_entries / 4 + 255) / 256)), dim3(256),
+                    0, keep, n_entries, static_cast<size_t>(nprobe) * m * kSmallSize, bounds, qtab);
+        DCPQ_CHECK_LAUNCH("ivf_quantize_kept_kernel");
+    } else {
+        DCPQ_LAUNCH(kStageIvfTables, st, ivf_tables_kernel<1>, tgrid, dim3(256), lds, queries, coarse, probe, nprobe,
+                    derived, m, dsub, qmin_bits, bounds, qtab, nullptr);
+        DCPQ_CHECK_LAUNCH("ivf_tables_kernel<quantize>");
+    }
     return DCPQ_OK;
 }
 
@@ -1065,7 +1099,10 @@ IvfSearchPlan plan_ivf_search(int nq, int nlist, int nprobe, int m, uint32_t r)
     p.off_count = off;   off = align_up(off + sizeof(uint32_t) * Q, 256);
     // the four steps run one after the other on the stream and share one scratch region
     size_t sub = dcpq_ivf_probe_workspace_bytes(nq, nlist);
-    const size_t others[] = {dcpq_ivf_tables_workspace_bytes(nq), dcpq_ivf_scan_workspace_bytes(nq, r),
+    // (the small-table entries are kept between the two table passes when that takes no more than 2 GiB)
+    const size_t keep_tables = dcpq_ivf_tables_workspace_bytes_fast(nq, nprobe, m);
+    const size_t others[] = {keep_tables <= (static_cast<size_t>(2) << 30) ? keep_tables : dcpq_ivf_tables_workspace_bytes(nq),
+                             dcpq_ivf_scan_workspace_bytes(nq, r),
                              dcpq_ivf_refine_workspace_bytes(nq, r)};
     for (size_t o : others) sub = o > sub ? o : sub;
     p.off_sub = off;     p.sub_bytes = align_up(sub, 256); off += p.sub_bytes;

@@ -27,14 +27,14 @@ static uint32_t next_pow2_r(uint32_t x)
 // DIRECT = false: `src` = the full tables [nq][M][table_size], an entry is looked up.
 // DIRECT = true:  `src` = the queries [nq][M * dsub]; an entry (Eq. 1: squared distance between the
 //   query's sub-vector and the centroid the sub-code names) is computed when a candidate asks for it,
-//   straight from the codebook `cb` [M][table_size][dsub] -- the refinement of Alg. 3 computes table
+//   straight from the codebook `cb` [M][table_size] rows of dsub floats, cstride floats apart -- the refinement of Alg. 3 computes table
 //   entries on demand because only a small part of a 2^16-entry table is ever used (Sec. 3.3,
 //   Refine step); here nothing is memoized, the entry is recomputed in double precision and rounded
 //   to fp32 once, which is what the tables hold.  Either way the distance is the fp32 sum of the M
 //   entries, j increasing.
 template <int M, typename CodeT, bool DIRECT>
 __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restrict__ src, uint32_t table_size,
-                                                          const float *__restrict__ cb, int dsub,
+                                                          const float *__restrict__ cb, int dsub, int cstride,
                                                           const CodeT *__restrict__ codes, uint32_t n_codes,
                                                           const uint32_t *__restrict__ cand_id, uint32_t r,
                                                           uint32_t k, uint32_t n_pow2, int use_lds,
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
             float e = 0.0f;
             if (id < n_codes) {                                          // pad slots (and anything out of range) sort last
                 const uint32_t cj = codes[static_cast<size_t>(id) * M + j];
-                const float *cen = cb + (static_cast<size_t>(j) * table_size + cj) * dsub;
+                const float *cen = cb + (static_cast<size_t>(j) * table_size + cj) * cstride;
                 double dj = 0.0;
                 if (vec4) {
 #pragma unroll 4
@@ -196,7 +196,7 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
 }
 
 template <int M, typename CodeT, bool DIRECT>
-static int launch_refine_m(const float *src, uint32_t table_size, const float *cb, int dsub, const CodeT *codes,
+static int launch_refine_m(const float *src, uint32_t table_size, const float *cb, int dsub, int cstride, const CodeT *codes,
                            uint64_t n_codes, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
                            float *dist, void *ws, hipStream_t st)
 {
@@ -206,20 +206,38 @@ static int launch_refine_m(const float *src, uint32_t table_size, const float *c
     const int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&refine_topk_kernel<M, CodeT, DIRECT>), static_cast<int>(lds));
     if (rc) return rc;
     DCPQ_LAUNCH(kStageRefine, st, (refine_topk_kernel<M, CodeT, DIRECT>), dim3(nq), dim3(1024), lds, src, table_size, cb, dsub,
-                codes, static_cast<uint32_t>(n_codes), cand_id, r, k, np2, use_lds, static_cast<uint64_t *>(ws), ids, dist);
+                cstride, codes, static_cast<uint32_t>(n_codes), cand_id, r, k, np2, use_lds, static_cast<uint64_t *>(ws), ids, dist);
     DCPQ_CHECK_LAUNCH("refine_topk_kernel");
     return DCPQ_OK;
 }
 
+// rows of dsub floats copied to rows cstride floats apart (the tail of a row is not written: it is never read)
+__global__ __launch_bounds__(256) void pad_rows_kernel(const float *__restrict__ src, size_t nrows, int dsub, int cstride,
+                                                       float *__restrict__ dst)
+{
+    const size_t e = static_cast<size_t>(blockIdx.x) * blockDim.x + threadIdx.x;
+    if (e >= nrows * dsub) return;
+    dst[(e / dsub) * cstride + e % dsub] = src[e];
+}
+
+int launch_pad_rows(const float *src, size_t nrows, int dsub, int cstride, float *dst, hipStream_t st)
+{
+    const size_t e = nrows * dsub;
+    DCPQ_LAUNCH(kStageRefine, st, pad_rows_kernel, dim3(static_cast<unsigned>((e + 255) / 256)), dim3(256), 0, src, nrows, dsub,
+                cstride, dst);
+    DCPQ_CHECK_LAUNCH("pad_rows_kernel");
+    return DCPQ_OK;
+}
+
 template <typename CodeT, bool DIRECT>
-static int launch_refine_t(const float *src, uint32_t table_size, const float *cb, int dsub, const CodeT *codes,
+static int launch_refine_t(const float *src, uint32_t table_size, const float *cb, int dsub, int cstride, const CodeT *codes,
                            uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
                            float *dist, void *ws, hipStream_t st)
 {
     if (nq == 0) return DCPQ_OK;
 #define DCPQ_LAUNCH_REFINE(MV)                                                                                      \
     case MV:                                                                                                        \
-        return launch_refine_m<MV, CodeT, DIRECT>(src, table_size, cb, dsub, codes, n_codes, cand_id, nq, r, k, ids, dist, ws, st);
+        return launch_refine_m<MV, CodeT, DIRECT>(src, table_size, cb, dsub, cstride, codes, n_codes, cand_id, nq, r, k, ids, dist, ws, st);
     switch (m) {
         DCPQ_LAUNCH_REFINE(1) DCPQ_LAUNCH_REFINE(2) DCPQ_LAUNCH_REFINE(4) DCPQ_LAUNCH_REFINE(8)
         DCPQ_LAUNCH_REFINE(16) DCPQ_LAUNCH_REFINE(32)
@@ -233,20 +251,20 @@ int launch_refine(const float *tables, uint32_t table_size, const void *codes, i
                   hipStream_t st)
 {
     if (code_bytes == 1)
-        return launch_refine_t<uint8_t, false>(tables, table_size, nullptr, 0, static_cast<const uint8_t *>(codes), n_codes, m,
+        return launch_refine_t<uint8_t, false>(tables, table_size, nullptr, 0, 0, static_cast<const uint8_t *>(codes), n_codes, m,
                                                cand_id, nq, r, k, ids, dist, ws, st);
-    return launch_refine_t<uint16_t, false>(tables, table_size, nullptr, 0, static_cast<const uint16_t *>(codes), n_codes, m,
+    return launch_refine_t<uint16_t, false>(tables, table_size, nullptr, 0, 0, static_cast<const uint16_t *>(codes), n_codes, m,
                                             cand_id, nq, r, k, ids, dist, ws, st);
 }
 
-int launch_refine_direct(const float *queries, const float *codebooks, int dsub, uint32_t table_size, const void *codes,
+int launch_refine_direct(const float *queries, const float *codebooks, int dsub, int cstride, uint32_t table_size, const void *codes,
                          int code_bytes, uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k,
                          uint32_t *ids, float *dist, void *ws, hipStream_t st)
 {
     if (code_bytes == 1)
-        return launch_refine_t<uint8_t, true>(queries, table_size, codebooks, dsub, static_cast<const uint8_t *>(codes), n_codes,
+        return launch_refine_t<uint8_t, true>(queries, table_size, codebooks, dsub, cstride, static_cast<const uint8_t *>(codes), n_codes,
                                               m, cand_id, nq, r, k, ids, dist, ws, st);
-    return launch_refine_t<uint16_t, true>(queries, table_size, codebooks, dsub, static_cast<const uint16_t *>(codes), n_codes, m,
+    return launch_refine_t<uint16_t, true>(queries, table_size, codebooks, dsub, cstride, static_cast<const uint16_t *>(codes), n_codes, m,
                                            cand_id, nq, r, k, ids, dist, ws, st);
 }
 
@@ -299,7 +317,7 @@ extern "C" int dcpq_refine_direct_topk(const float *queries, const float *codebo
     const size_t need = dcpq_refine_workspace_bytes(nq, r);
     if (need && (!workspace || workspace_bytes < need))
         return fail(DCPQ_EWORKSPACE, "refine_direct_topk: workspace %zu < %zu bytes", workspace_bytes, need);
-    return launch_refine_direct(queries, codebooks, dsub, 1u << b, codes, b / 8, n_codes, m, cand_id, nq, r, k, ids, dist,
+    return launch_refine_direct(queries, codebooks, dsub, dsub, 1u << b, codes, b / 8, n_codes, m, cand_id, nq, r, k, ids, dist,
                                 workspace, as_stream(stream));
 }
 

@@ -24,6 +24,9 @@ def run_ivf_case(d, nprobe, r, k, check_probe=True, plane=False, fused=False):
     low = binding.pack_low_bytes(codes) if plane else None
     probe = binding.ivf_probe(queries, coarse, nprobe)
     qtab, bounds = binding.ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r)
+    # the variant that keeps the entries between its passes gives the same bytes
+    qtab2, bounds2 = binding.ivf_build_small_tables(queries, coarse, probe, derived, codes, offsets, r, keep_entries=True)
+    assert torch.equal(qtab, qtab2) and torch.equal(bounds, bounds2)
     cand_id, cand_qd, count = binding.ivf_scan_candidates(low if plane else codes, offsets, probe, qtab, r)
     ids, dist = binding.ivf_refine_topk(queries, coarse, cb, codes, offsets, probe, cand_id, k)
     if fused:
