@@ -392,17 +392,17 @@ constexpr int kIvfAhead = 4;     // 64-code groups whose codes a wavefront loads
 // One wavefront per unit; grid (kIvfUnitsPerQuery / 4, nq), 256 threads.  The wavefront keeps the
 // 8-bit tables of its (query, list) in its own LDS slot and walks the unit 64 codes at a time.
 // CodeT: uint16_t (the codes as stored) or uint8_t (their low-byte plane).
+// One (query, unit) by one wavefront; nothing in it waits for another wavefront.
 template <int M, int MODE, typename CodeT>
-__global__ __launch_bounds__(256) void ivf_scan_kernel(const CodeT *__restrict__ codes, const IvfUnit *__restrict__ units,
-                                                      const uint32_t *__restrict__ nunits, const uint8_t *__restrict__ qtab,
-                                                      int nprobe, uint32_t r, uint32_t unit_step,
-                                                      const uint32_t *__restrict__ flags, uint32_t *__restrict__ hist,
-                                                      const uint32_t *__restrict__ thr, uint32_t *__restrict__ tie,
-                                                      uint32_t *__restrict__ counter, uint64_t *__restrict__ keys)
+__device__ inline void ivf_scan_unit(int q, const CodeT *__restrict__ codes, const IvfUnit *__restrict__ units,
+                                     const uint32_t *__restrict__ nunits, const uint8_t *__restrict__ qtab,
+                                     int nprobe, uint32_t r, uint32_t unit_step,
+                                     const uint32_t *__restrict__ flags, uint32_t *__restrict__ hist,
+                                     const uint32_t *__restrict__ thr, uint32_t *__restrict__ tie,
+                                     uint32_t *__restrict__ counter, uint64_t *__restrict__ keys)
 {
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int q = blockIdx.y;
     const uint32_t u = blockIdx.x * 4 + wave;
     uint8_t *tab = smem + wave * (M * 256);                                      // [M][256]
     uint32_t *lhist = reinterpret_cast<uint32_t *>(smem + 4 * M * 256) + wave * 256;   // kIvfHist only
@@ -417,7 +417,10 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const CodeT *__restrict__
         if (MODE == kIvfHist)
             for (int v = lane; v < 256; v += 64) lhist[v] = 0;
     }
-    __syncthreads();
+    // the tables are this wavefront's own: its lanes run in lockstep, the fences order the LDS accesses
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     if (!active) return;
 
     uint32_t T = 0, aux = 0;
@@ -488,6 +491,30 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const CodeT *__restrict__
         }
     } else if (MODE == kIvfTieCount) {
         if (lane == 0) tie[static_cast<size_t>(q) * kIvfUnitsPerQuery + u] = aux;
+    }
+}
+
+// Grid (kIvfUnitsPerQuery / 4, min(nq, kIvfRedoRows)): a wavefront takes the same unit number of every
+// kIvfRedoRows-th query.  With flags given only flagged queries are scanned, and since that is the rare case
+// (the three passes redo what the single pass could not finish) a row of workgroups serves many queries, so
+// that a launch with nothing to do costs a few thousand empty workgroups, not one per (query, 4 units).
+constexpr int kIvfRedoRows = 32;
+
+template <int M, int MODE, typename CodeT>
+__global__ __launch_bounds__(256) void ivf_scan_kernel(const CodeT *__restrict__ codes, const IvfUnit *__restrict__ units,
+                                                      const uint32_t *__restrict__ nunits, const uint8_t *__restrict__ qtab,
+                                                      int nprobe, int nq, uint32_t r, uint32_t unit_step,
+                                                      const uint32_t *__restrict__ flags, uint32_t *__restrict__ hist,
+                                                      const uint32_t *__restrict__ thr, uint32_t *__restrict__ tie,
+                                                      uint32_t *__restrict__ counter, uint64_t *__restrict__ keys)
+{
+    for (int q = blockIdx.y; q < nq; q += gridDim.y) {
+        if (flags && flags[q] == 0) continue;
+        ivf_scan_unit<M, MODE, CodeT>(q, codes, units, nunits, qtab, nprobe, r, unit_step, flags, hist, thr, tie, counter, keys);
+        // the next query's tables overwrite this one's: every lane is done with them
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 }
 
@@ -809,7 +836,7 @@ static int ivf_scan_m(const CodeT *codes, const int64_t *offsets, const int32_t 
     if (rc) return rc;
     DCPQ_LAUNCH(kStageIvf, st, ivf_plan_kernel, dim3(nq), dim3(256), 0, probe, nprobe, offsets, r, units, nunits, count);
     DCPQ_CHECK_LAUNCH("ivf_plan_kernel");
-    const dim3 grid(kIvfUnitsPerQuery / 4, nq);
+    const dim3 grid(kIvfUnitsPerQuery / 4, nq < kIvfRedoRows ? nq : kIvfRedoRows);
     const size_t lds_tab = 4 * M * 256;
     uint32_t *shist = reinterpret_cast<uint32_t *>(base + p.off_shist);
     uint32_t *fcount = reinterpret_cast<uint32_t *>(base + p.off_fcount);
@@ -832,17 +859,17 @@ static int ivf_scan_m(const CodeT *codes, const int64_t *offsets, const int32_t 
     if (rc) return rc;
     // the queries it flagged (a full slice, or fewer than r codes in the probed lists): three passes
     DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist, CodeT>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
-                nunits, qtab, nprobe, r, 1u, flags, hist, thr, tie, counter, keys);
+                nunits, qtab, nprobe, nq, r, 1u, flags, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<hist>");
     rc = launch_threshold(hist, nq, r, thr, st);
     if (rc) return rc;
     DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfTieCount, CodeT>), grid, dim3(256), lds_tab, codes, units, nunits, qtab,
-                nprobe, r, 1u, flags, hist, thr, tie, counter, keys);
+                nprobe, nq, r, 1u, flags, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<tiecount>");
     rc = launch_tie_quota(tie, kIvfUnitsPerQuery, nq, thr, st);
     if (rc) return rc;
     DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfCollect, CodeT>), grid, dim3(256), lds_tab, codes, units, nunits, qtab,
-                nprobe, r, 1u, flags, hist, thr, tie, counter, keys);
+                nprobe, nq, r, 1u, flags, hist, thr, tie, counter, keys);
     DCPQ_CHECK_LAUNCH("ivf_scan_kernel<collect>");
     return launch_sort_candidates(keys, nq, r, spill, cand_id, cand_qd, st, flags);
 }
