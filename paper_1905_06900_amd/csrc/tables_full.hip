@@ -7,10 +7,10 @@
 // is bound by writing the fp32 tables to HBM, not by the matrix pipe.  One rounding to fp32 at
 // the store.
 #include "common.h"
+#include "f64_tile.h"
 
 namespace dcpq {
 
-typedef double double4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kTileQ = 32;     // queries per workgroup   (2 row tiles of 16)
 constexpr int kTileC = 256;    // centroids per workgroup (4 wavefronts x 64)
@@ -44,45 +44,22 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
 
     const int lr = lane & 15, lk = lane >> 4;
     const int cw = c0 + wave * 64;                     // first centroid of this wavefront
-    // Operands of component step k0 + 4 are loaded while the MFMAs of step k0 run.  The loads are
-    // unconditional (clamped addresses): guarded ones would each be waited for on their own.
-    float av[MT], bv[4];
+    // this lane's rows, clamped to valid ones (rows past the end compute values that are never stored)
+    const float *ap[MT], *bp[4];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int q = q0 + mt * 16 + lr;
+        ap[mt] = queries + static_cast<size_t>(q < nq ? q : nq - 1) * D + j * dsub;
+    }
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) {
+        const int c = cw + lr * 4 + nt;
+        bp[nt] = cbj + static_cast<size_t>(c < ncent ? c : ncent - 1) * dsub;
+    }
     double na[MT], nb[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) na[mt] = 0.0;
-    auto load_step = [&](int k0) {
-        const int k = k0 + lk < dsub ? k0 + lk : dsub - 1;
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            const int q = q0 + mt * 16 + lr;
-            av[mt] = queries[static_cast<size_t>(q < nq ? q : nq - 1) * D + j * dsub + k];
-        }
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) {
-            const int c = cw + lr * 4 + nt;
-            bv[nt] = cbj[static_cast<size_t>(c < ncent ? c : ncent - 1) * dsub + k];
-        }
-    };
-    load_step(0);
-    for (int k0 = 0; k0 < dsub; k0 += 4) {
-        const bool kin = k0 + lk < dsub;
-        double a[MT], b[4];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) a[mt] = (kin && q0 + mt * 16 + lr < nq) ? static_cast<double>(av[mt]) : 0.0;
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) b[nt] = (kin && cw + lr * 4 + nt < ncent) ? static_cast<double>(bv[nt]) : 0.0;
-        if (k0 + 4 < dsub) load_step(k0 + 4);            // uniform
-        // squared norms in fp64 from the operands themselves (this lane's share of the components)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) na[mt] += a[mt] * a[mt];
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) nb[nt] += b[nt] * b[nt];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
-    }
+    f64_tile_products<MT>(ap, bp, dsub, lk, true, acc, na, nb);
     // sum the four component residues: lane (lr, *) then holds the norms of queries q0 + 16 mt + lr and of
     // its own four centroids; the queries' norms go through LDS, because the outputs of a lane belong to
     // other queries than its A operands

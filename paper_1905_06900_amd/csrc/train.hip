@@ -23,10 +23,10 @@
 //     (the distance-table kernel of tables_full.hip).
 #include "common.h"
 #include "device_util.h"
+#include "f64_tile.h"
 
 namespace dcpq {
 
-typedef double double4_t __attribute__((ext_vector_type(4)));
 
 constexpr int kAssignQ = 32;       // points per workgroup (2 row tiles of 16)
 constexpr int kAssignC = 256;      // centroids per step of a workgroup (4 wavefronts x 64)
@@ -69,6 +69,12 @@ __global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ p
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) na[mt] = 0.0;
 
+    const float *ap[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const uint64_t q = q0 + mt * 16 + lr;
+        ap[mt] = points + static_cast<size_t>(q < n ? q : n - 1) * ld + j * dsub;
+    }
     for (int c0 = 0; c0 < ncent; c0 += kAssignC) {                    // uniform
         const int cw = c0 + wave * 64;                                // first centroid of this wavefront
         double4_t acc[MT][4];
@@ -77,43 +83,14 @@ __global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ p
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt) acc[mt][nt] = double4_t{0.0, 0.0, 0.0, 0.0};
         double nb[4] = {0.0, 0.0, 0.0, 0.0};
-        float av[MT], bv[4];
-        // operands of component step k0 + 4 are loaded while the matrix instructions of step k0 run; the
-        // loads are unconditional from clamped addresses (guarded ones would each be waited for on their own)
-        auto load_step = [&](int k0) {
-            const int k = k0 + lk < dsub ? k0 + lk : dsub - 1;
+        // this lane's four centroids, clamped to valid ones (the others are skipped below)
+        const float *bp[4];
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const uint64_t q = q0 + mt * 16 + lr;
-                av[mt] = points[static_cast<size_t>(q < n ? q : n - 1) * ld + j * dsub + k];
-            }
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) {
-                const int c = cw + lr * 4 + nt;
-                bv[nt] = cbj[static_cast<size_t>(c < ncent ? c : ncent - 1) * dsub + k];
-            }
-        };
-        load_step(0);
-        for (int k0 = 0; k0 < dsub; k0 += 4) {
-            const bool kin = k0 + lk < dsub;
-            double a[MT], b[4];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) a[mt] = (kin && q0 + mt * 16 + lr < n) ? static_cast<double>(av[mt]) : 0.0;
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) b[nt] = kin ? static_cast<double>(bv[nt]) : 0.0;
-            if (k0 + 4 < dsub) load_step(k0 + 4);                     // uniform
-            if (c0 == 0) {
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) na[mt] += a[mt] * a[mt];
-            }
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) nb[nt] += b[nt] * b[nt];
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < 4; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+        for (int nt = 0; nt < 4; ++nt) {
+            const int c = cw + lr * 4 + nt;
+            bp[nt] = cbj + static_cast<size_t>(c < ncent ? c : ncent - 1) * dsub;
         }
+        f64_tile_products<MT>(ap, bp, dsub, lk, c0 == 0, acc, na, nb);
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) {
             nb[nt] += __shfl_xor(nb[nt], 16);
@@ -127,8 +104,13 @@ __global__ __launch_bounds__(256) void assign_kernel(const float *__restrict__ p
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-                    for (int v = 0; v < 4; ++v)
-                        take_smaller(best_v[mt][v], best_i[mt][v], nb[nt] - 2.0 * acc[mt][nt][v], static_cast<uint32_t>(c));
+                    for (int v = 0; v < 4; ++v) {
+                        // a lane meets its centroids in increasing index, so "strictly smaller" keeps the first of equals
+                        const double val = fma(-2.0, acc[mt][nt][v], nb[nt]);
+                        const bool better = val < best_v[mt][v];
+                        best_v[mt][v] = better ? val : best_v[mt][v];
+                        best_i[mt][v] = better ? static_cast<uint32_t>(c) : best_i[mt][v];
+                    }
             }
         }
     }

@@ -48,7 +48,9 @@ def test_assign_against_the_oracle(n, m, dsub, ncent):
     for j in range(m):
         ref, rd = oracle.assign(p_np[:, j * dsub:(j + 1) * dsub], c_np[j], want_dist=True)
         check_labels(labels[:, j], p_np[:, j * dsub:(j + 1) * dsub], c_np[j], ref, "sub-quantizer %d" % j)
-        np.testing.assert_allclose(dist[:, j], rd, rtol=1e-5, atol=1e-30)
+        # (a point that IS a centroid: the expanded form ||x||^2 + ||c||^2 - 2<x, c> leaves a rounding residue of
+        # the order of 1e-16 times the norms instead of an exact zero)
+        np.testing.assert_allclose(dist[:, j], rd, rtol=1e-5, atol=1e-12 * float((p_np.astype(np.float64) ** 2).sum(1).max()))
 
 
 @pytest.mark.parametrize("b", [16, 8])
