@@ -326,7 +326,7 @@ def run_ivf(w, args, steps, warmup, with_cpu):
         # own probe lists.
         import oracle
         threads = oracle.num_threads()
-        nsample = min(w.Q, 2 * threads)
+        nsample = min(w.Q, 8 * threads)
         pr = probe[:nsample]
         lists = torch.unique(pr)
         sizes = offsets[lists + 1] - offsets[lists]

@@ -204,7 +204,7 @@ __global__ __launch_bounds__(256) void ivf_tables_kernel(const float *__restrict
 {
     // keep (MODE 0, optional): the entries themselves, [nq][nprobe][m][256], for the quantization to read back
     // instead of computing them a second time
-    extern __shared__ float lds[];         // rho [kIvfTabProbes][m*dsub]
+    extern __shared__ __align__(16) float lds[];         // rho [kIvfTabProbes][m*dsub]
     __shared__ float red[4];
     const int p0 = blockIdx.x * kIvfTabProbes, q = blockIdx.y, tid = threadIdx.x;
     const int np = min(kIvfTabProbes, nprobe - p0);
@@ -226,13 +226,35 @@ __global__ __launch_bounds__(256) void ivf_tables_kernel(const float *__restrict
         float acc[kIvfTabProbes];
 #pragma unroll
         for (int pp = 0; pp < kIvfTabProbes; ++pp) acc[pp] = 0.0f;
-        for (int t = 0; t < dsub; ++t) {
-            const float ct = c[t];
+        if ((dsub & 3) == 0) {
+            // four components per step: one 16-byte load of the centroid, one 16-byte (broadcast) LDS read per
+            // list; the squares are still added one by one in ascending t
+            for (int t = 0; t < dsub; t += 4) {
+                const float4 c4 = *reinterpret_cast<const float4 *>(c + t);
 #pragma unroll
-            for (int pp = 0; pp < kIvfTabProbes; ++pp) {
-                if (pp < np) {                                    // uniform
-                    const float diff = __fsub_rn(lds[pp * D + j * dsub + t], ct);
-                    acc[pp] = __fadd_rn(acc[pp], __fmul_rn(diff, diff));
+                for (int pp = 0; pp < kIvfTabProbes; ++pp) {
+                    if (pp < np) {                                // uniform
+                        const float4 r4 = *reinterpret_cast<const float4 *>(lds + pp * D + j * dsub + t);
+                        float diff = __fsub_rn(r4.x, c4.x);
+                        acc[pp] = __fadd_rn(acc[pp], __fmul_rn(diff, diff));
+                        diff = __fsub_rn(r4.y, c4.y);
+                        acc[pp] = __fadd_rn(acc[pp], __fmul_rn(diff, diff));
+                        diff = __fsub_rn(r4.z, c4.z);
+                        acc[pp] = __fadd_rn(acc[pp], __fmul_rn(diff, diff));
+                        diff = __fsub_rn(r4.w, c4.w);
+                        acc[pp] = __fadd_rn(acc[pp], __fmul_rn(diff, diff));
+                    }
+                }
+            }
+        } else {
+            for (int t = 0; t < dsub; ++t) {
+                const float ct = c[t];
+#pragma unroll
+                for (int pp = 0; pp < kIvfTabProbes; ++pp) {
+                    if (pp < np) {                                // uniform
+                        const float diff = __fsub_rn(lds[pp * D + j * dsub + t], ct);
+                        acc[pp] = __fadd_rn(acc[pp], __fmul_rn(diff, diff));
+                    }
                 }
             }
         }
@@ -733,31 +755,53 @@ __global__ __launch_bounds__(1024) void ivf_refine_kernel(const float *__restric
     __syncthreads();
     uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(q) * n_pow2;
     const float *y = queries + static_cast<size_t>(q) * D;
-    for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x) {
-        uint64_t key = ~0ull;
-        if (t < r) {
-            const uint32_t id = cand_id[static_cast<size_t>(q) * r + t];
-            int p = -1;
-            for (int z = 0; z < nprobe; ++z)
-                if (id >= lbeg[z] && id < lend[z]) { p = z; break; }
-            if (p >= 0) {          // pad slots (id 0xFFFFFFFF) belong to no probed list
-                const float *cl = coarse + static_cast<size_t>(lst[p]) * D;
-                const uint16_t *c = codes + static_cast<size_t>(id) * M;
-                double d = 0.0;
-                for (int j = 0; j < M; ++j) {
-                    const float *cen = cb + (static_cast<size_t>(j) * kFullSize + c[j]) * dsub;
-                    double dj = 0.0;
-                    for (int tt = 0; tt < dsub; ++tt) {
-                        const double diff = (static_cast<double>(y[j * dsub + tt]) - static_cast<double>(cl[j * dsub + tt])) -
-                                            static_cast<double>(cen[tt]);
+    // One lane per (candidate, sub-quantizer): the M lanes of a candidate are neighbours in a wavefront.  They
+    // share the search for the candidate's list, each computes the squared distance of its own sub-vector
+    // (components in ascending order), and the sums are added in ascending j, as a single thread would.
+    {
+        const uint32_t lane = threadIdx.x & 63u;
+        const int j = static_cast<int>(threadIdx.x % M);
+        const bool vec4 = (dsub & 3) == 0;
+        for (uint32_t base = 0; base < n_pow2; base += blockDim.x / M) {      // uniform trip count
+            const uint32_t t = base + threadIdx.x / M;
+            uint32_t id = 0xFFFFFFFFu;
+            if (t < r) id = cand_id[static_cast<size_t>(q) * r + t];
+            int p = -1;                                                      // pad slots (id 0xFFFFFFFF) belong to no probed list
+            for (int z = j; z < nprobe; z += M)
+                if (id >= lbeg[z] && id < lend[z]) p = z;                    // the lists are disjoint: at most one
+#pragma unroll
+            for (int off = 1; off < M; off <<= 1) p = max(p, __shfl_xor(p, off));
+            double dj = 0.0;
+            if (p >= 0) {
+                const float *cl = coarse + static_cast<size_t>(lst[p]) * D + j * dsub;
+                const float *yj = y + j * dsub;
+                const float *cen = cb + (static_cast<size_t>(j) * kFullSize + codes[static_cast<size_t>(id) * M + j]) * dsub;
+                if (vec4) {
+                    for (int tt = 0; tt < dsub; tt += 4) {
+                        const float4 yv = *reinterpret_cast<const float4 *>(yj + tt);
+                        const float4 lv = *reinterpret_cast<const float4 *>(cl + tt);
+                        const float4 cv = *reinterpret_cast<const float4 *>(cen + tt);
+                        double diff = (static_cast<double>(yv.x) - static_cast<double>(lv.x)) - static_cast<double>(cv.x);
+                        dj += diff * diff;
+                        diff = (static_cast<double>(yv.y) - static_cast<double>(lv.y)) - static_cast<double>(cv.y);
+                        dj += diff * diff;
+                        diff = (static_cast<double>(yv.z) - static_cast<double>(lv.z)) - static_cast<double>(cv.z);
+                        dj += diff * diff;
+                        diff = (static_cast<double>(yv.w) - static_cast<double>(lv.w)) - static_cast<double>(cv.w);
                         dj += diff * diff;
                     }
-                    d += dj;
+                } else {
+                    for (int tt = 0; tt < dsub; ++tt) {
+                        const double diff = (static_cast<double>(yj[tt]) - static_cast<double>(cl[tt])) - static_cast<double>(cen[tt]);
+                        dj += diff * diff;
+                    }
                 }
-                key = make_key(__float_as_uint(static_cast<float>(d)), id);
             }
+            double d = __shfl(dj, static_cast<int>(lane - j));
+#pragma unroll
+            for (int jj = 1; jj < M; ++jj) d += __shfl(dj, static_cast<int>(lane - j + jj));
+            if (j == 0 && t < n_pow2) a[t] = p >= 0 ? make_key(__float_as_uint(static_cast<float>(d)), id) : ~0ull;
         }
-        a[t] = key;
     }
     bitonic_sort(a, n_pow2);
     for (uint32_t t = threadIdx.x; t < k; t += blockDim.x) {
@@ -936,6 +980,7 @@ extern "C" int dcpq_ivf_build_small_tables(const float *queries, int nq, const f
     if (nq == 0) return DCPQ_OK;
     DCPQ_REQUIRE(queries && coarse && probe && derived && codes && offsets && qtab && bounds && workspace,
                  "ivf_build_small_tables: null pointer");
+    DCPQ_REQUIRE((reinterpret_cast<uintptr_t>(derived) & 15) == 0, "ivf_build_small_tables: derived must be 16-byte aligned");
     if (workspace_bytes < dcpq_ivf_tables_workspace_bytes(nq))
         return fail(DCPQ_EWORKSPACE, "ivf_build_small_tables: workspace too small");
     hipStream_t st = as_stream(stream);
@@ -1083,6 +1128,8 @@ extern "C" int dcpq_ivf_refine_topk(const float *queries, const float *coarse, i
     DCPQ_REQUIRE(k >= 1 && k <= r, "ivf_refine_topk: needs 1 <= k <= r (k=%u r=%u)", k, r);
     if (nq == 0) return DCPQ_OK;
     DCPQ_REQUIRE(queries && coarse && codebooks && codes && offsets && probe && cand_id && ids && dist, "ivf_refine_topk: null pointer");
+    DCPQ_REQUIRE(((reinterpret_cast<uintptr_t>(queries) | reinterpret_cast<uintptr_t>(coarse) | reinterpret_cast<uintptr_t>(codebooks)) & 15) == 0,
+                 "ivf_refine_topk: queries, coarse and codebooks must be 16-byte aligned");
     const size_t need = dcpq_ivf_refine_workspace_bytes(nq, r);
     if (need && (!workspace || workspace_bytes < need)) return fail(DCPQ_EWORKSPACE, "ivf_refine_topk: workspace too small");
     hipStream_t st = as_stream(stream);
