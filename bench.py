@@ -333,7 +333,11 @@ def run_ivf(w, args, steps, warmup, with_cpu):
         off_c = torch.zeros(lists.numel() + 1, dtype=torch.int64, device=dev)
         off_c[1:] = torch.cumsum(sizes, 0)
         idx = torch.repeat_interleave(offsets[lists] - off_c[:-1], sizes) + torch.arange(int(off_c[-1]), device=dev)
-        codes_c = codes.view(torch.int16)[idx].contiguous().view(torch.uint16)
+        # (gathered in pieces: one indexing call over more than ~50 M rows of this 8 G-element array came back wrong)
+        codes_c = torch.empty((idx.numel(), w.m), dtype=torch.int16, device=dev)
+        for s0 in range(0, idx.numel(), 1 << 24):
+            codes_c[s0:s0 + (1 << 24)] = codes.view(torch.int16)[idx[s0:s0 + (1 << 24)]]
+        codes_c = codes_c.view(torch.uint16)
         remap = torch.full((w.nlist,), -1, dtype=torch.int64, device=dev)
         remap[lists] = torch.arange(lists.numel(), device=dev)
         cb_np, der_np = synth.to_numpy(cb), oracle.derive_codebooks(synth.to_numpy(cb))
