@@ -43,10 +43,13 @@
 //
 // 5. The inner loop is a software pipeline.  The vector instruction port of a SIMD (matrix and
 //    ordinary vector instructions share it) and the LDS are both close to full, and an LDS read
-//    comes back hundreds of clocks after its issue; so the rows of the next iteration and the code
-//    bytes of the one after it are always in flight, and everything per-iteration that is not a
-//    row read, a matrix instruction, an address permute or the sign test has been moved out of the
-//    loop (bounds live in LDS, code bytes are published a batch at a time).
+//    comes back hundreds of clocks after its issue; so (64-query tiles) the rows of the next
+//    iteration and the code bytes of the one after it are always in flight, and everything
+//    per-iteration that is not a row read, a matrix instruction, an address permute or the sign
+//    test has been moved out of the loop (bounds live in LDS, code bytes are published a batch at
+//    a time).  The 16- and 32-query tiles, which serve small batches where the code stream from
+//    memory sets the pace, keep a single set of row registers: a second set would push per-lane
+//    constants into scratch memory, and their reloads would queue behind the code prefetch.
 #include <type_traits>
 
 #include "common.h"
