@@ -333,11 +333,15 @@ ScanPlan plan_scan(uint64_t n_codes, int m, int nq, uint32_t r, int mode)
     p.fast = p.fqt != 0;
     if (p.fast) {
         p.ntiles = static_cast<uint32_t>((Q + p.fqt - 1) / p.fqt);
-        // workgroups along the codes, about 8 rounds of the 256 CUs in total, at least 16 Ki codes each
+        // workgroups along the codes, at least 16 Ki codes each
         const uint64_t rest = n_codes;
         // (a single tile does the same work in every workgroup, and one round of the 256 CUs measured
         // fastest for it; with several tiles the work per workgroup varies and more rounds even it out)
-        const uint64_t want = p.ntiles == 1 ? 256 : (2048 + p.ntiles - 1) / p.ntiles;
+        // Several tiles: at least 2048 workgroups in all and at least 128 per tile (measured: 4096 queries = 64
+        // tiles take 45.3 ms with 2048 workgroups, 41.5 ms with 8192, 43.4 ms with 131072; the rounds of
+        // workgroups end unevenly, the more so the longer a workgroup runs).
+        const uint64_t total = 128ull * p.ntiles > 2048 ? 128ull * p.ntiles : 2048;
+        const uint64_t want = p.ntiles == 1 ? 256 : (total + p.ntiles - 1) / p.ntiles;
         const uint64_t most = (rest + 16383) / 16384;
         uint64_t fb = want < most ? want : most;
         if (fb < 1) fb = 1;
