@@ -487,17 +487,15 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
             // codes in this group: fewer than 64 in the last group of the stretch, none past it
             const uint32_t gbase = cbeg + g * 64u;
             const int nlive = g < ngroups ? static_cast<int>(min(64u, cend - gbase)) : 0;
+            // Which of the 4 UC results hold the hit(s): one compare per result, whose outcome is a lane mask
+            // in scalar registers, so that the search for the (usually single) result with a hit runs on the
+            // scalar unit and only that result is decoded on the vector unit.
 #pragma unroll
             for (int u = 0; u < UC; ++u) {
-                // (taken apart from the OR above on purpose: sharing sub-terms with it would put one more
-                // instruction on the path of the chunks without a hit, which are nearly all)
-                int su = acc[u][0];
-                asm volatile("" : "+v"(su));
-                su = su | acc[u][1] | acc[u][2] | acc[u][3];
-                if (!__builtin_amdgcn_ballot_w64(su < 0)) continue;      // uniform: no hit in this step
                 const int first = (p * U + uc + u) * C::CPS;    // first code of the step within the group
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
+                    if (!__builtin_amdgcn_ballot_w64(acc[u][v] < 0)) continue;      // uniform
                     // (the empty asm keeps the compiler from precomputing, and then spilling, this sum for
                     // every step of a group outside the loop)
                     int slot = code_slot_of(v);
