@@ -96,7 +96,8 @@ def run_flat(w, args, steps, warmup, with_cpu, headline):
     torch.cuda.synchronize()
     setup_s = time.perf_counter() - t0
 
-    refine_mode = {"auto": binding.REFINE_AUTO, "tables": binding.REFINE_TABLES, "direct": binding.REFINE_DIRECT}[args.refine]
+    refine_mode = {"auto": binding.REFINE_AUTO, "tables": binding.REFINE_TABLES, "direct": binding.REFINE_DIRECT,
+                   "split": binding.REFINE_SPLIT}[args.refine]
 
     def step():
         binding.search(queries, cb, derived, codes, w.r, w.k, args.chunk, ws, ids, dist, refine_mode)
@@ -133,7 +134,7 @@ def run_flat(w, args, steps, warmup, with_cpu, headline):
             roofline = hbm_roofline(dom, wbytes, dom_ms, dom_launches, steps, w.name, "table writes to HBM")
     elif dom == "refine_topk":
         # pass two: per candidate one code and m centroid rows (on demand) or m table entries
-        direct = binding.search_refine_mode(w.b, w.dsub, w.r, refine_mode) == binding.REFINE_DIRECT
+        direct = binding.search_refine_mode(w.m, w.dsub, w.b, w.Q, w.r, refine_mode) != binding.REFINE_TABLES
         per_cand = code_bytes + w.m * (4 * w.dsub if direct else 4)
         roofline = hbm_roofline(dom, float(w.Q) * w.r * per_cand / (dom_launches / steps), dom_ms, dom_launches, steps, w.name,
                                 "scattered reads (one code and m %s per candidate)" % ("centroid rows" if direct else "table entries"))
@@ -155,8 +156,8 @@ def run_flat(w, args, steps, warmup, with_cpu, headline):
                    "code_bytes": code_bytes, "seed": w.seed},
         "roofline": roofline,
         "stage_ms_per_step": {s: round(v[0] / steps, 3) for s, v in stages.items() if v[1]},
-        "refine_mode": {binding.REFINE_TABLES: "tables", binding.REFINE_DIRECT: "direct"}[
-            binding.search_refine_mode(w.b, w.dsub, w.r, refine_mode)],
+        "refine_mode": {binding.REFINE_TABLES: "tables", binding.REFINE_DIRECT: "direct", binding.REFINE_SPLIT: "split"}[
+            binding.search_refine_mode(w.m, w.dsub, w.b, w.Q, w.r, refine_mode)],
         "setup_s": round(setup_s, 2),
     }
 
@@ -372,9 +373,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="headline workload only")
     ap.add_argument("--chunk", type=int, default=0, help="queries per chunk of the fused search (0 = default)")
-    ap.add_argument("--refine", choices=("auto", "tables", "direct"), default="auto",
-                    help="pass two of the flat workloads: table entries on demand (direct), from full tables, or the "
-                         "library's own choice")
+    ap.add_argument("--refine", choices=("auto", "tables", "direct", "split"), default="auto",
+                    help="pass two of the flat workloads: table entries on demand (direct: one kernel; split: by "
+                         "sub-quantizer), from full tables, or the library's own choice")
     ap.add_argument("--compare", action="store_true",
                     help="also time the conventional single-pass search (plain 16-bit and plain 8-bit PQ, Alg. 1) "
                          "on the same workload; flat workloads only")

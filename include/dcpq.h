@@ -218,14 +218,25 @@ int dcpq_search_bits_chunk(int m, int nq, int b, int chunk_queries);
  *   DCPQ_REFINE_TABLES  build the full tables of the chunk first, then look entries up
  *   DCPQ_REFINE_DIRECT  compute every entry a candidate needs from the codebooks (fp64, rounded to
  *                       fp32 once: the value the tables would hold, up to the last bit); no tables
- *   DCPQ_REFINE_AUTO    DIRECT while r <= 2^b / 8, else TABLES (dcpq_search uses this);
- *                       dcpq_search_refine_mode reports the choice
- * Both give the fp32 sum, j increasing, of the M entries; results agree within the 1e-5 bar and may
- * differ in the last bit (and then in the order of near-ties). */
+ *   DCPQ_REFINE_SPLIT   the same entries, bit for bit, computed in three kernels split by sub-quantizer
+ *                       so that each of the 8 second-level caches keeps serving one sub-codebook;
+ *                       its two intermediate arrays, chunk * r * m * (4 + b / 8) bytes, live in the
+ *                       region of the workspace that the tables would take: they fit whenever
+ *                       r * (4 + b / 8) <= 4 * 2^b; DCPQ_EINVAL if they do not, if chunk * r
+ *                       reaches 2^32, or if `queries` is not 16-byte aligned
+ *   DCPQ_REFINE_AUTO    TABLES when r > 2^b / 8; else SPLIT when it is possible, a sub-codebook (two
+ *                       for m = 16, four for m = 32) is smaller than 4 MB, the codebooks as a whole
+ *                       are not, and the chunk has at least 2^16 candidates; else DIRECT (dcpq_search
+ *                       uses this).
+ *                       dcpq_search_refine_mode reports the choice for the first chunk of a batch of
+ *                       nq queries under the default chunking
+ * All give the fp32 sum, j increasing, of the M entries; TABLES and the on-demand modes agree within
+ * the 1e-5 bar and may differ in the last bit (and then in the order of near-ties). */
 #define DCPQ_REFINE_AUTO 0
 #define DCPQ_REFINE_TABLES 1
 #define DCPQ_REFINE_DIRECT 2
-int dcpq_search_refine_mode(int b, int dsub, uint32_t r, int refine_mode);
+#define DCPQ_REFINE_SPLIT 3
+int dcpq_search_refine_mode(int m, int dsub, int b, int nq, uint32_t r, int refine_mode);
 int dcpq_search_bits(const float *queries, int nq, const float *codebooks, const float *derived, int m,
                      int dsub, int b, int bbar, const void *codes, uint64_t n_codes, uint32_t r, uint32_t k,
                      int refine_mode, uint32_t *ids, float *dist, int chunk_queries, void *workspace,

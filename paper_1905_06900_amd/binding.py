@@ -41,7 +41,7 @@ _SIGNATURES = {
     "dcpq_search_bits_chunk": (_i, [_i, _i, _i, _i]),
     "dcpq_search_bits_workspace_bytes": (_sz, [_u64, _i, _i, _u32, _i, _i]),
     "dcpq_search_bits": (_i, [_vp, _i, _vp, _vp, _i, _i, _i, _i, _vp, _u64, _u32, _u32, _i, _vp, _vp, _i, _vp, _sz, _vp]),
-    "dcpq_search_refine_mode": (_i, [_i, _i, _u32, _i]),
+    "dcpq_search_refine_mode": (_i, [_i, _i, _i, _i, _u32, _i]),
     "dcpq_refine_direct_topk": (_i, [_vp, _vp, _i, _i, _i, _vp, _u64, _vp, _i, _u32, _u32, _vp, _vp, _vp, _sz, _vp]),
     "dcpq_assign": (_i, [_vp, _u64, _i, _vp, _i, _i, _i, _vp, _i, _vp, _vp]),
     "dcpq_encode": (_i, [_vp, _u64, _vp, _i, _i, _i, _vp, _vp]),
@@ -314,11 +314,12 @@ def refine_topk(tables: torch.Tensor, codes: torch.Tensor, cand_id: torch.Tensor
     return ids, dist
 
 
-REFINE_AUTO, REFINE_TABLES, REFINE_DIRECT = 0, 1, 2
+REFINE_AUTO, REFINE_TABLES, REFINE_DIRECT, REFINE_SPLIT = 0, 1, 2, 3
 
 
-def search_refine_mode(b: int, dsub: int, r: int, refine_mode: int = REFINE_AUTO) -> int:
-    return int(lib().dcpq_search_refine_mode(b, dsub, r, refine_mode))
+def search_refine_mode(m: int, dsub: int, b: int, nq: int, r: int, refine_mode: int = REFINE_AUTO) -> int:
+    """The mode pass two of `search` runs in for (the first chunk of) a batch of nq queries."""
+    return int(lib().dcpq_search_refine_mode(m, dsub, b, nq, r, refine_mode))
 
 
 def refine_direct_topk(queries: torch.Tensor, codebooks: torch.Tensor, codes: torch.Tensor, cand_id: torch.Tensor,

@@ -102,5 +102,11 @@ int launch_pad_rows(const float *src, size_t nrows, int dsub, int cstride, float
 int launch_refine_direct(const float *queries, const float *codebooks, int dsub, int cstride, uint32_t table_size, const void *codes,
                          int code_bytes, uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k,
                          uint32_t *ids, float *dist, void *ws, hipStream_t st);
+// the same in three kernels, split by sub-quantizer so that each XCD's cache keeps one sub-codebook; `mid`:
+// refine_split_bytes(...) bytes, 256-byte aligned; nq * r must fit 32 bits
+size_t refine_split_bytes(int nq, uint32_t r, int m, int code_bytes);
+int launch_refine_split(const float *queries, const float *codebooks, int dsub, uint32_t table_size, const void *codes,
+                        int code_bytes, uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k,
+                        uint32_t *ids, float *dist, void *mid, void *ws, hipStream_t st);
 
 }  // namespace dcpq

@@ -23,16 +23,45 @@ static uint32_t next_pow2_r(uint32_t x)
     return p;
 }
 
+constexpr int kFromTables = 0, kOnDemand = 1, kFromTerms = 2;     // where refine_topk_kernel takes its entries from
+
+// Double-precision squared distance between a query sub-vector and a centroid row (Eq. 1), rounded to fp32
+// once: the value a full table holds.
+__device__ inline float entry_on_demand(const float *__restrict__ yj, const float *__restrict__ cen, int dsub, bool vec4)
+{
+    double dj = 0.0;
+    if (vec4) {
+#pragma unroll 4
+        for (int tt = 0; tt < dsub; tt += 4) {
+            const float4 cv = *reinterpret_cast<const float4 *>(cen + tt);
+            const float4 yv = *reinterpret_cast<const float4 *>(yj + tt);
+            const double d0 = static_cast<double>(yv.x) - static_cast<double>(cv.x);
+            const double d1 = static_cast<double>(yv.y) - static_cast<double>(cv.y);
+            const double d2 = static_cast<double>(yv.z) - static_cast<double>(cv.z);
+            const double d3 = static_cast<double>(yv.w) - static_cast<double>(cv.w);
+            dj = fma(d0, d0, dj); dj = fma(d1, d1, dj); dj = fma(d2, d2, dj); dj = fma(d3, d3, dj);
+        }
+    } else {
+        for (int tt = 0; tt < dsub; ++tt) {
+            const double df = static_cast<double>(yj[tt]) - static_cast<double>(cen[tt]);
+            dj = fma(df, df, dj);
+        }
+    }
+    return static_cast<float>(dj);
+}
+
 // CodeT: uint16_t or uint8_t sub-codes; table_size = 2^b entries per sub-quantizer.
-// DIRECT = false: `src` = the full tables [nq][M][table_size], an entry is looked up.
-// DIRECT = true:  `src` = the queries [nq][M * dsub]; an entry (Eq. 1: squared distance between the
+// MODE = kFromTables: `src` = the full tables [nq][M][table_size], an entry is looked up.
+// MODE = kFromTerms:  `src` = the entries themselves, [M][gridDim.x * r] (sub-quantizer, then query, then
+//   candidate), computed on demand by refine_terms_kernel below.
+// MODE = kOnDemand:   `src` = the queries [nq][M * dsub]; an entry (Eq. 1: squared distance between the
 //   query's sub-vector and the centroid the sub-code names) is computed when a candidate asks for it,
 //   straight from the codebook `cb` [M][table_size] rows of dsub floats, cstride floats apart -- the refinement of Alg. 3 computes table
 //   entries on demand because only a small part of a 2^16-entry table is ever used (Sec. 3.3,
 //   Refine step); here nothing is memoized, the entry is recomputed in double precision and rounded
 //   to fp32 once, which is what the tables hold.  Either way the distance is the fp32 sum of the M
 //   entries, j increasing.
-template <int M, typename CodeT, bool DIRECT>
+template <int M, typename CodeT, int MODE>
 __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restrict__ src, uint32_t table_size,
                                                           const float *__restrict__ cb, int dsub, int cstride,
                                                           const CodeT *__restrict__ codes, uint32_t n_codes,
@@ -44,6 +73,7 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
     extern __shared__ __align__(16) uint8_t smem[];
     const int q = blockIdx.x;
     uint64_t *a = use_lds ? reinterpret_cast<uint64_t *>(smem) : spill + static_cast<size_t>(q) * n_pow2;
+    constexpr bool DIRECT = MODE == kOnDemand;
     const float *tq = nullptr;
     float *ly = nullptr;
     if constexpr (DIRECT) {
@@ -51,7 +81,7 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
         ly = reinterpret_cast<float *>(smem + (use_lds ? sizeof(uint64_t) * n_pow2 : 0));     // the query
         for (int t = threadIdx.x; t < D; t += blockDim.x) ly[t] = src[static_cast<size_t>(q) * D + t];
         __syncthreads();
-    } else {
+    } else if constexpr (MODE == kFromTables) {
         tq = src + static_cast<size_t>(q) * M * table_size;
     }
     if constexpr (DIRECT) {
@@ -69,30 +99,28 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
             if (id < n_codes) {                                          // pad slots (and anything out of range) sort last
                 const uint32_t cj = codes[static_cast<size_t>(id) * M + j];
                 const float *cen = cb + (static_cast<size_t>(j) * table_size + cj) * cstride;
-                double dj = 0.0;
-                if (vec4) {
-#pragma unroll 4
-                    for (int tt = 0; tt < dsub; tt += 4) {
-                        const float4 cv = *reinterpret_cast<const float4 *>(cen + tt);
-                        const float4 yv = *reinterpret_cast<const float4 *>(yj + tt);
-                        const double d0 = static_cast<double>(yv.x) - static_cast<double>(cv.x);
-                        const double d1 = static_cast<double>(yv.y) - static_cast<double>(cv.y);
-                        const double d2 = static_cast<double>(yv.z) - static_cast<double>(cv.z);
-                        const double d3 = static_cast<double>(yv.w) - static_cast<double>(cv.w);
-                        dj = fma(d0, d0, dj); dj = fma(d1, d1, dj); dj = fma(d2, d2, dj); dj = fma(d3, d3, dj);
-                    }
-                } else {
-                    for (int tt = 0; tt < dsub; ++tt) {
-                        const double df = static_cast<double>(yj[tt]) - static_cast<double>(cen[tt]);
-                        dj = fma(df, df, dj);
-                    }
-                }
-                e = static_cast<float>(dj);
+                e = entry_on_demand(yj, cen, dsub, vec4);
             }
             float d = __shfl(e, static_cast<int>(lane - j));
 #pragma unroll
             for (int jj = 1; jj < M; ++jj) d = __fadd_rn(d, __shfl(e, static_cast<int>(lane - j + jj)));
             if (j == 0 && t < n_pow2) a[t] = id < n_codes ? make_key(__float_as_uint(d), id) : ~0ull;
+        }
+    } else if constexpr (MODE == kFromTerms) {
+        const size_t total = static_cast<size_t>(gridDim.x) * r;
+        for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x) {
+            uint64_t key = ~0ull;
+            if (t < r) {
+                const size_t at = static_cast<size_t>(q) * r + t;
+                const uint32_t id = cand_id[at];
+                if (id < n_codes) {                 // pad slots (and anything out of range) sort last
+                    float d = src[at];
+#pragma unroll
+                    for (int j = 1; j < M; ++j) d = __fadd_rn(d, src[j * total + at]);
+                    key = make_key(__float_as_uint(d), id);
+                }
+            }
+            a[t] = key;
         }
     } else {
         for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x) {
@@ -195,17 +223,17 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
     }
 }
 
-template <int M, typename CodeT, bool DIRECT>
+template <int M, typename CodeT, int MODE>
 static int launch_refine_m(const float *src, uint32_t table_size, const float *cb, int dsub, int cstride, const CodeT *codes,
                            uint64_t n_codes, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
                            float *dist, void *ws, hipStream_t st)
 {
     const uint32_t np2 = next_pow2_r(r);
     const int use_lds = np2 <= kRefineLdsKeys;
-    const size_t lds = (use_lds ? sizeof(uint64_t) * np2 : 0) + (DIRECT ? sizeof(float) * M * dsub : 0);
-    const int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&refine_topk_kernel<M, CodeT, DIRECT>), static_cast<int>(lds));
+    const size_t lds = (use_lds ? sizeof(uint64_t) * np2 : 0) + (MODE == kOnDemand ? sizeof(float) * M * dsub : 0);
+    const int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&refine_topk_kernel<M, CodeT, MODE>), static_cast<int>(lds));
     if (rc) return rc;
-    DCPQ_LAUNCH(kStageRefine, st, (refine_topk_kernel<M, CodeT, DIRECT>), dim3(nq), dim3(1024), lds, src, table_size, cb, dsub,
+    DCPQ_LAUNCH(kStageRefine, st, (refine_topk_kernel<M, CodeT, MODE>), dim3(nq), dim3(1024), lds, src, table_size, cb, dsub,
                 cstride, codes, static_cast<uint32_t>(n_codes), cand_id, r, k, np2, use_lds, static_cast<uint64_t *>(ws), ids, dist);
     DCPQ_CHECK_LAUNCH("refine_topk_kernel");
     return DCPQ_OK;
@@ -229,7 +257,7 @@ int launch_pad_rows(const float *src, size_t nrows, int dsub, int cstride, float
     return DCPQ_OK;
 }
 
-template <typename CodeT, bool DIRECT>
+template <typename CodeT, int MODE>
 static int launch_refine_t(const float *src, uint32_t table_size, const float *cb, int dsub, int cstride, const CodeT *codes,
                            uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
                            float *dist, void *ws, hipStream_t st)
@@ -237,7 +265,7 @@ static int launch_refine_t(const float *src, uint32_t table_size, const float *c
     if (nq == 0) return DCPQ_OK;
 #define DCPQ_LAUNCH_REFINE(MV)                                                                                      \
     case MV:                                                                                                        \
-        return launch_refine_m<MV, CodeT, DIRECT>(src, table_size, cb, dsub, cstride, codes, n_codes, cand_id, nq, r, k, ids, dist, ws, st);
+        return launch_refine_m<MV, CodeT, MODE>(src, table_size, cb, dsub, cstride, codes, n_codes, cand_id, nq, r, k, ids, dist, ws, st);
     switch (m) {
         DCPQ_LAUNCH_REFINE(1) DCPQ_LAUNCH_REFINE(2) DCPQ_LAUNCH_REFINE(4) DCPQ_LAUNCH_REFINE(8)
         DCPQ_LAUNCH_REFINE(16) DCPQ_LAUNCH_REFINE(32)
@@ -251,9 +279,9 @@ int launch_refine(const float *tables, uint32_t table_size, const void *codes, i
                   hipStream_t st)
 {
     if (code_bytes == 1)
-        return launch_refine_t<uint8_t, false>(tables, table_size, nullptr, 0, 0, static_cast<const uint8_t *>(codes), n_codes, m,
+        return launch_refine_t<uint8_t, kFromTables>(tables, table_size, nullptr, 0, 0, static_cast<const uint8_t *>(codes), n_codes, m,
                                                cand_id, nq, r, k, ids, dist, ws, st);
-    return launch_refine_t<uint16_t, false>(tables, table_size, nullptr, 0, 0, static_cast<const uint16_t *>(codes), n_codes, m,
+    return launch_refine_t<uint16_t, kFromTables>(tables, table_size, nullptr, 0, 0, static_cast<const uint16_t *>(codes), n_codes, m,
                                             cand_id, nq, r, k, ids, dist, ws, st);
 }
 
@@ -262,10 +290,185 @@ int launch_refine_direct(const float *queries, const float *codebooks, int dsub,
                          uint32_t *ids, float *dist, void *ws, hipStream_t st)
 {
     if (code_bytes == 1)
-        return launch_refine_t<uint8_t, true>(queries, table_size, codebooks, dsub, cstride, static_cast<const uint8_t *>(codes), n_codes,
+        return launch_refine_t<uint8_t, kOnDemand>(queries, table_size, codebooks, dsub, cstride, static_cast<const uint8_t *>(codes), n_codes,
                                               m, cand_id, nq, r, k, ids, dist, ws, st);
-    return launch_refine_t<uint16_t, true>(queries, table_size, codebooks, dsub, cstride, static_cast<const uint16_t *>(codes), n_codes, m,
+    return launch_refine_t<uint16_t, kOnDemand>(queries, table_size, codebooks, dsub, cstride, static_cast<const uint16_t *>(codes), n_codes, m,
                                            cand_id, nq, r, k, ids, dist, ws, st);
+}
+
+
+// ---- on demand, split by sub-quantizer ---------------------------------------------------------
+// The one-kernel form above gathers, for every candidate, m centroid rows out of codebooks of tens of
+// megabytes: nearly every row misses the 4 MB second-level cache of the XCD the workgroup runs on, and the
+// kernel is bound by the number of memory lines it moves.  A sub-quantizer's own codebook (2^16 rows of
+// dsub floats: 3 MB at dsub = 12) does fit one such cache, and the chip has 8 of them; workgroups are handed
+// to the 8 XCDs in turn, so workgroup number w runs on XCD w mod 8.  The split form therefore lets the
+// workgroups with w mod 8 = x compute the entries of sub-quantizers j = x, x + 8, ... only (for m < 8: of
+// j = x mod m, for one part in 8 / m of the candidates), so that each cache keeps seeing the same few
+// megabytes of rows.  Should the hardware hand workgroups out differently, the result is the same and only
+// the time changes.  Three kernels:
+//   gather_codes_kernel   sub-codes of all candidates of the batch, by sub-quantizer: plane[j][candidate]
+//                         (one scattered read of a whole code per candidate, contiguous writes)
+//   refine_terms_kernel   entry[j][candidate] (Eq. 1, as in the one-kernel form: fp64, rounded to fp32 once)
+//   refine_topk_kernel<kFromTerms>   fp32 sum over j increasing, then the k smallest by (distance, id)
+// Candidates are numbered query * r + position, as in cand_id.
+constexpr uint32_t kSplitChunk = 2048;      // candidates per workgroup of refine_terms_kernel (256 threads x 8)
+
+template <int M, typename CodeT>
+__global__ __launch_bounds__(256) void gather_codes_kernel(const CodeT *__restrict__ codes, uint32_t n_codes,
+                                                           const uint32_t *__restrict__ cand_id, uint32_t total,
+                                                           CodeT *__restrict__ plane)
+{
+    const uint32_t t = blockIdx.x * 256u + threadIdx.x;
+    if (t >= total) return;
+    const uint32_t id = cand_id[t];
+    constexpr int BYTES = M * static_cast<int>(sizeof(CodeT));
+    CodeT c[M];
+#pragma unroll
+    for (int j = 0; j < M; ++j) c[j] = 0;                              // pad slots: any valid sub-code
+    if (id < n_codes) {
+        const uint8_t *src = reinterpret_cast<const uint8_t *>(codes) + static_cast<size_t>(id) * BYTES;
+        if constexpr (BYTES % 16 == 0) {
+#pragma unroll
+            for (int v = 0; v < BYTES / 16; ++v) reinterpret_cast<uint4 *>(c)[v] = reinterpret_cast<const uint4 *>(src)[v];
+        } else if constexpr (BYTES == 8) {
+            *reinterpret_cast<uint2 *>(c) = *reinterpret_cast<const uint2 *>(src);
+        } else if constexpr (BYTES == 4) {
+            *reinterpret_cast<uint32_t *>(c) = *reinterpret_cast<const uint32_t *>(src);
+        } else {
+#pragma unroll
+            for (int j = 0; j < M; ++j) c[j] = reinterpret_cast<const CodeT *>(src)[j];
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < M; ++j) plane[static_cast<size_t>(j) * total + t] = c[j];
+}
+
+// P > 0: rows of P 16-byte parts (dsub = 4 P).  Lane l of a wavefront reading its own row with P loads would
+// send P separate requests per row to the second-level cache, whose request rate is what bounds this kernel
+// (2.9 requests per entry measured at dsub = 12); instead the P * 64 parts of the wavefront's 64 rows are
+// fetched in row order, lane after lane, so that the parts of a row travel in one request (two when the row
+// lies across a 64-byte boundary), parked in LDS, and each lane then picks up its row there.
+// P = 0: rows of any length, each read by its own lane.
+template <typename CodeT, int P>
+__global__ __launch_bounds__(256) void refine_terms_kernel(const float *__restrict__ queries, int m, int dsub,
+                                                           const float *__restrict__ cb, uint32_t table_size,
+                                                           const CodeT *__restrict__ plane, uint32_t total, uint32_t r,
+                                                           float *__restrict__ terms)
+{
+    __shared__ float4 stage[P ? 256 * P : 1];
+    const uint32_t x = blockIdx.x & 7u;                                // the XCD this workgroup is expected on
+    const uint32_t first = (blockIdx.x >> 3) * kSplitChunk;            // its stretch of candidates
+    const bool vec4 = (dsub & 3) == 0;
+    const int D = m * dsub;
+    const uint32_t lane = threadIdx.x & 63u;
+    float4 *ws = stage + (threadIdx.x >> 6) * (64 * P);                // this wavefront's rows
+    // m >= 8: sub-quantizers x, x + 8, ..., every candidate of the stretch; m < 8: sub-quantizer x mod m, the
+    // candidates of part x / m out of 8 / m (threads are dealt to the parts in turn)
+    const uint32_t parts = m >= 8 ? 1u : 8u / static_cast<uint32_t>(m), part = m >= 8 ? 0u : x / static_cast<uint32_t>(m);
+    for (int j = m >= 8 ? static_cast<int>(x) : static_cast<int>(x % static_cast<uint32_t>(m)); j < m; j += 8) {
+        const CodeT *pj = plane + static_cast<size_t>(j) * total;
+        const float *cj = cb + static_cast<size_t>(j) * table_size * dsub;
+        float *tj = terms + static_cast<size_t>(j) * total;
+        // (the same number of rounds for every thread: kSplitChunk is a multiple of 256 * parts)
+#pragma unroll 2
+        for (uint32_t i = threadIdx.x + 256u * part; i < kSplitChunk; i += 256u * parts) {
+            const uint32_t t = first + i;
+            const bool live = t < total;
+            const uint32_t code = live ? pj[t] : 0u;                   // past the end: any valid row, result dropped
+            const float *yj = queries + static_cast<size_t>(live ? t / r : 0u) * D + j * dsub;
+            float e;
+            if constexpr (P > 0) {
+#pragma unroll
+                for (int c = 0; c < P; ++c) {
+                    const uint32_t f = 64u * c + lane;                 // part f % P of the row of lane f / P
+                    const uint32_t owner = f / P;
+                    const uint32_t oc = static_cast<uint32_t>(__shfl(static_cast<int>(code), static_cast<int>(owner)));
+                    ws[f] = *reinterpret_cast<const float4 *>(cj + static_cast<size_t>(oc) * dsub + 4u * (f - owner * P));
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                double dj = 0.0;
+#pragma unroll
+                for (int c = 0; c < P; ++c) {                          // the arithmetic of entry_on_demand, part by part
+                    const float4 cv = ws[lane * P + c];
+                    const float4 yv = *reinterpret_cast<const float4 *>(yj + 4 * c);
+                    const double d0 = static_cast<double>(yv.x) - static_cast<double>(cv.x);
+                    const double d1 = static_cast<double>(yv.y) - static_cast<double>(cv.y);
+                    const double d2 = static_cast<double>(yv.z) - static_cast<double>(cv.z);
+                    const double d3 = static_cast<double>(yv.w) - static_cast<double>(cv.w);
+                    dj = fma(d0, d0, dj); dj = fma(d1, d1, dj); dj = fma(d2, d2, dj); dj = fma(d3, d3, dj);
+                }
+                e = static_cast<float>(dj);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");     // every lane has its row before the next round parks new ones
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            } else {
+                e = entry_on_demand(yj, cj + static_cast<size_t>(code) * dsub, dsub, vec4);
+            }
+            if (live) tj[t] = e;
+        }
+    }
+}
+
+// bytes of the two intermediate arrays (sub-code planes, then entries) for nq queries
+size_t refine_split_bytes(int nq, uint32_t r, int m, int code_bytes)
+{
+    const size_t total = static_cast<size_t>(nq) * r;
+    return align_up(total * m * code_bytes, 256) + total * m * sizeof(float);
+}
+
+template <typename CodeT>
+static int launch_refine_split_t(const float *queries, const float *codebooks, int dsub, uint32_t table_size, const CodeT *codes,
+                                 uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k, uint32_t *ids,
+                                 float *dist, void *mid, void *ws, hipStream_t st)
+{
+    const uint32_t total = static_cast<uint32_t>(static_cast<size_t>(nq) * r);
+    CodeT *plane = static_cast<CodeT *>(mid);
+    float *terms = reinterpret_cast<float *>(static_cast<uint8_t *>(mid) + align_up(static_cast<size_t>(total) * m * sizeof(CodeT), 256));
+    const dim3 g1((total + 255u) / 256u);
+#define DCPQ_LAUNCH_GATHER(MV)                                                                                      \
+    case MV:                                                                                                        \
+        DCPQ_LAUNCH(kStageRefine, st, (gather_codes_kernel<MV, CodeT>), g1, dim3(256), 0, codes,                     \
+                    static_cast<uint32_t>(n_codes), cand_id, total, plane);                                        \
+        break;
+    switch (m) {
+        DCPQ_LAUNCH_GATHER(1) DCPQ_LAUNCH_GATHER(2) DCPQ_LAUNCH_GATHER(4) DCPQ_LAUNCH_GATHER(8)
+        DCPQ_LAUNCH_GATHER(16) DCPQ_LAUNCH_GATHER(32)
+        default: return fail(DCPQ_EUNSUPPORTED, "m=%d not supported", m);
+    }
+#undef DCPQ_LAUNCH_GATHER
+    DCPQ_CHECK_LAUNCH("gather_codes_kernel");
+    const uint32_t stretches = (total + kSplitChunk - 1) / kSplitChunk;
+#define DCPQ_LAUNCH_TERMS(PV)                                                                                       \
+    case PV:                                                                                                        \
+        DCPQ_LAUNCH(kStageRefine, st, (refine_terms_kernel<CodeT, PV>), dim3(8u * stretches), dim3(256), 0, queries, m, dsub,    \
+                    codebooks, table_size, plane, total, r, terms);                                                 \
+        break;
+    // rows of up to 8 whole 16-byte parts go through LDS (codebooks are 16-byte aligned: the callers check)
+    switch (dsub % 4 == 0 && dsub <= 32 ? dsub / 4 : 0) {
+        DCPQ_LAUNCH_TERMS(1) DCPQ_LAUNCH_TERMS(2) DCPQ_LAUNCH_TERMS(3) DCPQ_LAUNCH_TERMS(4) DCPQ_LAUNCH_TERMS(5)
+        DCPQ_LAUNCH_TERMS(6) DCPQ_LAUNCH_TERMS(7) DCPQ_LAUNCH_TERMS(8)
+        default: DCPQ_LAUNCH(kStageRefine, st, (refine_terms_kernel<CodeT, 0>), dim3(8u * stretches), dim3(256), 0, queries, m,
+                             dsub, codebooks, table_size, plane, total, r, terms);
+    }
+#undef DCPQ_LAUNCH_TERMS
+    DCPQ_CHECK_LAUNCH("refine_terms_kernel");
+    return launch_refine_t<CodeT, kFromTerms>(terms, table_size, nullptr, 0, 0, codes, n_codes, m, cand_id, nq, r, k, ids, dist, ws, st);
+}
+
+// mid: refine_split_bytes(nq, r, m, code_bytes) bytes, 256-byte aligned; nq * r must fit 32 bits (the caller checks both)
+int launch_refine_split(const float *queries, const float *codebooks, int dsub, uint32_t table_size, const void *codes,
+                        int code_bytes, uint64_t n_codes, int m, const uint32_t *cand_id, int nq, uint32_t r, uint32_t k,
+                        uint32_t *ids, float *dist, void *mid, void *ws, hipStream_t st)
+{
+    if (nq == 0) return DCPQ_OK;
+    if (code_bytes == 1)
+        return launch_refine_split_t<uint8_t>(queries, codebooks, dsub, table_size, static_cast<const uint8_t *>(codes), n_codes, m,
+                                              cand_id, nq, r, k, ids, dist, mid, ws, st);
+    return launch_refine_split_t<uint16_t>(queries, codebooks, dsub, table_size, static_cast<const uint16_t *>(codes), n_codes, m,
+                                           cand_id, nq, r, k, ids, dist, mid, ws, st);
 }
 
 }  // namespace dcpq

@@ -26,7 +26,7 @@
 // 3. Capped buckets become a running threshold.  Each query has a bucket bound T_cur that the
 //    scan never lets fall below the bucket of its r-th best candidate: it starts from the histogram
 //    of a strided sample of the codes, at the bucket where the sample's count reaches what r
-//    codes of the whole array would leave in a sample of that size (plus eight standard
+//    codes of the whole array would leave in a sample of that size (plus five standard
 //    deviations), and it is lowered whenever the exact per-bucket counts of the candidates
 //    appended so far reach r below a smaller bucket (Sec. 3.3, Scan step: the dynamic upper bound
 //    of the capped buckets).  A pair with qd <= T_cur is appended to the query's candidate buffer.
@@ -149,8 +149,8 @@ __global__ __launch_bounds__(256) void swizzle_tables_kernel(const uint8_t *__re
 // The bucket of the sample's r-th smallest qd is a bound that cannot fail (the sample is part of the
 // array), but it lets r / S of all codes through.  The array's r-th smallest qd is about the sample's
 // (r S / n)-th smallest, so the bound starts at the bucket where the sample's cumulative count reaches
-// e + 8 sqrt(e) + 8 with e = r S / n (eight standard deviations of the count above its mean), or r
-// if that is smaller.  Should that bucket hold fewer than r codes of the whole array after all, the
+// e + 5 sqrt(e) + 5 with e = r S / n (five standard deviations of the count above its mean: a query in
+// ten million starts too low), or r if that is smaller.  Should that bucket hold fewer than r codes of the whole array after all, the
 // selection sees fewer than r appended candidates and has the query redone by the three-pass path.
 __global__ __launch_bounds__(256) void sample_threshold_kernel(const uint32_t *__restrict__ shist, uint32_t r,
                                                                uint64_t n_codes, int *__restrict__ t_cur)
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(256) void sample_threshold_kernel(const uint32_t *_
     uint32_t rs = r;
     if (n_codes) {                                        // 0: the sample's own r-th smallest
         const float e = static_cast<float>(r) * static_cast<float>(cum[255]) / static_cast<float>(n_codes);
-        const float want = e + 8.0f * sqrtf(e) + 8.0f;
+        const float want = e + 5.0f * sqrtf(e) + 5.0f;
         if (want < static_cast<float>(r)) rs = static_cast<uint32_t>(want) + 1u;
     }
     const uint32_t before = b ? cum[b - 1] : 0u;

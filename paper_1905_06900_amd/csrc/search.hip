@@ -8,7 +8,7 @@ namespace dcpq {
 
 struct SearchPlan {
     int chunk;
-    size_t off_qtab, off_bounds, off_cand_id, off_cand_qd, off_tables, off_scan, off_refine, total;
+    size_t off_qtab, off_bounds, off_cand_id, off_cand_qd, off_tables, tables_bytes, off_scan, off_refine, total;
 };
 
 static SearchPlan plan_search(uint64_t n_codes, int m, int nq, uint32_t r, int full_bits, int chunk_queries)
@@ -29,11 +29,13 @@ static SearchPlan plan_search(uint64_t n_codes, int m, int nq, uint32_t r, int f
     p.off_cand_id = off; off = align_up(off + sizeof(uint32_t) * static_cast<size_t>(chunk) * r, 256);
     p.off_cand_qd = off; off = align_up(off + static_cast<size_t>(chunk) * r, 256);
     // the full tables of a chunk (table mode), or the codebooks with their rows padded to whole 64-byte units
-    // (on-demand mode with rows shorter than that; 16 floats per row): the region holds the larger of the two
+    // (on-demand mode with rows shorter than that; 16 floats per row), or the sub-code planes and entries of the
+    // split on-demand mode (used only where they fit): the region holds the larger of the first two
     {
         const size_t tables = sizeof(float) * ((static_cast<size_t>(chunk) * m) << full_bits);
         const size_t padded = sizeof(float) * ((static_cast<size_t>(m) * 16) << full_bits);
-        p.off_tables = off;  off = align_up(off + (tables > padded ? tables : padded), 256);
+        p.tables_bytes = tables > padded ? tables : padded;
+        p.off_tables = off;  off = align_up(off + p.tables_bytes, 256);
     }
     // The scan and the refinement lay their scratch out for the number of queries they are given, and
     // a smaller batch does not always need less (fewer queries can mean more units or slices), so
@@ -76,17 +78,35 @@ extern "C" size_t dcpq_search_workspace_bytes(uint64_t n_codes, int m, int nq, u
     return dcpq_search_bits_workspace_bytes(n_codes, m, nq, r, kFullBits, chunk_queries);
 }
 
-// Whether pass two computes its table entries on demand (DCPQ_REFINE_DIRECT) or looks them up in full
-// tables built first (DCPQ_REFINE_TABLES).  On demand a query gathers r m centroid rows; with tables it
-// writes 2^b m entries and then makes r m scattered 4-byte lookups.  Measured on MI355X a gathered row
-// costs about 8 ps more than a table lookup (27 against 19 ps for random 16-bit sub-codes, dsub = 12)
-// and a 2^16-entry table 60 to 200 ns to build (dsub = 12 to 60), which puts the break-even near
-// r = 8000 for b = 16; the rule below scales that with the table size.
-static int refine_mode_for(int requested, int b, int dsub, uint32_t r)
+// How pass two gets its table entries: looked up in full tables built first (DCPQ_REFINE_TABLES), or computed
+// on demand, in one kernel (DCPQ_REFINE_DIRECT) or split by sub-quantizer (DCPQ_REFINE_SPLIT).  On demand a
+// query gathers r m centroid rows; with tables it writes 2^b m entries and then makes r m scattered 4-byte
+// lookups.  Measured on MI355X a gathered row costs about 8 ps more than a table lookup (27 against 19 ps for
+// random 16-bit sub-codes, dsub = 12) and a 2^16-entry table 60 to 200 ns to build (dsub = 12 to 60), which
+// puts the break-even near r = 8000 for b = 16; the rule below scales that with the table size.
+// The split form pays when the sub-codebooks that one XCD would serve (one in eight of them) fit its 4 MB
+// cache with room to spare while the codebooks as a whole do not (measured at m = 8, dsub = 12, r = 4000:
+// 2.9 times faster with 64 queries, 2.2 times with 4096; with rows of exactly 4 MB per sub-quantizer and
+// codes that follow the queries, 1.4 times slower), and the batch is not tiny; it is possible when its
+// intermediate arrays fit the table region and candidate numbers 32 bits.
+static bool split_possible(const SearchPlan &p, int m, int b, int nq, uint32_t r, const float *queries)
 {
-    (void)dsub;
-    if (requested == DCPQ_REFINE_TABLES || requested == DCPQ_REFINE_DIRECT) return requested;
-    return r <= (1u << b) / 8 ? DCPQ_REFINE_DIRECT : DCPQ_REFINE_TABLES;
+    // (its kernels read query sub-vectors 16 bytes at a time from where the caller keeps them)
+    return static_cast<uint64_t>(nq) * r < (1ull << 32) && refine_split_bytes(nq, r, m, b / 8) <= p.tables_bytes &&
+           (reinterpret_cast<uintptr_t>(queries) & 15) == 0;
+}
+
+static bool split_pays(int m, int dsub, int b, int nq, uint32_t r)
+{
+    const size_t sub = (sizeof(float) * static_cast<size_t>(dsub)) << b;
+    return sub * ((m + 7) / 8) < (4u << 20) && sub * m > (4u << 20) && static_cast<uint64_t>(nq) * r >= (1u << 16);
+}
+
+static int refine_mode_for(int requested, const SearchPlan &p, int m, int dsub, int b, int nq, uint32_t r, const float *queries)
+{
+    if (requested != DCPQ_REFINE_AUTO) return requested;
+    if (r > (1u << b) / 8) return DCPQ_REFINE_TABLES;
+    return split_possible(p, m, b, nq, r, queries) && split_pays(m, dsub, b, nq, r) ? DCPQ_REFINE_SPLIT : DCPQ_REFINE_DIRECT;
 }
 
 extern "C" int dcpq_search_bits(const float *queries, int nq, const float *codebooks, const float *derived, int m,
@@ -101,7 +121,8 @@ extern "C" int dcpq_search_bits(const float *queries, int nq, const float *codeb
     DCPQ_REQUIRE(n_codes >= 1 && n_codes < (1ull << 32), "search: n_codes out of range");
     DCPQ_REQUIRE(r >= 1 && r <= n_codes && k >= 1 && k <= r, "search: needs 1 <= k <= r <= n_codes");
     DCPQ_REQUIRE(r <= (1u << 26), "search: r=%u above the supported 2^26", r);
-    DCPQ_REQUIRE(refine_mode == DCPQ_REFINE_AUTO || refine_mode == DCPQ_REFINE_TABLES || refine_mode == DCPQ_REFINE_DIRECT,
+    DCPQ_REQUIRE(refine_mode == DCPQ_REFINE_AUTO || refine_mode == DCPQ_REFINE_TABLES || refine_mode == DCPQ_REFINE_DIRECT ||
+                     refine_mode == DCPQ_REFINE_SPLIT,
                  "search: refine_mode=%d", refine_mode);
     if (nq == 0) return DCPQ_OK;
     DCPQ_REQUIRE(queries && codebooks && derived && codes && ids && dist && workspace, "search: null pointer");
@@ -120,14 +141,23 @@ extern "C" int dcpq_search_bits(const float *queries, int nq, const float *codeb
     hipStream_t st = as_stream(stream);
     const int D = m * dsub;
     const int code_bytes = b / 8;
-    const bool direct = refine_mode_for(refine_mode, b, dsub, r) == DCPQ_REFINE_DIRECT;
-    // On demand, a candidate gathers m centroid rows; a row shorter than a 64-byte unit that does not divide it
+    const int tail = nq % p.chunk;
+    const int mode_full = refine_mode_for(refine_mode, p, m, dsub, b, p.chunk, r, queries);
+    const int mode_tail = tail ? refine_mode_for(refine_mode, p, m, dsub, b, tail, r, queries) : mode_full;
+    if (mode_full == DCPQ_REFINE_SPLIT && !split_possible(p, m, b, p.chunk, r, queries))
+        return fail(DCPQ_EINVAL, "search: DCPQ_REFINE_SPLIT: %zu bytes of sub-codes and entries per chunk do not fit the table "
+                                 "region (%zu bytes), or chunk * r reaches 2^32, or the queries are not 16-byte aligned",
+                    refine_split_bytes(p.chunk, r, m, b / 8), p.tables_bytes);
+    const bool any_split = mode_full == DCPQ_REFINE_SPLIT || mode_tail == DCPQ_REFINE_SPLIT;
+    const bool any_direct = mode_full == DCPQ_REFINE_DIRECT || mode_tail == DCPQ_REFINE_DIRECT;
+    // On demand in one kernel, a candidate gathers m centroid rows; a row shorter than a 64-byte unit that does not divide it
     // lies across two memory lines more often than it has to, so such codebooks are copied once per call into
     // rows of 16 floats (25 -> 33 MB at m = 8, dsub = 12: 30 microseconds, 6 % off the refinement).  Longer rows
     // gain nothing and the copy costs more (measured at dsub = 60), so they are read in place.
     const float *rows = codebooks;
     int cstride = dsub;
-    if (direct && dsub < 16 && 16 % dsub != 0) {
+    // (the split form reads the codebooks in place and uses the region for its own arrays: no copy then)
+    if (any_direct && !any_split && dsub < 16 && 16 % dsub != 0) {
         cstride = 16;
         int rc = launch_pad_rows(codebooks, static_cast<size_t>(m) << b, dsub, cstride, tables, st);
         if (rc) return rc;
@@ -148,7 +178,11 @@ extern "C" int dcpq_search_bits(const float *queries, int nq, const float *codeb
         if (rc) return rc;
         uint32_t *ids_c = ids + static_cast<size_t>(q0) * k;
         float *dist_c = dist + static_cast<size_t>(q0) * k;
-        if (direct) {
+        const int mode = nc == p.chunk ? mode_full : mode_tail;
+        if (mode == DCPQ_REFINE_SPLIT) {
+            rc = launch_refine_split(y, codebooks, dsub, 1u << b, codes, code_bytes, n_codes, m, cand_id, nc, r, k, ids_c, dist_c,
+                                     tables, base + p.off_refine, st);
+        } else if (mode == DCPQ_REFINE_DIRECT) {
             rc = launch_refine_direct(y, rows, dsub, cstride, 1u << b, codes, code_bytes, n_codes, m, cand_id, nc, r, k, ids_c,
                                       dist_c, base + p.off_refine, st);
         } else {
@@ -171,7 +205,9 @@ extern "C" int dcpq_search(const float *queries, int nq, const float *codebooks,
                             DCPQ_REFINE_AUTO, ids, dist, chunk_queries, workspace, workspace_bytes, stream);
 }
 
-extern "C" int dcpq_search_refine_mode(int b, int dsub, uint32_t r, int refine_mode)
+extern "C" int dcpq_search_refine_mode(int m, int dsub, int b, int nq, uint32_t r, int refine_mode)
 {
-    return refine_mode_for(refine_mode, b, dsub, r);
+    if (nq <= 0 || !m_supported(m) || !dcpq_bits_supported(b, 1) || r == 0) return refine_mode;
+    const SearchPlan p = plan_search(1, m, nq, r, b, 0);
+    return refine_mode_for(refine_mode, p, m, dsub, b, p.chunk, r, nullptr);
 }

@@ -51,6 +51,15 @@ def test_two_pass_search_with_these_bit_widths(b, bbar, m, dsub, N, Q, r):
     ids, dist = binding.refine_topk(tables, codes, cand_id, k)
     fids, fdist = binding.search(queries, cb, derived, codes, r, k, refine_mode=binding.REFINE_TABLES)
     dids, ddist = binding.search(queries, cb, derived, codes, r, k, refine_mode=binding.REFINE_DIRECT)
+    # on demand, split by sub-quantizer: the same bits as the one-kernel form; its arrays always fit the table
+    # region when r * (4 + b / 8) <= 4 * 2^b, and where they do not fit the mode is refused
+    try:
+        sids, sdist = binding.search(queries, cb, derived, codes, r, k, refine_mode=binding.REFINE_SPLIT)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(to_np(sids), to_np(dids), err_msg="split on-demand refinement, ids")
+        np.testing.assert_array_equal(to_np(sdist), to_np(ddist), err_msg="split on-demand refinement, distances")
+    except binding.DcpqError as err:
+        assert err.code == binding.EINVAL and r * (4 + b // 8) > 4 << b
     torch.cuda.synchronize()
 
     cb_np, q_np = to_np(cb), to_np(queries)

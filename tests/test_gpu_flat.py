@@ -48,8 +48,8 @@ def test_cfg0_scaled_on_demand_refinement(case0):
     # pass two with table entries computed on demand: staged and fused agree bit for bit, both match the
     # oracle, and the default mode of the fused search is this one for the shape (r <= 2^16 / 8)
     c = case0
-    assert binding.search_refine_mode(16, c.w.dsub, c.w.r) == binding.REFINE_DIRECT
-    assert binding.search_refine_mode(16, c.w.dsub, 10_000) == binding.REFINE_TABLES
+    assert binding.search_refine_mode(c.w.m, c.w.dsub, 16, c.w.Q, c.w.r) == binding.REFINE_DIRECT
+    assert binding.search_refine_mode(c.w.m, c.w.dsub, 16, c.w.Q, 10_000) == binding.REFINE_TABLES
     sids, sdist = binding.refine_direct_topk(c.queries, c.cb, c.codes, c.cand_id, c.w.k)
     fids, fdist = binding.search(c.queries, c.cb, c.derived, c.codes, c.w.r, c.w.k, chunk_queries=16)
     torch.cuda.synchronize()
@@ -58,6 +58,33 @@ def test_cfg0_scaled_on_demand_refinement(case0):
     c.check_pass_two(sids, sdist)
     # against the table mode: the same distances up to the last bit
     np.testing.assert_allclose(to_np(sdist), to_np(c.dist), rtol=2e-7)
+
+
+@pytest.mark.parametrize("cfg,N,Q,r,chunk", [(0, 90_001, 37, 1000, 16), (2, 150_001, 290, 4000, 280),
+                                             (4, 40_001, 21, 700, 0)])
+def test_split_on_demand_refinement(cfg, N, Q, r, chunk):
+    # Pass two split by sub-quantizer (m = 4: two parts of the candidates per sub-quantizer; m = 8: one
+    # sub-quantizer per slice; m = 16: two) gives the bits of the one-kernel form, with a ragged last chunk too,
+    # and matches the oracle.  The middle case is large enough for the library to pick the split form by itself
+    # for the full chunk (280 x 4000 candidates) and the one-kernel form for the last 10 queries.
+    w = small_flat(cfg, N, Q, r)
+    print("split refinement: cfg%d recipe N=%d Q=%d r=%d chunk=%d" % (cfg, N, Q, r, chunk), flush=True)
+    c = FlatCase(w, DEV)
+    dids, ddist = binding.search(c.queries, c.cb, c.derived, c.codes, r, w.k, chunk_queries=chunk,
+                                 refine_mode=binding.REFINE_DIRECT)
+    sids, sdist = binding.search(c.queries, c.cb, c.derived, c.codes, r, w.k, chunk_queries=chunk,
+                                 refine_mode=binding.REFINE_SPLIT)
+    aids, adist = binding.search(c.queries, c.cb, c.derived, c.codes, r, w.k, chunk_queries=chunk)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(sids), to_np(dids))
+    np.testing.assert_array_equal(to_np(sdist), to_np(ddist))
+    np.testing.assert_array_equal(to_np(aids), to_np(dids))
+    np.testing.assert_array_equal(to_np(adist), to_np(ddist))
+    if cfg == 2:
+        assert binding.search_refine_mode(w.m, w.dsub, 16, 280, r) == binding.REFINE_SPLIT
+        assert binding.search_refine_mode(w.m, w.dsub, 16, 10, r) == binding.REFINE_DIRECT
+    c.oracle(qsel=np.arange(0, Q, max(1, Q // 24)))
+    c.check_pass_two(sids, sdist)
 
 
 def test_fused_search_m2_with_a_ragged_last_chunk():
