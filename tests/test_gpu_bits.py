@@ -36,6 +36,9 @@ CASES = [  # (b, bbar, m, dsub, N, Q, r)
     (8, 6, 16, 4, 30_001, 11, 200),
     (8, 8, 8, 6, 30_001, 11, 200),
     (8, 4, 2, 16, 30_001, 5, 100),
+    (16, 8, 1, 8, 20_001, 7, 200),
+    (16, 8, 32, 4, 20_001, 7, 200),
+    (16, 5, 2, 8, 20_001, 7, 200),
 ]
 
 
