@@ -111,7 +111,11 @@ int dcpq_scan_query_tile(int m);
  * device work).  info (host pointer, ninfo >= 6) receives: [0] queries per tile, [1] number of tiles,
  * [2] workgroups along the codes in the single-pass launch, [3] codes per workgroup (for the three-pass
  * algorithm: codes per wavefront unit), [4] slices of a query's candidate buffer, [5] entries per slice.
- * [2], [4], [5] are 0 for the three-pass algorithm. */
+ * [2], [4], [5] are 0 for the three-pass algorithm.  With ninfo >= 10 also the sample that gives the
+ * single-pass scan its starting bounds: [6] runs of 256 codes, [7] codes between the starts of two runs,
+ * [8] 16 when the histogram pass reads one run in 16 and the single-pass kernel counts the whole sample
+ * below the bound that gives (the pilot pass, large arrays), 1 when the histogram pass reads every run,
+ * [9] the rank wanted within the sample (all 0 for the three-pass algorithm). */
 int dcpq_scan_plan(uint64_t n_codes, int m, int nq, uint32_t r, int mode, uint64_t *info, int ninfo);
 int dcpq_scan_candidates(const uint16_t *codes, uint64_t n_codes, int m, const uint8_t *qtab, int nq,
                          uint32_t r, uint32_t *cand_id, uint8_t *cand_qd, void *workspace,

@@ -241,9 +241,10 @@ SCAN_AUTO, SCAN_THREE_PASS, SCAN_TILE16, SCAN_TILE32, SCAN_TILE64 = 0, 1, 2, 3, 
 
 def scan_plan(n_codes: int, m: int, nq: int, r: int, mode: int = SCAN_AUTO) -> dict:
     """How the scan lays out its work for this problem (see dcpq_scan_plan)."""
-    info = (C.c_uint64 * 6)()
-    _check(lib().dcpq_scan_plan(n_codes, m, nq, r, mode, C.cast(info, C.c_void_p), 6))
-    keys = ("query_tile", "tiles", "blocks", "codes_per_block", "slices", "slice_cap")
+    info = (C.c_uint64 * 10)()
+    _check(lib().dcpq_scan_plan(n_codes, m, nq, r, mode, C.cast(info, C.c_void_p), 10))
+    keys = ("query_tile", "tiles", "blocks", "codes_per_block", "slices", "slice_cap", "sample_runs", "sample_stride",
+            "pilot_every", "pilot_rank")
     return dict(zip(keys, (int(v) for v in info)))
 
 

@@ -27,7 +27,9 @@
 //    scan never lets fall below the bucket of its r-th best candidate: it starts from the histogram
 //    of a strided sample of the codes, at the bucket where the sample's count reaches what r
 //    codes of the whole array would leave in a sample of that size (plus five standard
-//    deviations), and it is lowered whenever the exact per-bucket counts of the candidates
+//    deviations; when the sample is large the byte-gathering histogram kernel reads a sixteenth
+//    of it and this kernel itself, in a pilot pass, counts the whole sample below the bound that
+//    gives), and it is lowered whenever the exact per-bucket counts of the candidates
 //    appended so far reach r below a smaller bucket (Sec. 3.3, Scan step: the dynamic upper bound
 //    of the capped buckets).  A pair with qd <= T_cur is appended to the query's candidate buffer.
 //    Whatever the timing of the updates, the buffer ends up a superset of the true candidate set,
@@ -204,7 +206,7 @@ __device__ inline void transposed_low_bytes(const uint32_t (&w)[M * sizeof(CodeT
 }
 
 // Appends one candidate (rec: id in bits 0..31, qd in 32..39, query-in-tile in 40..47) to slice
-// `slice` of its query's buffer and counts it in the query's exact per-bucket histogram.  Returns the
+// `slice` of its query's buffer (unless cap = 0) and counts it in the query's exact per-bucket histogram.  Returns the
 // query when this append is one of those (every `upd`-th of the slice) after which the query's bucket
 // bound is to be recomputed, else -1.  Kept out of line: it is the rare path and would otherwise be
 // replicated at every call site.
@@ -216,17 +218,25 @@ __device__ __noinline__ int append_candidate(uint64_t rec, int q0, uint32_t slic
     const size_t cell = static_cast<size_t>(q) * nslices + slice;
     const uint32_t pos = atomicAdd(&count[cell], 1u);
     if (pos < cap) keys[cell * cap + pos] = rec & 0xFFFFFFFFFFull;
-    else atomicMin(&t_cur[q], -1);                     // slice full: stop appending, query is redone
+    else if (cap) atomicMin(&t_cur[q], -1);            // slice full: stop appending, query is redone
+    // (cap = 0: the pilot pass, which only counts)
     atomicAdd(&chist[static_cast<size_t>(q) * 256 + qd], 1u);
     return (pos + 1) % upd == 0 ? static_cast<int>(q) : -1;
 }
 
 template <int M, int QT, int WAVES, typename CodeT>
 __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
-    const CodeT *__restrict__ codes, uint64_t code_begin, uint64_t code_end, uint32_t codes_per_block,
-    const uint8_t *__restrict__ qsw, int nq, uint32_t r, uint32_t nslices, uint32_t cap, uint32_t upd,
-    uint32_t qflush, int *t_cur, uint32_t *count, uint32_t *chist, uint64_t *__restrict__ keys)
+    const CodeT *__restrict__ codes, uint64_t code_end, uint64_t block_stride, uint32_t block_groups, uint32_t total_groups,
+    uint32_t gshift, uint32_t gstride, const uint8_t *__restrict__ qsw, int nq, uint32_t r, uint32_t nslices, uint32_t cap,
+    uint32_t upd, uint32_t qflush, int *t_cur, uint32_t *count, uint32_t *chist, uint64_t *__restrict__ keys)
 {
+    // The codes of workgroup y (blockIdx.y) are 64-code groups y * block_groups ... (block_groups of them, fewer
+    // at the end: total_groups in all); group g of the workgroup starts at code
+    //   y * block_stride + (g >> gshift) * gstride + (g mod 2^gshift) * 64
+    // and ends before code_end.  The scan of the whole array is gshift = 0, gstride = 64, block_stride = 64 *
+    // block_groups (one contiguous stretch per workgroup); the pilot pass over a sample reads runs of 2^gshift
+    // groups that start every gstride codes.  cap = 0 (pilot pass): candidates are counted in chist but not
+    // stored, and a bound of 255 lets nothing through instead of everything.
     using C = FastCfg<M, QT, WAVES>;
     constexpr int PF = C::PREFETCH;
     extern __shared__ __align__(16) uint8_t smem[];
@@ -246,6 +256,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     auto start_value = [&](int q) {
         int t = -1;
         if (q < nq) t = __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (cap == 0 && t >= 255) t = -1;
         return t >= 255 ? static_cast<int>(128u * M - 0x80000000u) : static_cast<int>(128u * M - static_cast<uint32_t>(t) - 1u);
     };
     {
@@ -305,12 +316,13 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     };
     auto query_of = [&](int v) { return query_at(lane, v); };
 
-    // this workgroup's codes: a stretch of codes_per_block out of code_begin .. code_end (ids fit 32
-    // bits: the host checks n_codes)
-    const uint64_t cbeg64 = code_begin + static_cast<uint64_t>(blockIdx.y) * codes_per_block;
-    const uint32_t cbeg = static_cast<uint32_t>(cbeg64);
-    const uint32_t cend = static_cast<uint32_t>(min(code_end, cbeg64 + codes_per_block));
-    const uint32_t ngroups = cbeg64 < code_end ? (cend - cbeg + 63u) / 64u : 0u;
+    // this workgroup's codes (ids fit 32 bits: the host checks n_codes)
+    const uint32_t cbeg = static_cast<uint32_t>(static_cast<uint64_t>(blockIdx.y) * block_stride);
+    const uint32_t cend = static_cast<uint32_t>(code_end);
+    const uint32_t gfirst = blockIdx.y * block_groups;
+    const uint32_t ngroups = gfirst < total_groups ? min(block_groups, total_groups - gfirst) : 0u;
+    const uint32_t gmask = (1u << gshift) - 1u;
+    auto group_base = [&](uint32_t g) { return cbeg + (g >> gshift) * gstride + (g & gmask) * 64u; };     // for g < ngroups
 
     // Pending candidates of this wavefront: records wq[0 .. qlen), qlen <= QCAP = 64.  qlen is
     // wave-uniform (it only changes by ballot counts), so it lives in a scalar register and the queue
@@ -345,7 +357,7 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
     const uint32_t ng_w = ngroups > static_cast<uint32_t>(wave) ? (ngroups - wave + WAVES - 1) / WAVES : 0u;
     constexpr int RW = M * static_cast<int>(sizeof(CodeT)) / 4;     // words per code as stored
     auto load_group = [&](uint32_t g, uint32_t (&dst)[RW]) {
-        const uint32_t id = cbeg + g * 64u + lane;
+        const uint32_t id = group_base(g) + lane;
         if (g < ngroups && id < cend) {
             const uint8_t *src = reinterpret_cast<const uint8_t *>(codes) + static_cast<uint64_t>(id) * (4 * RW);
             if constexpr (RW % 4 == 0) {
@@ -485,8 +497,8 @@ __global__ __launch_bounds__(WAVES * 64) void scan_fast_kernel(
             sign = sign | acc[UC - 1][3];
             if (!__builtin_amdgcn_ballot_w64(sign < 0)) continue;    // uniform
             // codes in this group: fewer than 64 in the last group of the stretch, none past it
-            const uint32_t gbase = cbeg + g * 64u;
-            const int nlive = g < ngroups ? static_cast<int>(min(64u, cend - gbase)) : 0;
+            const uint32_t gbase = group_base(g);
+            const int nlive = g < ngroups && gbase < cend ? static_cast<int>(min(64u, cend - gbase)) : 0;
             // Which of the 4 UC results hold the hit(s): one compare per result, whose outcome is a lane mask
             // in scalar registers, so that the search for the (usually single) result with a hit runs on the
             // scalar unit and only that result is decoded on the vector unit.
@@ -796,12 +808,34 @@ static int launch_fast_t(const CodeT *codes, uint64_t n_codes, const uint8_t *qt
     // sample histogram -> starting bounds
     int rc = launch_sample_hist(codes, n_codes, M, qtab, nq, r, shist, p, st);
     if (rc) return rc;
-    rc = launch_sample_threshold(shist, nq, r, n_codes, t_cur, st);
-    if (rc) return rc;
-    // the scan
+    if (p.pilot) {
+        if (p.s_unit != 256) return fail(DCPQ_EINVAL, "single-pass scan: the pilot pass reads runs of 256 codes");
+        // The histogram covered one run in kPilotEvery of the sample.  It gives a bound for the pilot pass: the
+        // bucket below which the whole sample (taken as the array, its wanted rank pilot_r as r) should hold
+        // pilot_r codes with the usual slack.  The pilot pass counts every sample code at or below that bound
+        // exactly, and the starting bound of the scan is the bucket where those counts reach pilot_r -- the bucket
+        // a histogram of the whole sample would have given (255, and with it the redo path, if the counts never
+        // get there).
+        rc = launch_sample_threshold(shist, nq, p.pilot_r, p.s_count, t_cur, st);
+        if (rc) return rc;
+        DCPQ_LAUNCH(kStageScanHist, st, (scan_fast_kernel<M, QT, WAVES, CodeT>), dim3(p.ntiles, p.pilot_blocks), dim3(WAVES * 64),
+                    C::LDS_BYTES, codes, n_codes, static_cast<uint64_t>(p.pilot_runs) * p.s_stride, p.pilot_runs * (p.s_unit / 64),
+                    p.s_nunits * (p.s_unit / 64), 2u, static_cast<uint32_t>(p.s_stride), qsw, nq, p.pilot_r, p.slices, 0u, 16u, 4u,
+                    t_cur, fcount, chist, fkeys);
+        DCPQ_CHECK_LAUNCH("scan_fast_kernel<pilot>");
+        rc = launch_sample_threshold(chist, nq, p.pilot_r, 0, t_cur, st);      // 0: the counted codes' own pilot_r-th smallest
+        if (rc) return rc;
+        rc = launch_zero_words(reinterpret_cast<uint32_t *>(base + p.off_fzero), p.fzero_bytes / sizeof(uint32_t), st);
+        if (rc) return rc;
+    } else {
+        rc = launch_sample_threshold(shist, nq, r, n_codes, t_cur, st);
+        if (rc) return rc;
+    }
+    // the scan: one contiguous stretch of codes per workgroup
     DCPQ_LAUNCH(kStageScanFast, st, (scan_fast_kernel<M, QT, WAVES, CodeT>), dim3(p.ntiles, p.fblocks), dim3(WAVES * 64),
-                C::LDS_BYTES, codes, static_cast<uint64_t>(0), n_codes, p.codes_per_block, qsw, nq, r, p.slices, p.cap, p.upd,
-                p.qflush, t_cur, fcount, chist, fkeys);
+                C::LDS_BYTES, codes, n_codes, static_cast<uint64_t>(p.codes_per_block), p.codes_per_block / 64,
+                static_cast<uint32_t>((n_codes + 63) / 64), 0u, 64u, qsw, nq, r, p.slices, p.cap, p.upd, p.qflush, t_cur, fcount,
+                chist, fkeys);
     DCPQ_CHECK_LAUNCH("scan_fast_kernel");
     // exact selection + list of queries to redo
     rc = launch_fast_select(fkeys, fcount, chist, nq, r, p.slices, p.cap, p.sortcap, n_codes, fsort, cand_id, cand_qd, flags, st);

@@ -21,6 +21,8 @@ inline uint32_t next_pow2(uint32_t x)
 // cursors, which keeps same-address atomics (they serialize in the L2) off the critical path.
 constexpr int kFastSlices = 16;      // at most; fewer when there are fewer workgroups along the codes
 
+constexpr uint32_t kPilotEvery = 16;
+
 struct ScanPlan {
     // three-pass path
     uint32_t unit;        // codes scanned by one wavefront
@@ -46,6 +48,14 @@ struct ScanPlan {
     uint32_t sortcap;         // keys the final selection can sort (power of two)
     uint32_t s_unit, s_nunits;    // sample: s_nunits runs of s_unit codes ...
     uint64_t s_stride;            // ... starting every s_stride codes
+    // pilot pass (large arrays): the histogram pass reads only every kPilotEvery-th run of the sample, and the
+    // sample itself goes through the single-pass kernel, counting only
+    bool pilot;
+    uint32_t s1_nunits;           // runs the histogram pass reads
+    uint64_t s_count;             // codes in the sample
+    uint32_t pilot_r;             // rank wanted within the sample: what r codes of the array leave in it, plus slack
+    uint32_t pilot_blocks;        // workgroups per tile of the pilot pass ...
+    uint32_t pilot_runs;          // ... and sample runs per workgroup
     size_t off_fzero, fzero_bytes;   // fcount, chist, shist, nflag: cleared together
     size_t off_fcount;    // uint32 [nq][slices]
     size_t off_chist;     // uint32 [nq][256]

@@ -344,16 +344,40 @@ def test_scan_large_array_estimated_starting_bound(Q):
     scan_vs_oracle(codes, qtab, r, modes=(binding.SCAN_AUTO, binding.SCAN_TILE16, binding.SCAN_TILE64))
 
 
-def test_scan_estimated_bound_too_low_is_redone():
+def test_scan_pilot_pass_starting_bound():
+    """A batch large enough for the sample to be read in two stages: the histogram pass over one run in 16, then
+    the single-pass kernel itself counting the whole sample below the bound that gives (runs addressed by
+    stride, a last run cut by the end of the array is possible, nothing stored), then the scan proper."""
+    rng = np.random.default_rng(4242)
+    N, Q, r = 1_200_003, 1000, 700
+    for mode in (binding.SCAN_AUTO, binding.SCAN_TILE16, binding.SCAN_TILE32):
+        assert binding.scan_plan(N, 8, Q, r, mode)["pilot_every"] == 16
+    codes = rng.integers(0, 65536, size=(N, 8)).astype(np.uint16)
+    qtab = rng.integers(0, 40, size=(Q, 8, 256)).astype(np.uint8)
+    qtab[5] = 0                       # every code ties at 0
+    qtab[6] = 255                     # every code saturates
+    print("scan pilot-pass case N=%d Q=%d r=%d" % (N, Q, r), flush=True)
+    scan_vs_oracle(codes, qtab, r, modes=(binding.SCAN_AUTO, binding.SCAN_TILE16, binding.SCAN_TILE32))
+
+
+@pytest.mark.parametrize("N,Q,pilot", [(4_200_003, 130, False), (300_003, 1000, True)])
+def test_scan_estimated_bound_too_low_is_redone(N, Q, pilot):
     """The estimated starting bound fails when the sample misrepresents the array: here the near codes sit
     exactly in the runs of 256 codes, evenly spread, that the sample reads, so the estimate puts r codes
     below a bucket that holds fewer in the whole array.  Such queries (the even ones here; the odd ones'
     tables spread the near codes over half as many buckets, so their first bucket does hold r) must come
-    out exact all the same: the selection sees fewer than r candidates and has them redone."""
+    out exact all the same: the selection sees fewer than r candidates and has them redone.  Both ways of
+    reading the sample are covered."""
     rng = np.random.default_rng(5150)
-    N, r, Q = 4_200_003, 700, 6
-    runs = 65536 // 256
-    stride = N // runs
+    r = 700
+    plan = binding.scan_plan(N, 8, Q, r)
+    runs, stride = plan["sample_runs"], plan["sample_stride"]
+    # a sample well inside the array; with the larger batch it is read in two stages (histogram of one run in 16,
+    # then the pilot pass of the single-pass kernel), with the smaller one by the histogram pass alone
+    assert runs * 256 * 4 <= N and plan["pilot_every"] == (16 if pilot else 1)
+    # the near codes (all in the sample) spread over 100 buckets for the even queries: fewer than r in the first
+    # bucket, which is nevertheless where the estimate starts (it expects r * sample / N + slack codes there)
+    assert runs * 256 / 100 < r < runs * 256 / 50
     pos = (np.arange(runs, dtype=np.int64)[:, None] * stride + np.arange(256)[None, :]).ravel()
     codes = rng.integers(0, 65536, size=(N, 8)).astype(np.uint16)
     low0 = rng.integers(200, 256, size=N)
