@@ -302,6 +302,7 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(const float *__restrict__
                                                       uint32_t r, const uint32_t *__restrict__ qmin_bits,
                                                       float *__restrict__ bounds)
 {
+    extern __shared__ __align__(16) float rho[];   // D floats: the query minus the centroid of the list being walked
     __shared__ uint64_t start[kIvfMaxProbe + 1];   // exclusive prefix of the list sizes in probe order
     __shared__ int lst[kIvfMaxProbe];
     __shared__ float red[4];
@@ -318,29 +319,44 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(const float *__restrict__
     const uint64_t total = start[nprobe];
     const uint32_t n_first = static_cast<uint32_t>(total < r ? total : r);
     const float *y = queries + static_cast<size_t>(q) * D;
+    const bool vec4 = (dsub & 3) == 0;               // centroid rows of whole 16-byte vectors (derived is 16-byte aligned)
     float hi = -INFINITY;
-    for (uint32_t i = tid; i < n_first; i += 256) {
-        int p = 0;                                    // list holding the i-th code of the walk:
-        for (int lo = 0, up = nprobe; ;) {            // the first p with start[p + 1] > i (skips empty lists)
-            if (lo >= up) { p = lo; break; }
-            const int mid = (lo + up) / 2;
-            if (start[mid + 1] <= i) lo = mid + 1; else up = mid;
-        }
+    // The walk takes the lists in probe order; the codes of one list share the residual of the query against
+    // that list's centroid, which the workgroup works out once per list (the walk seldom leaves the first one).
+    for (int p = 0; p < nprobe && start[p] < n_first; ++p) {              // uniform
+        const uint32_t lo = static_cast<uint32_t>(start[p]);
+        const uint32_t up = static_cast<uint32_t>(start[p + 1] < n_first ? start[p + 1] : n_first);
+        if (up == lo) continue;                                           // an empty list (uniform)
         const int l = lst[p];
-        const uint16_t *c = codes + (static_cast<size_t>(offsets[l]) + (i - start[p])) * m;
         const float *cl = coarse + static_cast<size_t>(l) * D;
-        float d = 0.0f;
-        for (int j = 0; j < m; ++j) {
-            const float *cen = derived + (static_cast<size_t>(j) * kSmallSize + (c[j] & 255)) * dsub;
-            float acc = 0.0f;
-            for (int t = 0; t < dsub; ++t) {
-                const float rho = __fsub_rn(y[j * dsub + t], cl[j * dsub + t]);
-                const float diff = __fsub_rn(rho, cen[t]);
-                acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+        __syncthreads();                                                  // the previous list's residual is no longer read
+        for (int t = tid; t < D; t += 256) rho[t] = __fsub_rn(y[t], cl[t]);
+        __syncthreads();
+        for (uint32_t i = lo + tid; i < up; i += 256) {
+            const uint16_t *c = codes + (static_cast<size_t>(offsets[l]) + (i - lo)) * m;
+            float d = 0.0f;
+            for (int j = 0; j < m; ++j) {
+                const float *cen = derived + (static_cast<size_t>(j) * kSmallSize + (c[j] & 255)) * dsub;
+                const float *rj = rho + j * dsub;
+                float acc = 0.0f;
+                if (vec4) {
+                    for (int t = 0; t < dsub; t += 4) {
+                        const float4 cv = *reinterpret_cast<const float4 *>(cen + t);
+                        const float d0 = __fsub_rn(rj[t], cv.x), d1 = __fsub_rn(rj[t + 1], cv.y);
+                        const float d2 = __fsub_rn(rj[t + 2], cv.z), d3 = __fsub_rn(rj[t + 3], cv.w);
+                        acc = __fadd_rn(acc, __fmul_rn(d0, d0)); acc = __fadd_rn(acc, __fmul_rn(d1, d1));
+                        acc = __fadd_rn(acc, __fmul_rn(d2, d2)); acc = __fadd_rn(acc, __fmul_rn(d3, d3));
+                    }
+                } else {
+                    for (int t = 0; t < dsub; ++t) {
+                        const float diff = __fsub_rn(rj[t], cen[t]);
+                        acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                    }
+                }
+                d = j == 0 ? acc : __fadd_rn(d, acc);
             }
-            d = j == 0 ? acc : __fadd_rn(d, acc);
+            hi = fmaxf(hi, d);
         }
-        hi = fmaxf(hi, d);
     }
     hi = block_reduce(hi, true, red);
     if (tid == 0) {
@@ -1005,7 +1021,7 @@ extern "C" int dcpq_ivf_build_small_tables(const float *queries, int nq, const f
     DCPQ_LAUNCH(kStageIvfTables, st, ivf_tables_kernel<0>, tgrid, dim3(256), lds, queries, coarse, probe, nprobe,
                 derived, m, dsub, qmin_bits, bounds, qtab, keep);
     DCPQ_CHECK_LAUNCH("ivf_tables_kernel<min>");
-    DCPQ_LAUNCH(kStageIvfTables, st, ivf_qmax_kernel, dim3(nq), dim3(256), 0, queries, coarse, probe, nprobe, derived, m, dsub,
+    DCPQ_LAUNCH(kStageIvfTables, st, ivf_qmax_kernel, dim3(nq), dim3(256), sizeof(float) * m * dsub, queries, coarse, probe, nprobe, derived, m, dsub,
                 codes, offsets, r, qmin_bits, bounds);
     DCPQ_CHECK_LAUNCH("ivf_qmax_kernel");
     if (keep) {
