@@ -360,6 +360,18 @@ def test_scan_pilot_pass_starting_bound():
     scan_vs_oracle(codes, qtab, r, modes=(binding.SCAN_AUTO, binding.SCAN_TILE16, binding.SCAN_TILE32))
 
 
+@pytest.mark.parametrize("m,Q", [(4, 2000), (16, 500), (32, 250)])
+def test_scan_pilot_pass_other_code_widths(m, Q):
+    """The pilot pass with the dense matrix instruction (m = 4) and with the 32- and 16-query tiles of m = 16, 32."""
+    rng = np.random.default_rng(4300 + m)
+    N, r = 300_007, 700
+    assert binding.scan_plan(N, m, Q, r)["pilot_every"] == 16
+    codes = rng.integers(0, 65536, size=(N, m)).astype(np.uint16)
+    qtab = rng.integers(0, 320 // m, size=(Q, m, 256)).astype(np.uint8)
+    print("scan pilot-pass case m=%d N=%d Q=%d r=%d" % (m, N, Q, r), flush=True)
+    scan_vs_oracle(codes, qtab, r, modes=(binding.SCAN_AUTO,))
+
+
 @pytest.mark.parametrize("N,Q,pilot", [(4_200_003, 130, False), (300_003, 1000, True)])
 def test_scan_estimated_bound_too_low_is_redone(N, Q, pilot):
     """The estimated starting bound fails when the sample misrepresents the array: here the near codes sit
