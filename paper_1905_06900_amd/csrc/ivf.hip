@@ -24,6 +24,8 @@ namespace dcpq {
 
 constexpr int kIvfUnitsPerQuery = 1024;   // upper bound of scan units per query (unit size adapts)
 constexpr int kIvfMaxProbe = 512;         // nprobe supported by the per-query planning kernels
+constexpr uint32_t kIvfSampleStep = 16;   // the first 1 / kIvfSampleStep of every probed list is the sample that gives the scan its starting bounds
+constexpr int kIvfSampleUnits = kIvfMaxProbe + kIvfUnitsPerQuery / static_cast<int>(kIvfSampleStep);   // sample units a query can have
 
 struct IvfUnit {
     uint64_t begin;    // first code of the unit (global position)
@@ -373,10 +375,12 @@ __global__ __launch_bounds__(256) void ivf_qmax_kernel(const float *__restrict__
 __global__ __launch_bounds__(256) void ivf_plan_kernel(const int32_t *__restrict__ probe, int nprobe,
                                                       const int64_t *__restrict__ offsets, uint32_t r,
                                                       IvfUnit *__restrict__ units, uint32_t *__restrict__ nunits,
-                                                      uint32_t *__restrict__ count)
+                                                      uint32_t *__restrict__ count, IvfUnit *__restrict__ sunits,
+                                                      uint32_t *__restrict__ nsunits, uint32_t *__restrict__ probed)
 {
     __shared__ uint64_t key[kIvfMaxProbe];         // (list id << 32) | probe position
     __shared__ uint32_t ubase[kIvfMaxProbe + 1];
+    __shared__ uint32_t sbase[kIvfMaxProbe + 1];   // the same for the sample units
     __shared__ uint64_t s_total;
     __shared__ uint32_t s_unit;
     const int q = blockIdx.x, tid = threadIdx.x;
@@ -397,19 +401,41 @@ __global__ __launch_bounds__(256) void ivf_plan_kernel(const int32_t *__restrict
         uint64_t unit = (total + (want - nprobe) - 1) / (want - nprobe);
         unit = (unit + 63) / 64 * 64;
         if (unit < 256) unit = 256;
-        uint32_t u = 0;
+        uint32_t u = 0, su = 0;
         for (int s = 0; s < nprobe; ++s) {
             const int l = static_cast<int>(key[s] >> 32);
+            const uint64_t size = static_cast<uint64_t>(offsets[l + 1] - offsets[l]);
             ubase[s] = u;
-            u += static_cast<uint32_t>((static_cast<uint64_t>(offsets[l + 1] - offsets[l]) + unit - 1) / unit);
+            u += static_cast<uint32_t>((size + unit - 1) / unit);
+            sbase[s] = su;                                   // (at most one unit per list and one per kIvfSampleStep scan units)
+            su += static_cast<uint32_t>(((size + kIvfSampleStep - 1) / kIvfSampleStep + unit - 1) / unit);
         }
         ubase[nprobe] = u;
+        sbase[nprobe] = su;
+        nsunits[q] = su;
         s_total = total; s_unit = static_cast<uint32_t>(unit);
         nunits[q] = u;
         count[q] = static_cast<uint32_t>(total < r ? total : r);
+        probed[q] = static_cast<uint32_t>(total < 0xFFFFFFFFull ? total : 0xFFFFFFFFull);     // codes in the probed lists
     }
     __syncthreads();
     const uint32_t unit = s_unit;
+    // The sample that gives the scan its starting bound: the first ceil(size / kIvfSampleStep) codes of every probed
+    // list (a list keeps its codes in no order that matters here), so that every list is in it with the same weight; cut
+    // into units no longer than the scan's, so that a long list's share is not one wavefront's work.
+    for (int s = 0; s < nprobe; ++s) {
+        const int l = static_cast<int>(key[s] >> 32);
+        const uint64_t lo = static_cast<uint64_t>(offsets[l]), size = static_cast<uint64_t>(offsets[l + 1]) - lo;
+        const uint64_t part = (size + kIvfSampleStep - 1) / kIvfSampleStep;
+        const uint32_t nu = sbase[s + 1] - sbase[s];
+        for (uint32_t c = tid; c < nu; c += 256) {
+            IvfUnit rec;
+            rec.begin = lo + static_cast<uint64_t>(c) * unit;
+            rec.count = static_cast<uint32_t>(min(static_cast<uint64_t>(unit), part - static_cast<uint64_t>(c) * unit));
+            rec.p = static_cast<uint32_t>(key[s] & 0xFFFFFFFFu);
+            sunits[static_cast<size_t>(q) * kIvfSampleUnits + sbase[s] + c] = rec;
+        }
+    }
     for (int s = 0; s < nprobe; ++s) {
         const int l = static_cast<int>(key[s] >> 32);
         const uint64_t lo = static_cast<uint64_t>(offsets[l]), size = static_cast<uint64_t>(offsets[l + 1]) - lo;
@@ -558,7 +584,7 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const CodeT *__restrict__
 
 // The same scan in ONE pass over the probed lists (each pass reads every probed code from HBM, and no
 // two queries share them, so passes are what the scan costs).  As in the flat single pass, a query has
-// a running bucket bound, initialised from the histogram of a sample (every kIvfSampleStep-th unit) and
+// a running bucket bound, initialised from the histogram of a sample (the first 1 / kIvfSampleStep of every list) and
 // lowered as exact per-bucket counts of appended candidates accumulate; pairs at or below the bound are
 // appended to the query's sliced buffer, the exact r are selected afterwards, and a query whose buffer
 // overflows (or whose lists hold fewer than r codes) is redone by the three passes above.
@@ -570,7 +596,6 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const CodeT *__restrict__
 // are looked up), in two sets of kIvfRawWords words per lane; while one set is processed the loads
 // of the next are under way, the first of them issued together with the load of the unit's tables,
 // and nothing in the kernel waits for another wavefront.
-constexpr uint32_t kIvfSampleStep = 16;
 constexpr int kIvfRawWords = 16;         // registers per lane and set that hold codes in flight
 
 // The bytes of code i as stored, in RW words (a narrower code is zero-extended).
@@ -605,8 +630,9 @@ __device__ inline uint32_t low_byte_of(const uint32_t (&w)[RW], int j)
     else return (w[j >> 2] >> (8 * (j & 3))) & 255u;
 }
 
-// SAMPLE: the pass that finds the starting bounds -- only every kIvfSampleStep-th unit is read, nothing
-// is appended, and `count` is the per-query histogram of the integer distances ([nq][256]).
+// SAMPLE: the pass that finds the starting bounds -- `units` and `nunits` are the sample's (the first
+// 1 / kIvfSampleStep of every probed list), nothing is appended, and `count` is the per-query histogram of the
+// integer distances ([nq][256]).
 template <int M, typename CodeT, bool SAMPLE>
 __global__ __launch_bounds__(256) void ivf_scan_single_kernel(const CodeT *__restrict__ codes,
                                                              const IvfUnit *__restrict__ units,
@@ -623,8 +649,8 @@ __global__ __launch_bounds__(256) void ivf_scan_single_kernel(const CodeT *__res
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int q = blockIdx.x;
     const uint32_t u = blockIdx.y * 4 + wave;
+    // (SAMPLE: `units` and `nunits` are the sample's, kIvfSampleUnits records per query)
     if (u >= nunits[q]) return;                              // uniform per wavefront; the kernel has no workgroup barrier
-    if (SAMPLE && u % kIvfSampleStep != 0) return;
     uint8_t *tab = smem + wave * (M * 256);                                           // [M][256]
     uint64_t *wq = reinterpret_cast<uint64_t *>(smem + 4 * M * 256) + wave * 64;      // pending candidates
     uint32_t *lhist = reinterpret_cast<uint32_t *>(smem + 4 * M * 256) + wave * 256;  // SAMPLE: this wavefront's histogram
@@ -632,7 +658,7 @@ __global__ __launch_bounds__(256) void ivf_scan_single_kernel(const CodeT *__res
 #pragma unroll
         for (int b = 0; b < 4; ++b) lhist[lane + 64 * b] = 0;
     }
-    const IvfUnit un = units[static_cast<size_t>(q) * kIvfUnitsPerQuery + u];
+    const IvfUnit un = units[static_cast<size_t>(q) * (SAMPLE ? kIvfSampleUnits : kIvfUnitsPerQuery) + u];
     if (un.count == 0) return;                               // uniform (the planner makes no empty units)
 
     auto load_set = [&](uint32_t base0, uint32_t (&w)[GPB][RW]) {
@@ -833,7 +859,7 @@ __global__ __launch_bounds__(1024) void ivf_refine_kernel(const float *__restric
 struct IvfScanPlan {
     size_t off_hist, off_thr, off_counter, off_nunits, zero_bytes, off_tie, off_units, off_keys, off_spill, total;
     // single pass: sample histogram, cursors, appended histogram (cleared with the rest); bounds, flags, buffers
-    size_t off_shist, off_fcount, off_chist, off_tcur, off_flags, off_fkeys, off_fsort;
+    size_t off_shist, off_fcount, off_chist, off_tcur, off_flags, off_fkeys, off_fsort, off_probed, off_sunits, off_nsunits;
     uint32_t cap, upd, qflush, sortcap;
 };
 
@@ -869,6 +895,9 @@ static IvfScanPlan plan_ivf_scan(int nq, uint32_t r)
     p.sortcap = next_pow2(2 * r) < kSortLdsKeys ? kSortLdsKeys : next_pow2(2 * r);
     p.off_tcur = off;    off = align_up(off + sizeof(int32_t) * Q, 256);
     p.off_flags = off;   off = align_up(off + sizeof(uint32_t) * Q, 256);
+    p.off_probed = off;  off = align_up(off + sizeof(uint32_t) * Q, 256);
+    p.off_sunits = off;  off = align_up(off + sizeof(IvfUnit) * Q * kIvfSampleUnits, 256);
+    p.off_nsunits = off; off = align_up(off + sizeof(uint32_t) * Q, 256);
     p.off_fkeys = off;   off = align_up(off + sizeof(uint64_t) * Q * kFastSlices * p.cap, 256);
     p.off_fsort = off;
     if (p.sortcap > kSortLdsKeys) off = align_up(off + sizeof(uint64_t) * Q * p.sortcap, 256);
@@ -894,7 +923,11 @@ static int ivf_scan_m(const CodeT *codes, const int64_t *offsets, const int32_t 
     if (rc) return rc;
     rc = launch_fill_u64(keys, static_cast<size_t>(nq) * r, ~0ull, st);     // unused slots read as padding
     if (rc) return rc;
-    DCPQ_LAUNCH(kStageIvf, st, ivf_plan_kernel, dim3(nq), dim3(256), 0, probe, nprobe, offsets, r, units, nunits, count);
+    uint32_t *probed = reinterpret_cast<uint32_t *>(base + p.off_probed);
+    IvfUnit *sunits = reinterpret_cast<IvfUnit *>(base + p.off_sunits);
+    uint32_t *nsunits = reinterpret_cast<uint32_t *>(base + p.off_nsunits);
+    DCPQ_LAUNCH(kStageIvf, st, ivf_plan_kernel, dim3(nq), dim3(256), 0, probe, nprobe, offsets, r, units, nunits, count, sunits,
+                nsunits, probed);
     DCPQ_CHECK_LAUNCH("ivf_plan_kernel");
     const dim3 grid(kIvfUnitsPerQuery / 4, nq < kIvfRedoRows ? nq : kIvfRedoRows);
     const size_t lds_tab = 4 * M * 256;
@@ -905,11 +938,15 @@ static int ivf_scan_m(const CodeT *codes, const int64_t *offsets, const int32_t 
     uint32_t *flags = reinterpret_cast<uint32_t *>(base + p.off_flags);
     uint64_t *fkeys = reinterpret_cast<uint64_t *>(base + p.off_fkeys);
     uint64_t *fsort = reinterpret_cast<uint64_t *>(base + p.off_fsort);
-    // single pass: bounds from a sample of the units, one pass over all of them, exact selection
-    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_single_kernel<M, CodeT, true>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
-                lds_tab + 4 * 256 * 4, codes, units, nunits, qtab, nprobe, r, p.cap, p.upd, p.qflush, t_cur, shist, chist, fkeys);
+    // single pass: bounds from a sample of the probed lists, one pass over all their units, exact selection
+    DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_single_kernel<M, CodeT, true>),
+                dim3(nq, (nprobe + kIvfUnitsPerQuery / kIvfSampleStep + 3) / 4), dim3(256),
+                lds_tab + 4 * 256 * 4, codes, sunits, nsunits, qtab, nprobe, r, p.cap, p.upd, p.qflush, t_cur, shist, chist, fkeys);
     DCPQ_CHECK_LAUNCH("ivf_scan_single_kernel<sample>");
-    rc = launch_sample_threshold(shist, nq, r, 0, t_cur, st);     // 0: the sample's own r-th smallest
+    // As in the flat scan, the bound starts at the bucket where the sample's count reaches what r codes of all the
+    // query's probed codes would leave in a sample of that size, plus slack; a query whose bucket holds fewer than
+    // r codes after all is flagged by the selection and redone below.
+    rc = launch_sample_threshold(shist, nq, r, 0, t_cur, st, probed);
     if (rc) return rc;
     DCPQ_LAUNCH(kStageIvfScan, st, (ivf_scan_single_kernel<M, CodeT, false>), dim3(nq, kIvfUnitsPerQuery / 4), dim3(256),
                 lds_tab + 4 * 64 * 8, codes, units, nunits, qtab, nprobe, r, p.cap, p.upd, p.qflush, t_cur, fcount, chist,

@@ -155,7 +155,8 @@ __global__ __launch_bounds__(256) void swizzle_tables_kernel(const uint8_t *__re
 // ten million starts too low), or r if that is smaller.  Should that bucket hold fewer than r codes of the whole array after all, the
 // selection sees fewer than r appended candidates and has the query redone by the three-pass path.
 __global__ __launch_bounds__(256) void sample_threshold_kernel(const uint32_t *__restrict__ shist, uint32_t r,
-                                                               uint64_t n_codes, int *__restrict__ t_cur)
+                                                               uint64_t n_codes, const uint32_t *__restrict__ n_each,
+                                                               int *__restrict__ t_cur)
 {
     __shared__ uint32_t cum[256];
     const int q = blockIdx.x, b = threadIdx.x;
@@ -168,6 +169,7 @@ __global__ __launch_bounds__(256) void sample_threshold_kernel(const uint32_t *_
         __syncthreads();
     }
     uint32_t rs = r;
+    if (n_each) n_codes = n_each[q];                      // every query scans its own codes (probed lists)
     if (n_codes) {                                        // 0: the sample's own r-th smallest
         const float e = static_cast<float>(r) * static_cast<float>(cum[255]) / static_cast<float>(n_codes);
         const float want = e + 5.0f * sqrtf(e) + 5.0f;
@@ -845,9 +847,10 @@ static int launch_fast_t(const CodeT *codes, uint64_t n_codes, const uint8_t *qt
     return DCPQ_OK;
 }
 
-int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, uint64_t n_codes, int *t_cur, hipStream_t st)
+int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, uint64_t n_codes, int *t_cur, hipStream_t st,
+                            const uint32_t *n_each)
 {
-    DCPQ_LAUNCH(kStageSelect, st, sample_threshold_kernel, dim3(nq), dim3(256), 0, shist, r, n_codes, t_cur);
+    DCPQ_LAUNCH(kStageSelect, st, sample_threshold_kernel, dim3(nq), dim3(256), 0, shist, r, n_codes, n_each, t_cur);
     DCPQ_CHECK_LAUNCH("sample_threshold_kernel");
     return DCPQ_OK;
 }

@@ -85,7 +85,9 @@ int launch_scan_fast(const CodeT *codes, uint64_t n_codes, int m, const uint8_t 
 
 // Steps of the single-pass selection that the inverted-list variant reuses.
 // n_codes: size of the array the sample was drawn from (the sample's own size is the histogram's total)
-int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, uint64_t n_codes, int *t_cur, hipStream_t st);
+// n_each (optional): the number of codes each query scans, where it is not the same n_codes for all of them
+int launch_sample_threshold(const uint32_t *shist, int nq, uint32_t r, uint64_t n_codes, int *t_cur, hipStream_t st,
+                            const uint32_t *n_each = nullptr);
 // n_ids: the ids are below this (0 = unknown)
 int launch_fast_select(const uint64_t *keys, const uint32_t *count, const uint32_t *chist, int nq, uint32_t r,
                        uint32_t nslices, uint32_t cap, uint32_t sortcap, uint64_t n_ids, uint64_t *spill, uint32_t *cand_id,
