@@ -24,7 +24,7 @@ namespace dcpq {
 
 constexpr int kIvfUnitsPerQuery = 1024;   // upper bound of scan units per query (unit size adapts)
 constexpr int kIvfMaxProbe = 512;         // nprobe supported by the per-query planning kernels
-constexpr uint32_t kIvfSampleStep = 16;   // the first 1 / kIvfSampleStep of every probed list is the sample that gives the scan its starting bounds
+constexpr uint32_t kIvfSampleStep = 32;   // the first 1 / kIvfSampleStep of every probed list is the sample that gives the scan its starting bounds
 constexpr int kIvfSampleUnits = kIvfMaxProbe + kIvfUnitsPerQuery / static_cast<int>(kIvfSampleStep);   // sample units a query can have
 
 struct IvfUnit {
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(256) void ivf_plan_kernel(const int32_t *__restrict
     __shared__ uint64_t key[kIvfMaxProbe];         // (list id << 32) | probe position
     __shared__ uint32_t ubase[kIvfMaxProbe + 1];
     __shared__ uint32_t sbase[kIvfMaxProbe + 1];   // the same for the sample units
-    __shared__ uint64_t s_total;
+    __shared__ uint64_t lsize[kIvfMaxProbe];       // codes in the s-th probed list (lists in id order)
     __shared__ uint32_t s_unit;
     const int q = blockIdx.x, tid = threadIdx.x;
     uint32_t np2 = 1;
@@ -390,9 +390,15 @@ __global__ __launch_bounds__(256) void ivf_plan_kernel(const int32_t *__restrict
         key[p] = p < static_cast<uint32_t>(nprobe)
                      ? make_key(static_cast<uint32_t>(probe[static_cast<size_t>(q) * nprobe + p]), p) : ~0ull;
     bitonic_sort(key, np2);
+    // (the list sizes are fetched by all threads at once: the planning below is one thread's walk over them)
+    for (int s = tid; s < nprobe; s += 256) {
+        const int l = static_cast<int>(key[s] >> 32);
+        lsize[s] = static_cast<uint64_t>(offsets[l + 1] - offsets[l]);
+    }
+    __syncthreads();
     if (tid == 0) {
         uint64_t total = 0;
-        for (int s = 0; s < nprobe; ++s) { const int l = static_cast<int>(key[s] >> 32); total += static_cast<uint64_t>(offsets[l + 1] - offsets[l]); }
+        for (int s = 0; s < nprobe; ++s) total += lsize[s];
         // three units per probed list on average, and at least 512 less one per list in all (measured: fewer,
         // longer units leave the chip unevenly loaded, more of them pay the latency of a wavefront's first
         // loads too often); never more than the unit table holds
@@ -403,8 +409,7 @@ __global__ __launch_bounds__(256) void ivf_plan_kernel(const int32_t *__restrict
         if (unit < 256) unit = 256;
         uint32_t u = 0, su = 0;
         for (int s = 0; s < nprobe; ++s) {
-            const int l = static_cast<int>(key[s] >> 32);
-            const uint64_t size = static_cast<uint64_t>(offsets[l + 1] - offsets[l]);
+            const uint64_t size = lsize[s];
             ubase[s] = u;
             u += static_cast<uint32_t>((size + unit - 1) / unit);
             sbase[s] = su;                                   // (at most one unit per list and one per kIvfSampleStep scan units)
@@ -413,7 +418,7 @@ __global__ __launch_bounds__(256) void ivf_plan_kernel(const int32_t *__restrict
         ubase[nprobe] = u;
         sbase[nprobe] = su;
         nsunits[q] = su;
-        s_total = total; s_unit = static_cast<uint32_t>(unit);
+        s_unit = static_cast<uint32_t>(unit);
         nunits[q] = u;
         count[q] = static_cast<uint32_t>(total < r ? total : r);
         probed[q] = static_cast<uint32_t>(total < 0xFFFFFFFFull ? total : 0xFFFFFFFFull);     // codes in the probed lists
@@ -674,23 +679,20 @@ __global__ __launch_bounds__(256) void ivf_scan_single_kernel(const CodeT *__res
         const int t = __hip_atomic_load(&t_cur[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         return t >= 255 ? 0x7fffffff : t;
     };
-    // the unit's tables and its first codes travel together
-    constexpr int TV = M * 256 / 16 / 64 > 0 ? M * 256 / 16 / 64 : 1;   // 16-byte words of the tables per lane
-    uint4 tv[TV];
-    {
-        const uint4 *src = reinterpret_cast<const uint4 *>(qtab + (static_cast<size_t>(q) * nprobe + un.p) * M * 256);
-#pragma unroll
-        for (int v = 0; v < TV; ++v)
-            if (lane + 64 * v < M * 256 / 16) tv[v] = src[lane + 64 * v];
-    }
+    // The unit's first codes and its tables travel together: the code loads are issued first, the table words
+    // follow them and go from their registers straight to LDS.  (Held in an array across the code loads, the table
+    // words were put in scratch memory by the compiler: 2 KB written and read back per wavefront, a gigabyte of
+    // traffic per batch at 1024 queries x 64 lists.)
     uint32_t wa[GPB][RW], wb[GPB][RW];
     load_set(0, wa);
     int T = load_bound();
     {
+        constexpr int NTW = M * 256 / 16;                                // 16-byte words of the tables
+        const uint4 *src = reinterpret_cast<const uint4 *>(qtab + (static_cast<size_t>(q) * nprobe + un.p) * M * 256);
         uint4 *dst = reinterpret_cast<uint4 *>(tab);
 #pragma unroll
-        for (int v = 0; v < TV; ++v)
-            if (lane + 64 * v < M * 256 / 16) dst[lane + 64 * v] = tv[v];
+        for (int v = 0; v < (NTW + 63) / 64; ++v)
+            if (NTW % 64 == 0 || lane + 64 * v < NTW) dst[lane + 64 * v] = src[lane + 64 * v];
     }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
