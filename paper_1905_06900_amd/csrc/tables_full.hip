@@ -29,9 +29,13 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
 {
     __shared__ double ny[kTileQ];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // The query tile varies fastest over the workgroups: those that run at the same time then share their
+    // centroids (which they fetch through the caches of 8 XCDs, not once per query tile from memory: 1.1 GB ->
+    // about 0.3 GB for 1024 queries x 65536 centroids of 128 components), and the few queries stay cached anyway.
+    const int qtiles = (nq + kTileQ - 1) / kTileQ;
     const int j = blockIdx.z;
-    const int q0 = blockIdx.y * kTileQ;
-    const int c0 = blockIdx.x * kTileC;
+    const int q0 = static_cast<int>(blockIdx.x % qtiles) * kTileQ;
+    const int c0 = static_cast<int>(blockIdx.x / qtiles) * kTileC;
     const int D = m * dsub;
     const float *cbj = cb + static_cast<size_t>(j) * ncent * dsub;
 
@@ -218,7 +222,9 @@ int launch_distance_tables(const float *queries, int nq, const float *codebooks,
     else if (ks <= 8) launch_stream<8, 256>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
     else if (ks <= 16) launch_stream<16, 512>(queries, nq, codebooks, m, dsub, ncent, tables, stage, st);
     else {
-        const dim3 grid((ncent + kTileC - 1) / kTileC, (nq + kTileQ - 1) / kTileQ, m);
+        const uint64_t wgs = static_cast<uint64_t>((ncent + kTileC - 1) / kTileC) * static_cast<uint64_t>((nq + kTileQ - 1) / kTileQ);
+        if (wgs > 0x7fffffffull) return fail(DCPQ_EINVAL, "distance tables: %d queries x %d centroids are too many for one launch", nq, ncent);
+        const dim3 grid(static_cast<unsigned>(wgs), 1, m);
         DCPQ_LAUNCH(stage, st, full_tables_kernel, grid, dim3(256), 0, queries, nq, codebooks, m, dsub, ncent, tables);
     }
     DCPQ_CHECK_LAUNCH("full_tables_kernel");
