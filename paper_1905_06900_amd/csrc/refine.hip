@@ -58,16 +58,16 @@ __device__ inline float entry_on_demand(const float *__restrict__ yj, const floa
 //   query's sub-vector and the centroid the sub-code names) is computed when a candidate asks for it,
 //   straight from the codebook `cb` [M][table_size] rows of dsub floats, cstride floats apart -- the refinement of Alg. 3 computes table
 //   entries on demand because only a small part of a 2^16-entry table is ever used (Sec. 3.3,
-//   Refine step); here nothing is memoized, the entry is recomputed in double precision and rounded
-//   to fp32 once, which is what the tables hold.  Either way the distance is the fp32 sum of the M
-//   entries, j increasing.
+//   Refine step); the entry is computed in double precision and rounded to fp32 once, which is what the
+//   tables hold, and with memo_slots > 0 the entries of a query's distinct sub-codes are computed once and
+//   kept in LDS (see the kernel body).  Either way the distance is the fp32 sum of the M entries, j increasing.
 template <int M, typename CodeT, int MODE>
 __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restrict__ src, uint32_t table_size,
                                                           const float *__restrict__ cb, int dsub, int cstride,
                                                           const CodeT *__restrict__ codes, uint32_t n_codes,
                                                           const uint32_t *__restrict__ cand_id, uint32_t r,
                                                           uint32_t k, uint32_t n_pow2, int use_lds,
-                                                          uint64_t *__restrict__ spill,
+                                                          uint32_t memo_slots, uint64_t *__restrict__ spill,
                                                           uint32_t *__restrict__ ids, float *__restrict__ dist)
 {
     extern __shared__ __align__(16) uint8_t smem[];
@@ -86,20 +86,86 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
     }
     if constexpr (DIRECT) {
         // One lane per (candidate, sub-quantizer): the M lanes of a candidate are neighbours in a
-        // wavefront, each computes one entry, and the first of them adds the M entries up in order.
+        // wavefront, each gets one entry, and the first of them adds the M entries up in order.
+        //
+        // Memoized entries (Sec. 3.3, Refine step: a table entry is computed when first asked for and kept).  With
+        // encoded data the candidates of a query repeat a few sub-codes (measured on the GIST- and SIFT-shaped
+        // workloads: 60 and 26 distinct values per sub-quantizer among 5000 and 2000 candidates), so the workgroup
+        // first collects the distinct (sub-quantizer, sub-code) pairs of its query in an LDS hash set of memo_slots
+        // slots per sub-quantizer, computes every collected entry once, and then lets each candidate look its
+        // entries up.  The value of an entry does not depend on who computes it, so the result is the same bits.
+        // With nearly all sub-codes different (random codes) the set fills up, or the first candidates show that
+        // little repeats; the entries are then computed per candidate as before.
         const bool vec4 = (dsub & 3) == 0;                               // rows of whole 16-byte vectors
         const uint32_t lane = threadIdx.x & 63u;
         const int j = static_cast<int>(threadIdx.x % M);
         const float *yj = ly + j * dsub;
-        for (uint32_t base = 0; base < n_pow2; base += blockDim.x / M) {  // uniform trip count
+        const uint32_t per_pass = blockDim.x / M;                        // candidates per pass of the workgroup
+        constexpr uint32_t kEmpty = 0xFFFFFFFFu;
+        uint32_t *hkey = reinterpret_cast<uint32_t *>(ly + M * dsub);    // [M][memo_slots] sub-code, or kEmpty
+        float *hval = reinterpret_cast<float *>(hkey + M * memo_slots);  // [M][memo_slots] its entry
+        __shared__ uint32_t s_claimed, s_over;
+        const uint32_t hmask = memo_slots - 1u;
+        auto first_slot = [&](uint32_t cj) { return ((cj * 40503u) >> 3) & hmask; };
+        bool memo = memo_slots != 0;
+        if (memo) {                                                      // uniform
+            for (uint32_t t = threadIdx.x; t < M * memo_slots; t += blockDim.x) hkey[t] = kEmpty;
+            if (threadIdx.x == 0) { s_claimed = 0; s_over = 0; }
+            __syncthreads();
+            uint32_t *hj = hkey + j * memo_slots;
+            for (uint32_t base = 0; base < r; base += per_pass) {        // uniform trip count
+                const uint32_t t = base + threadIdx.x / M;
+                uint32_t id = kEmpty;
+                if (t < r) id = cand_id[static_cast<size_t>(q) * r + t];
+                if (id < n_codes) {
+                    const uint32_t cj = codes[static_cast<size_t>(id) * M + j];
+                    uint32_t h = first_slot(cj);
+                    bool placed = false;
+                    for (int probes = 0; probes < 32 && !placed; ++probes) {
+                        const uint32_t old = atomicCAS(&hj[h], kEmpty, cj);
+                        if (old == kEmpty) { atomicAdd(&s_claimed, 1u); placed = true; }
+                        else if (old == cj) placed = true;
+                        else h = (h + 1u) & hmask;
+                    }
+                    if (!placed) s_over = 1;                             // benign race: every writer stores 1
+                }
+                // after the first four passes: does anything repeat?  (more than half of the pairs seen so far new,
+                // or the sets half full: give up)
+                if (base == 3 * per_pass) {
+                    __syncthreads();
+                    if (threadIdx.x == 0 && (s_claimed > 2 * per_pass * M || s_claimed > M * memo_slots / 2)) s_over = 1;
+                    __syncthreads();
+                    if (s_over) break;                                   // uniform
+                }
+            }
+            __syncthreads();
+            memo = s_over == 0;
+            if (memo) {                                                  // uniform
+                for (uint32_t sl = threadIdx.x; sl < M * memo_slots; sl += blockDim.x) {
+                    const uint32_t cj = hkey[sl];
+                    if (cj != kEmpty) {
+                        const uint32_t js = sl / memo_slots;
+                        hval[sl] = entry_on_demand(ly + js * dsub, cb + (static_cast<size_t>(js) * table_size + cj) * cstride, dsub, vec4);
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        for (uint32_t base = 0; base < n_pow2; base += per_pass) {       // uniform trip count
             const uint32_t t = base + threadIdx.x / M;
             uint32_t id = 0xFFFFFFFFu;
             if (t < r) id = cand_id[static_cast<size_t>(q) * r + t];
             float e = 0.0f;
             if (id < n_codes) {                                          // pad slots (and anything out of range) sort last
                 const uint32_t cj = codes[static_cast<size_t>(id) * M + j];
-                const float *cen = cb + (static_cast<size_t>(j) * table_size + cj) * cstride;
-                e = entry_on_demand(yj, cen, dsub, vec4);
+                if (memo) {
+                    uint32_t h = first_slot(cj);
+                    while (hkey[j * memo_slots + h] != cj) h = (h + 1u) & hmask;      // it is there: every pair was collected
+                    e = hval[j * memo_slots + h];
+                } else {
+                    const float *cen = cb + (static_cast<size_t>(j) * table_size + cj) * cstride;
+                    e = entry_on_demand(yj, cen, dsub, vec4);
+                }
             }
             float d = __shfl(e, static_cast<int>(lane - j));
 #pragma unroll
@@ -230,11 +296,24 @@ static int launch_refine_m(const float *src, uint32_t table_size, const float *c
 {
     const uint32_t np2 = next_pow2_r(r);
     const int use_lds = np2 <= kRefineLdsKeys;
-    const size_t lds = (use_lds ? sizeof(uint64_t) * np2 : 0) + (MODE == kOnDemand ? sizeof(float) * M * dsub : 0);
+    size_t lds = (use_lds ? sizeof(uint64_t) * np2 : 0) + (MODE == kOnDemand ? sizeof(float) * M * dsub : 0);
+    // on demand: a hash set of the query's distinct (sub-quantizer, sub-code) pairs with their entries, as many
+    // slots per sub-quantizer (a power of two, at most 512) as the LDS left beside the keys, the query and the
+    // kernel's static arrays (17 KB) holds; none if that is fewer than 64
+    // (with fewer than 16 passes of the workgroup over its candidates, 1024 / M at a time, collecting and looking up
+    // costs more than it saves: measured at r = 1000, m = 4)
+    uint32_t memo_slots = 0;
+    if (MODE == kOnDemand && static_cast<uint64_t>(r) * M >= 16u * 1024u) {
+        memo_slots = 512;
+        while (memo_slots >= 64 && lds + static_cast<size_t>(8) * M * memo_slots > static_cast<size_t>(140) * 1024) memo_slots /= 2;
+        if (memo_slots < 64) memo_slots = 0;
+        lds += static_cast<size_t>(8) * M * memo_slots;
+    }
     const int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&refine_topk_kernel<M, CodeT, MODE>), static_cast<int>(lds));
     if (rc) return rc;
     DCPQ_LAUNCH(kStageRefine, st, (refine_topk_kernel<M, CodeT, MODE>), dim3(nq), dim3(1024), lds, src, table_size, cb, dsub,
-                cstride, codes, static_cast<uint32_t>(n_codes), cand_id, r, k, np2, use_lds, static_cast<uint64_t *>(ws), ids, dist);
+                cstride, codes, static_cast<uint32_t>(n_codes), cand_id, r, k, np2, use_lds, memo_slots, static_cast<uint64_t *>(ws),
+                ids, dist);
     DCPQ_CHECK_LAUNCH("refine_topk_kernel");
     return DCPQ_OK;
 }

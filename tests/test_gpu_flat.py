@@ -87,6 +87,36 @@ def test_split_on_demand_refinement(cfg, N, Q, r, chunk):
     c.check_pass_two(sids, sdist)
 
 
+@pytest.mark.parametrize("case", ["few distinct sub-codes", "set too small"])
+def test_on_demand_refinement_with_memoized_entries(case):
+    # The one-kernel on-demand refinement collects the distinct (sub-quantizer, sub-code) pairs of a query's
+    # candidates in a hash set and computes each entry once (it does so from r m >= 16384 on).  First case: encoded
+    # data, where a few dozen sub-codes repeat and the set is used.  Second case: 600 different sub-codes per
+    # sub-quantizer (m = 4: 512 slots each): sub-codes do repeat, but the sets cannot hold them, and the kernel falls
+    # back to computing per candidate.  Either way: the bits of the split form (which never memoizes), and the
+    # oracle's results.
+    if case == "few distinct sub-codes":
+        w = small_flat(4, 40_001, 21, 1100)                       # GIST-like recipe, m = 16: 17600 pairs per query
+        c = FlatCase(w, DEV)
+    else:
+        w = dataclasses.replace(small_flat(0, 100_003, 9, 4200), data="custom")
+        g = torch.Generator(device=DEV); g.manual_seed(991)
+        cb = synth.hierarchical_codebooks(w.m, w.dsub, w.b, w.pbits, lambda shape, gg: 40.0 * torch.rand(
+            shape, generator=gg, device=DEV, dtype=torch.float32), 4.0, DEV, 992)
+        values = torch.randperm(65536, generator=g, device=DEV)[:600]
+        codes = values[torch.randint(0, 600, (w.N, w.m), generator=g, device=DEV)].to(torch.int32).to(torch.int16).view(torch.uint16)
+        queries = 40.0 * torch.rand((w.Q, w.m * w.dsub), generator=g, device=DEV, dtype=torch.float32)
+        c = FlatCase(w, DEV, data=dict(codebooks=cb, codes=codes, queries=queries))
+    print("memoized refinement, %s: m=%d N=%d Q=%d r=%d" % (case, w.m, w.N, w.Q, w.r), flush=True)
+    dids, ddist = binding.search(c.queries, c.cb, c.derived, c.codes, w.r, w.k, refine_mode=binding.REFINE_DIRECT)
+    sids, sdist = binding.search(c.queries, c.cb, c.derived, c.codes, w.r, w.k, refine_mode=binding.REFINE_SPLIT)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(dids), to_np(sids))
+    np.testing.assert_array_equal(to_np(ddist), to_np(sdist))
+    c.oracle()
+    c.check_pass_two(dids, ddist)
+
+
 def test_fused_search_m2_with_a_ragged_last_chunk():
     # m = 2 goes through the three-pass scan, whose scratch layout depends on the batch size: the
     # last chunk (48 queries after a chunk of 64) lays it out differently from the full chunks
