@@ -7,6 +7,8 @@
 // usually little more than k) are gathered and only those are sorted, by the exact (distance, id)
 // key.  When that superset is large (many equal distances) all r keys are sorted instead.
 // Squared distances are non-negative, so their fp32 bit patterns order like the values.
+#include <type_traits>
+
 #include "common.h"
 #include "device_util.h"
 
@@ -102,6 +104,7 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
         const float *yj = ly + j * dsub;
         const uint32_t per_pass = blockDim.x / M;                        // candidates per pass of the workgroup
         constexpr uint32_t kEmpty = 0xFFFFFFFFu;
+        constexpr int kAhead = 4;                                        // passes whose loads are issued together
         uint32_t *hkey = reinterpret_cast<uint32_t *>(ly + M * dsub);    // [M][memo_slots] sub-code, or kEmpty
         float *hval = reinterpret_cast<float *>(hkey + M * memo_slots);  // [M][memo_slots] its entry
         __shared__ uint32_t s_claimed, s_over;
@@ -113,12 +116,21 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
             if (threadIdx.x == 0) { s_claimed = 0; s_over = 0; }
             __syncthreads();
             uint32_t *hj = hkey + j * memo_slots;
-            for (uint32_t base = 0; base < r; base += per_pass) {        // uniform trip count
-                const uint32_t t = base + threadIdx.x / M;
-                uint32_t id = kEmpty;
-                if (t < r) id = cand_id[static_cast<size_t>(q) * r + t];
-                if (id < n_codes) {
-                    const uint32_t cj = codes[static_cast<size_t>(id) * M + j];
+            // (kAhead passes at a time: their ids, then their sub-codes, are loaded together, so that a wavefront waits
+            // for memory twice per kAhead passes and not twice per pass)
+            for (uint32_t base = 0; base < r; base += kAhead * per_pass) {        // uniform trip count
+                uint32_t idv[kAhead], cjv[kAhead];
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    const uint32_t t = base + u * per_pass + threadIdx.x / M;
+                    idv[u] = t < r ? cand_id[static_cast<size_t>(q) * r + t] : kEmpty;
+                }
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) cjv[u] = idv[u] < n_codes ? codes[static_cast<size_t>(idv[u]) * M + j] : 0u;
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    if (idv[u] >= n_codes) continue;
+                    const uint32_t cj = cjv[u];
                     uint32_t h = first_slot(cj);
                     bool placed = false;
                     for (int probes = 0; probes < 32 && !placed; ++probes) {
@@ -129,11 +141,11 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
                     }
                     if (!placed) s_over = 1;                             // benign race: every writer stores 1
                 }
-                // after the first four passes: does anything repeat?  (more than half of the pairs seen so far new,
+                // after the first kAhead passes: does anything repeat?  (more than half of the pairs seen so far new,
                 // or the sets half full: give up)
-                if (base == 3 * per_pass) {
+                if (base == 0) {
                     __syncthreads();
-                    if (threadIdx.x == 0 && (s_claimed > 2 * per_pass * M || s_claimed > M * memo_slots / 2)) s_over = 1;
+                    if (threadIdx.x == 0 && (s_claimed > kAhead / 2 * per_pass * M || s_claimed > M * memo_slots / 2)) s_over = 1;
                     __syncthreads();
                     if (s_over) break;                                   // uniform
                 }
@@ -151,27 +163,43 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
             }
             __syncthreads();
         }
-        for (uint32_t base = 0; base < n_pow2; base += per_pass) {       // uniform trip count
-            const uint32_t t = base + threadIdx.x / M;
-            uint32_t id = 0xFFFFFFFFu;
-            if (t < r) id = cand_id[static_cast<size_t>(q) * r + t];
-            float e = 0.0f;
-            if (id < n_codes) {                                          // pad slots (and anything out of range) sort last
-                const uint32_t cj = codes[static_cast<size_t>(id) * M + j];
-                if (memo) {
-                    uint32_t h = first_slot(cj);
-                    while (hkey[j * memo_slots + h] != cj) h = (h + 1u) & hmask;      // it is there: every pair was collected
-                    e = hval[j * memo_slots + h];
-                } else {
-                    const float *cen = cb + (static_cast<size_t>(j) * table_size + cj) * cstride;
-                    e = entry_on_demand(yj, cen, dsub, vec4);
-                }
-            }
-            float d = __shfl(e, static_cast<int>(lane - j));
+        // (the memoized form takes kAhead passes at a time, as above; computing per candidate, where the rows of one
+        // pass already keep the memory system busy, measured slower that way)
+        auto build_keys = [&](auto ahead_tag) {
+        constexpr int AH = decltype(ahead_tag)::value;
+        for (uint32_t base = 0; base < n_pow2; base += AH * per_pass) {           // uniform trip count
+            uint32_t idv[AH], cjv[AH];
 #pragma unroll
-            for (int jj = 1; jj < M; ++jj) d = __fadd_rn(d, __shfl(e, static_cast<int>(lane - j + jj)));
-            if (j == 0 && t < n_pow2) a[t] = id < n_codes ? make_key(__float_as_uint(d), id) : ~0ull;
+            for (int u = 0; u < AH; ++u) {
+                const uint32_t t = base + u * per_pass + threadIdx.x / M;
+                idv[u] = t < r ? cand_id[static_cast<size_t>(q) * r + t] : 0xFFFFFFFFu;
+            }
+#pragma unroll
+            for (int u = 0; u < AH; ++u) cjv[u] = idv[u] < n_codes ? codes[static_cast<size_t>(idv[u]) * M + j] : 0u;
+#pragma unroll
+            for (int u = 0; u < AH; ++u) {
+                const uint32_t t = base + u * per_pass + threadIdx.x / M;
+                const uint32_t id = idv[u], cj = cjv[u];
+                float e = 0.0f;
+                if (id < n_codes) {                                      // pad slots (and anything out of range) sort last
+                    if (memo) {
+                        uint32_t h = first_slot(cj);
+                        while (hkey[j * memo_slots + h] != cj) h = (h + 1u) & hmask;      // it is there: every pair was collected
+                        e = hval[j * memo_slots + h];
+                    } else {
+                        const float *cen = cb + (static_cast<size_t>(j) * table_size + cj) * cstride;
+                        e = entry_on_demand(yj, cen, dsub, vec4);
+                    }
+                }
+                float d = __shfl(e, static_cast<int>(lane - j));
+#pragma unroll
+                for (int jj = 1; jj < M; ++jj) d = __fadd_rn(d, __shfl(e, static_cast<int>(lane - j + jj)));
+                if (j == 0 && t < n_pow2) a[t] = id < n_codes ? make_key(__float_as_uint(d), id) : ~0ull;
+            }
         }
+        };
+        if (memo) build_keys(std::integral_constant<int, kAhead>{});      // uniform
+        else build_keys(std::integral_constant<int, 1>{});
     } else if constexpr (MODE == kFromTerms) {
         const size_t total = static_cast<size_t>(gridDim.x) * r;
         for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x) {
@@ -300,10 +328,10 @@ static int launch_refine_m(const float *src, uint32_t table_size, const float *c
     // on demand: a hash set of the query's distinct (sub-quantizer, sub-code) pairs with their entries, as many
     // slots per sub-quantizer (a power of two, at most 512) as the LDS left beside the keys, the query and the
     // kernel's static arrays (17 KB) holds; none if that is fewer than 64
-    // (with fewer than 16 passes of the workgroup over its candidates, 1024 / M at a time, collecting and looking up
+    // (with fewer than 8 passes of the workgroup over its candidates, 1024 / M at a time, collecting and looking up
     // costs more than it saves: measured at r = 1000, m = 4)
     uint32_t memo_slots = 0;
-    if (MODE == kOnDemand && static_cast<uint64_t>(r) * M >= 16u * 1024u) {
+    if (MODE == kOnDemand && static_cast<uint64_t>(r) * M >= 8u * 1024u) {
         memo_slots = 512;
         while (memo_slots >= 64 && lds + static_cast<size_t>(8) * M * memo_slots > static_cast<size_t>(140) * 1024) memo_slots /= 2;
         if (memo_slots < 64) memo_slots = 0;

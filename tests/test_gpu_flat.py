@@ -90,7 +90,7 @@ def test_split_on_demand_refinement(cfg, N, Q, r, chunk):
 @pytest.mark.parametrize("case", ["few distinct sub-codes", "set too small"])
 def test_on_demand_refinement_with_memoized_entries(case):
     # The one-kernel on-demand refinement collects the distinct (sub-quantizer, sub-code) pairs of a query's
-    # candidates in a hash set and computes each entry once (it does so from r m >= 16384 on).  First case: encoded
+    # candidates in a hash set and computes each entry once (it does so from r m >= 8192 on).  First case: encoded
     # data, where a few dozen sub-codes repeat and the set is used.  Second case: 600 different sub-codes per
     # sub-quantizer (m = 4: 512 slots each): sub-codes do repeat, but the sets cannot hold them, and the kernel falls
     # back to computing per candidate.  Either way: the bits of the split form (which never memoizes), and the
