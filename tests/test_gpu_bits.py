@@ -33,7 +33,7 @@ CASES = [  # (b, bbar, m, dsub, N, Q, r)
     (16, 4, 8, 6, 50_001, 21, 300),
     (8, 4, 8, 6, 70_001, 37, 500),
     (8, 5, 4, 8, 40_003, 9, 300),
-    (8, 6, 16, 4, 30_001, 11, 200),
+    (8, 6, 16, 4, 30_001, 11, 600),      # r m = 9600: the on-demand refinement memoizes (at most 256 distinct sub-codes)
     (8, 8, 8, 6, 30_001, 11, 200),
     (8, 4, 2, 16, 30_001, 5, 100),
     (16, 8, 1, 8, 20_001, 7, 200),
