@@ -48,14 +48,31 @@ __global__ __launch_bounds__(256) void small_tables_kernel(
     __syncthreads();
 
     // Eq. 1 on the derived codebooks: thread i owns entry i of every table.
+    const bool vec4 = (dsub & 3) == 0 && (reinterpret_cast<uintptr_t>(derived) & 15) == 0;      // uniform
     float lo = INFINITY;
     if (tid < ks) {
         for (int j = 0; j < M; ++j) {
             const float *c = derived + (static_cast<size_t>(j) * ks + tid) * dsub;
             float acc = 0.0f;
-            for (int t = 0; t < dsub; ++t) {
-                const float diff = __fsub_rn(ly[j * dsub + t], c[t]);
-                acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+            if (vec4) {
+                // a centroid row as 16-byte vectors (a thread reads its own row: 4-byte loads would touch as many
+                // memory lines four times as often); the squares are still added one by one in ascending t
+                for (int t = 0; t < dsub; t += 4) {
+                    const float4 c4 = *reinterpret_cast<const float4 *>(c + t);
+                    float diff = __fsub_rn(ly[j * dsub + t], c4.x);
+                    acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                    diff = __fsub_rn(ly[j * dsub + t + 1], c4.y);
+                    acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                    diff = __fsub_rn(ly[j * dsub + t + 2], c4.z);
+                    acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                    diff = __fsub_rn(ly[j * dsub + t + 3], c4.w);
+                    acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                }
+            } else {
+                for (int t = 0; t < dsub; ++t) {
+                    const float diff = __fsub_rn(ly[j * dsub + t], c[t]);
+                    acc = __fadd_rn(acc, __fmul_rn(diff, diff));
+                }
             }
             ltab[j * ks + tid] = acc;
             lo = fminf(lo, acc);
