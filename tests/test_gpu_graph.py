@@ -13,9 +13,14 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda"
 
 
-def test_flat_search_captured_in_a_graph_replays_to_the_eager_result():
-    w = synth.scaled(synth.WORKLOADS[0], N=120_001, Q=40, r=800)
-    print("graph capture: flat search N=%d Q=%d" % (w.N, w.Q), flush=True)
+@pytest.mark.parametrize("cfg,N,Q,r", [(0, 120_001, 40, 800), (2, 300_007, 1000, 700)])
+def test_flat_search_captured_in_a_graph_replays_to_the_eager_result(cfg, N, Q, r):
+    # the second case is large enough for the pilot pass of the scan and for the refinement split by sub-quantizer
+    w = synth.scaled(synth.WORKLOADS[cfg], N=N, Q=Q, r=r)
+    if cfg == 2:
+        assert binding.scan_plan(w.N, w.m, w.Q, w.r)["pilot_every"] == 16
+        assert binding.search_refine_mode(w.m, w.dsub, 16, w.Q, w.r) == binding.REFINE_SPLIT
+    print("graph capture: flat search, cfg%d recipe, N=%d Q=%d r=%d" % (cfg, w.N, w.Q, w.r), flush=True)
     d = synth.make_flat(w, DEV)
     cb, codes, queries = d["codebooks"], d["codes"], d["queries"]
     derived = binding.derive_codebooks(cb)
