@@ -87,6 +87,23 @@ def test_split_on_demand_refinement(cfg, N, Q, r, chunk):
     c.check_pass_two(sids, sdist)
 
 
+def test_on_demand_refinement_with_r_above_the_lds_sort():
+    # r = 9000 candidates per query: the refinement's keys go to the global spill area instead of LDS (and the default
+    # mode would be full tables); the on-demand forms, memoized (tie-heavy cfg0 codes repeat sub-codes) and split,
+    # still agree bit for bit and with the oracle
+    w = small_flat(0, 100_003, 5, 9000)
+    print("on-demand refinement, keys spilled: m=%d N=%d Q=%d r=%d" % (w.m, w.N, w.Q, w.r), flush=True)
+    c = FlatCase(w, DEV)
+    assert binding.search_refine_mode(w.m, w.dsub, 16, w.Q, w.r) == binding.REFINE_TABLES
+    dids, ddist = binding.search(c.queries, c.cb, c.derived, c.codes, w.r, w.k, refine_mode=binding.REFINE_DIRECT)
+    sids, sdist = binding.search(c.queries, c.cb, c.derived, c.codes, w.r, w.k, refine_mode=binding.REFINE_SPLIT)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_np(dids), to_np(sids))
+    np.testing.assert_array_equal(to_np(ddist), to_np(sdist))
+    c.oracle()
+    c.check_pass_two(dids, ddist)
+
+
 @pytest.mark.parametrize("case", ["few distinct sub-codes", "set too small"])
 def test_on_demand_refinement_with_memoized_entries(case):
     # The one-kernel on-demand refinement collects the distinct (sub-quantizer, sub-code) pairs of a query's
