@@ -609,13 +609,15 @@ static size_t rank_lds_bytes(uint32_t sortcap) { return 8 * static_cast<size_t>(
 // flags[q] = 1 when the query must be redone (buffer overflow, fewer than r candidates, or more
 // candidates at or below the bound than the sort area holds).
 // The candidates at or below the bound are dealt into groups -- (bucket, one of 2^s equal ranges of the
-// ids, s as large as 2048 groups allow: 8 ranges when all 256 buckets are in play, 2048 when everything
-// ties in bucket 0) -- by a counting sort: one pass over the buffer counts the groups, a prefix sum gives every group
-// its place in the output (groups ordered by bucket, then by id range, are already in (qd, id) order),
-// a second pass deals the ids out, and inside a group a candidate's rank is the number of ids below its
-// own.  With r spread over tens of buckets and the ids spread over the array the groups hold a few
-// dozen ids, so this is several times cheaper than a sorting network over the whole set, which remains
-// for queries with a very large group (many equal qd in one stretch of ids).
+// ids), over the buckets from the first one that holds a candidate up to the bound's (the r smallest of
+// an array sit in a handful of buckets, with nothing below them), s as large as 2048 groups allow: 8
+// ranges if all 256 buckets were in play, 2048 when everything ties in one bucket -- by a counting sort:
+// one pass over the buffer counts the groups, a prefix sum gives every group its place in the output
+// (groups ordered by bucket, then by id range, are already in (qd, id) order), a second pass deals the
+// ids out, and inside a group a candidate's rank is the number of ids below its own.  With the ids spread
+// over the array the groups hold a few ids, so this is several times cheaper than a sorting network
+// over the whole set, which remains for queries with a very large group (many equal qd in one stretch
+// of ids).
 // id_mul: the finest id range of an id is the high word of id * id_mul (below 2048 for every id of the
 // array, and non-decreasing in the id, which is all the order needs); coarser ranges are its top bits.
 __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__restrict__ keys,
@@ -630,7 +632,7 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
     extern __shared__ __align__(16) uint8_t smem[];
     __shared__ uint32_t cum[256];                // inclusive prefix of the bucket counts
     __shared__ uint32_t wsum[16];
-    __shared__ uint32_t s_t, s_keep, s_pos, s_big;
+    __shared__ uint32_t s_t, s_keep, s_pos, s_big, s_b0;
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     uint32_t n = 0;
     bool over = false;
@@ -644,7 +646,7 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
         return;
     }
     if (tid < 256) cum[tid] = chist[static_cast<size_t>(q) * 256 + tid];
-    if (tid == 0) { s_t = 255; s_keep = n; s_pos = 0; s_big = 0; }
+    if (tid == 0) { s_t = 255; s_keep = n; s_pos = 0; s_big = 0; s_b0 = 0; }
     __syncthreads();
     for (int off = 1; off < 256; off <<= 1) {
         uint32_t add = 0;
@@ -656,9 +658,10 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
     if (tid < 256) {
         const uint32_t before = tid ? cum[tid - 1] : 0u;
         if (before < r && cum[tid] >= r) { s_t = tid; s_keep = cum[tid]; }
+        if (before == 0 && cum[tid] > 0) s_b0 = tid;                      // the first bucket that holds a candidate
     }
     __syncthreads();
-    const uint32_t T = s_t, keep = s_keep;
+    const uint32_t T = s_t, keep = s_keep, b0 = s_b0;
     if (keep > sortcap) {                        // tie bucket does not fit the sort area
         if (tid == 0) flags[q] = 1;
         return;
@@ -668,10 +671,13 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
         uint32_t *gstart = gcnt + kGroups;                                // [kGroups] first output position of the group
         uint32_t *ids = gstart + kGroups;                                 // [sortcap]
         uint16_t *grp = reinterpret_cast<uint16_t *>(ids + sortcap);      // [sortcap]
+        // the groups cover the buckets b0 .. T only (the r smallest of an array sit in a few buckets just below T, and
+        // the buckets under them are empty: counting them would leave most groups unused and the rest large)
+        const uint32_t nbuckets = T - b0 + 1;
         int sub_bits = 0;
-        while (sub_bits < kRangeBits && ((T + 1) << (sub_bits + 1)) <= kGroups) ++sub_bits;
+        while (sub_bits < kRangeBits && (nbuckets << (sub_bits + 1)) <= kGroups) ++sub_bits;
         const int range_shift = kRangeBits - sub_bits;
-        const uint32_t ngroups = (T + 1) << sub_bits;
+        const uint32_t ngroups = nbuckets << sub_bits;
         for (uint32_t t = tid; t < ngroups; t += 1024) gcnt[t] = 0;
         __syncthreads();
         // count the groups: one wavefront per slice at a time, so that the slices' loads are in flight together
@@ -682,7 +688,7 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
             for (uint32_t t = lane; t < c; t += 64) {
                 const uint64_t key = keys[cell * cap + t];
                 const uint32_t qd = static_cast<uint32_t>(key >> 32);
-                if (qd <= T) atomicAdd(&gcnt[(qd << sub_bits) + (__umulhi(static_cast<uint32_t>(key), id_mul) >> range_shift)], 1u);
+                if (qd <= T) atomicAdd(&gcnt[((qd - b0) << sub_bits) + (__umulhi(static_cast<uint32_t>(key), id_mul) >> range_shift)], 1u);
             }
         }
         __syncthreads();
@@ -714,7 +720,7 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
                     const uint64_t key = keys[cell * cap + t];
                     const uint32_t qd = static_cast<uint32_t>(key >> 32);
                     if (qd <= T) {
-                        const uint32_t g = (qd << sub_bits) + (__umulhi(static_cast<uint32_t>(key), id_mul) >> range_shift);
+                        const uint32_t g = ((qd - b0) << sub_bits) + (__umulhi(static_cast<uint32_t>(key), id_mul) >> range_shift);
                         const uint32_t pos = gstart[g] + atomicAdd(&gcnt[g], 1u);
                         if (pos < sortcap) { ids[pos] = static_cast<uint32_t>(key); grp[pos] = static_cast<uint16_t>(g); }
                     }
@@ -724,12 +730,18 @@ __global__ __launch_bounds__(1024) void fast_select_kernel(const uint64_t *__res
             for (uint32_t t = tid; t < keep; t += 1024) {
                 const uint32_t id = ids[t], g = grp[t];
                 const uint32_t lo = gstart[g], hi = g + 1 < ngroups ? gstart[g + 1] : keep;
-                uint32_t rank = 0;
-                for (uint32_t k = lo; k < hi; ++k) rank += ids[k] < id ? 1u : 0u;
+                // rank inside the group: ids read four at a time where they are aligned (one LDS read per four compares)
+                uint32_t rank = 0, k = lo;
+                for (; k < hi && (k & 3u); ++k) rank += ids[k] < id ? 1u : 0u;
+                for (; k + 4 <= hi; k += 4) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(ids + k);
+                    rank += (v.x < id ? 1u : 0u) + (v.y < id ? 1u : 0u) + (v.z < id ? 1u : 0u) + (v.w < id ? 1u : 0u);
+                }
+                for (; k < hi; ++k) rank += ids[k] < id ? 1u : 0u;
                 const uint32_t out = lo + rank;
                 if (out < r) {
                     cand_id[static_cast<size_t>(q) * r + out] = id;
-                    cand_qd[static_cast<size_t>(q) * r + out] = static_cast<uint8_t>(g >> sub_bits);
+                    cand_qd[static_cast<size_t>(q) * r + out] = static_cast<uint8_t>((g >> sub_bits) + b0);
                 }
             }
             if (tid == 0) flags[q] = 0;
