@@ -87,9 +87,6 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
         tq = src + static_cast<size_t>(q) * M * table_size;
     }
     if constexpr (DIRECT) {
-        // One lane per (candidate, sub-quantizer): the M lanes of a candidate are neighbours in a
-        // wavefront, each gets one entry, and the first of them adds the M entries up in order.
-        //
         // Memoized entries (Sec. 3.3, Refine step: a table entry is computed when first asked for and kept).  With
         // encoded data the candidates of a query repeat a few sub-codes (measured on the GIST- and SIFT-shaped
         // workloads: 60 and 26 distinct values per sub-quantizer among 5000 and 2000 candidates), so the workgroup
@@ -99,97 +96,149 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
         // With nearly all sub-codes different (random codes) the set fills up, or the first candidates show that
         // little repeats; the entries are then computed per candidate as before.
         const bool vec4 = (dsub & 3) == 0;                               // rows of whole 16-byte vectors
-        const uint32_t lane = threadIdx.x & 63u;
-        const int j = static_cast<int>(threadIdx.x % M);
-        const float *yj = ly + j * dsub;
-        const uint32_t per_pass = blockDim.x / M;                        // candidates per pass of the workgroup
         constexpr uint32_t kEmpty = 0xFFFFFFFFu;
-        constexpr int kAhead = 4;                                        // passes whose loads are issued together
+        constexpr uint32_t kMemoFirst = 256;                             // candidates of the first collecting pass
         uint32_t *hkey = reinterpret_cast<uint32_t *>(ly + M * dsub);    // [M][memo_slots] sub-code, or kEmpty
         float *hval = reinterpret_cast<float *>(hkey + M * memo_slots);  // [M][memo_slots] its entry
+        uint16_t *hlist = reinterpret_cast<uint16_t *>(hval + M * memo_slots);  // [M * memo_slots / 2] the slots in use
         __shared__ uint32_t s_claimed, s_over;
         const uint32_t hmask = memo_slots - 1u;
         auto first_slot = [&](uint32_t cj) { return ((cj * 40503u) >> 3) & hmask; };
+        // the M sub-codes of a candidate, as stored (whole 16-byte words where the code is made of them)
+        const bool codes_aligned = (reinterpret_cast<uintptr_t>(codes) & 15) == 0;      // uniform
+        auto load_code = [&](uint32_t id, uint32_t (&c)[M]) {
+            constexpr int BYTES = M * static_cast<int>(sizeof(CodeT));
+            const CodeT *src = codes + static_cast<size_t>(id) * M;
+            if constexpr (BYTES % 16 == 0) {
+                if (codes_aligned) {
+                    uint4 raw[BYTES / 16];
+#pragma unroll
+                    for (int v = 0; v < BYTES / 16; ++v) raw[v] = reinterpret_cast<const uint4 *>(src)[v];
+#pragma unroll
+                    for (int jj = 0; jj < M; ++jj) {
+                        const int byte = jj * static_cast<int>(sizeof(CodeT));
+                        const uint4 w4 = raw[byte / 16];
+                        const uint32_t word = (byte % 16) / 4 == 0 ? w4.x : (byte % 16) / 4 == 1 ? w4.y : (byte % 16) / 4 == 2 ? w4.z : w4.w;
+                        c[jj] = sizeof(CodeT) == 2 ? (word >> (8 * (byte % 4))) & 0xFFFFu : (word >> (8 * (byte % 4))) & 0xFFu;
+                    }
+                    return;
+                }
+            }
+#pragma unroll
+            for (int jj = 0; jj < M; ++jj) c[jj] = src[jj];
+        };
         bool memo = memo_slots != 0;
         if (memo) {                                                      // uniform
+            // In the memoized form a lane takes a whole candidate (its entries come from LDS, there is nothing to
+            // spread over lanes): collecting pass, then the entries of the collected pairs, then the look-up pass.
             for (uint32_t t = threadIdx.x; t < M * memo_slots; t += blockDim.x) hkey[t] = kEmpty;
             if (threadIdx.x == 0) { s_claimed = 0; s_over = 0; }
             __syncthreads();
-            uint32_t *hj = hkey + j * memo_slots;
-            // (kAhead passes at a time: their ids, then their sub-codes, are loaded together, so that a wavefront waits
-            // for memory twice per kAhead passes and not twice per pass)
-            for (uint32_t base = 0; base < r; base += kAhead * per_pass) {        // uniform trip count
-                uint32_t idv[kAhead], cjv[kAhead];
+            // (a short first pass: it shows whether anything repeats, and after it most pairs are found by a read)
+            const uint32_t first = blockDim.x < kMemoFirst ? blockDim.x : kMemoFirst;
+            for (uint32_t base = 0; base < r; base += base == 0 ? first : blockDim.x) {  // uniform trip count
+                const uint32_t t = base + threadIdx.x;
+                uint32_t id = kEmpty;
+                if (t < r && (base != 0 || threadIdx.x < first)) id = cand_id[static_cast<size_t>(q) * r + t];
+                if (id < n_codes) {
+                    uint32_t c[M], seen0[M];
+                    load_code(id, c);
+                    // (the M first slots are read together: nearly every pair is already there, in its first slot)
 #pragma unroll
-                for (int u = 0; u < kAhead; ++u) {
-                    const uint32_t t = base + u * per_pass + threadIdx.x / M;
-                    idv[u] = t < r ? cand_id[static_cast<size_t>(q) * r + t] : kEmpty;
-                }
+                    for (int jj = 0; jj < M; ++jj)
+                        seen0[jj] = __hip_atomic_load(&hkey[jj * memo_slots + first_slot(c[jj])], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 #pragma unroll
-                for (int u = 0; u < kAhead; ++u) cjv[u] = idv[u] < n_codes ? codes[static_cast<size_t>(idv[u]) * M + j] : 0u;
-#pragma unroll
-                for (int u = 0; u < kAhead; ++u) {
-                    if (idv[u] >= n_codes) continue;
-                    const uint32_t cj = cjv[u];
-                    uint32_t h = first_slot(cj);
-                    bool placed = false;
-                    for (int probes = 0; probes < 32 && !placed; ++probes) {
-                        const uint32_t old = atomicCAS(&hj[h], kEmpty, cj);
-                        if (old == kEmpty) { atomicAdd(&s_claimed, 1u); placed = true; }
-                        else if (old == cj) placed = true;
-                        else h = (h + 1u) & hmask;
+                    for (int jj = 0; jj < M; ++jj) {
+                        uint32_t *hj = hkey + jj * memo_slots;
+                        const uint32_t cj = c[jj];
+                        if (seen0[jj] == cj) continue;
+                        uint32_t h = first_slot(cj);
+                        bool placed = false;
+                        for (int probes = 0; probes < 32 && !placed; ++probes) {
+                            // a plain read first: nearly every pair is already there
+                            uint32_t cur = __hip_atomic_load(&hj[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                            if (cur == kEmpty) {
+                                cur = atomicCAS(&hj[h], kEmpty, cj);
+                                if (cur == kEmpty) {
+                                    const uint32_t at = atomicAdd(&s_claimed, 1u);
+                                    if (at < M * memo_slots / 2) hlist[at] = static_cast<uint16_t>(jj * memo_slots + h);
+                                    cur = cj;
+                                }
+                            }
+                            if (cur == cj) placed = true;
+                            else h = (h + 1u) & hmask;
+                        }
+                        if (!placed) s_over = 1;                         // benign race: every writer stores 1
                     }
-                    if (!placed) s_over = 1;                             // benign race: every writer stores 1
                 }
-                // after the first kAhead passes: does anything repeat?  (more than half of the pairs seen so far new,
-                // or the sets half full: give up)
+                // after the first pass: does anything repeat?  (more than half of the pairs seen so far new, or the
+                // sets half full: give up)
                 if (base == 0) {
                     __syncthreads();
-                    if (threadIdx.x == 0 && (s_claimed > kAhead / 2 * per_pass * M || s_claimed > M * memo_slots / 2)) s_over = 1;
+                    const uint32_t seen = (r < first ? r : first) * M;
+                    if (threadIdx.x == 0 && (s_claimed > seen / 2 || s_claimed > M * memo_slots / 2)) s_over = 1;
                     __syncthreads();
                     if (s_over) break;                                   // uniform
                 }
             }
             __syncthreads();
-            memo = s_over == 0;
+            memo = s_over == 0 && s_claimed <= M * memo_slots / 2;       // (the list of slots in use holds that many)
             if (memo) {                                                  // uniform
-                for (uint32_t sl = threadIdx.x; sl < M * memo_slots; sl += blockDim.x) {
-                    const uint32_t cj = hkey[sl];
-                    if (cj != kEmpty) {
-                        const uint32_t js = sl / memo_slots;
-                        hval[sl] = entry_on_demand(ly + js * dsub, cb + (static_cast<size_t>(js) * table_size + cj) * cstride, dsub, vec4);
+                const uint32_t n_used = s_claimed;
+                for (uint32_t u = threadIdx.x; u < n_used; u += blockDim.x) {
+                    const uint32_t sl = hlist[u], js = sl / memo_slots;
+                    hval[sl] = entry_on_demand(ly + js * dsub, cb + (static_cast<size_t>(js) * table_size + hkey[sl]) * cstride, dsub, vec4);
+                }
+                __syncthreads();
+                for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x) {
+                    uint64_t key = ~0ull;
+                    if (t < r) {
+                        const uint32_t id = cand_id[static_cast<size_t>(q) * r + t];
+                        if (id < n_codes) {                              // pad slots (and anything out of range) sort last
+                            uint32_t c[M], slot[M];
+                            float e[M];
+                            load_code(id, c);
+                            // first slots and their values read together; the few pairs that sit further on are found after
+#pragma unroll
+                            for (int jj = 0; jj < M; ++jj) slot[jj] = jj * memo_slots + first_slot(c[jj]);
+                            bool all_first = true;
+#pragma unroll
+                            for (int jj = 0; jj < M; ++jj) all_first = all_first && hkey[slot[jj]] == c[jj];
+                            if (!all_first) {
+#pragma unroll
+                                for (int jj = 0; jj < M; ++jj) {
+                                    uint32_t h = slot[jj] - jj * memo_slots;
+                                    while (hkey[jj * memo_slots + h] != c[jj]) h = (h + 1u) & hmask;  // it is there: every pair was collected
+                                    slot[jj] = jj * memo_slots + h;
+                                }
+                            }
+#pragma unroll
+                            for (int jj = 0; jj < M; ++jj) e[jj] = hval[slot[jj]];
+                            float d = e[0];
+#pragma unroll
+                            for (int jj = 1; jj < M; ++jj) d = __fadd_rn(d, e[jj]);
+                            key = make_key(__float_as_uint(d), id);
+                        }
                     }
+                    a[t] = key;
                 }
             }
-            __syncthreads();
         }
-        // (the memoized form takes kAhead passes at a time, as above; computing per candidate, where the rows of one
-        // pass already keep the memory system busy, measured slower that way)
-        auto build_keys = [&](auto ahead_tag) {
-        constexpr int AH = decltype(ahead_tag)::value;
-        for (uint32_t base = 0; base < n_pow2; base += AH * per_pass) {           // uniform trip count
-            uint32_t idv[AH], cjv[AH];
-#pragma unroll
-            for (int u = 0; u < AH; ++u) {
-                const uint32_t t = base + u * per_pass + threadIdx.x / M;
-                idv[u] = t < r ? cand_id[static_cast<size_t>(q) * r + t] : 0xFFFFFFFFu;
-            }
-#pragma unroll
-            for (int u = 0; u < AH; ++u) cjv[u] = idv[u] < n_codes ? codes[static_cast<size_t>(idv[u]) * M + j] : 0u;
-#pragma unroll
-            for (int u = 0; u < AH; ++u) {
-                const uint32_t t = base + u * per_pass + threadIdx.x / M;
-                const uint32_t id = idv[u], cj = cjv[u];
+        if (!memo) {                                                     // uniform
+            // One lane per (candidate, sub-quantizer): the M lanes of a candidate are neighbours in a wavefront, each
+            // computes one entry, and the sums are formed in ascending j from the neighbours' values.
+            const uint32_t lane = threadIdx.x & 63u;
+            const int j = static_cast<int>(threadIdx.x % M);
+            const float *yj = ly + j * dsub;
+            for (uint32_t base = 0; base < n_pow2; base += blockDim.x / M) {  // uniform trip count
+                const uint32_t t = base + threadIdx.x / M;
+                uint32_t id = 0xFFFFFFFFu;
+                if (t < r) id = cand_id[static_cast<size_t>(q) * r + t];
                 float e = 0.0f;
                 if (id < n_codes) {                                      // pad slots (and anything out of range) sort last
-                    if (memo) {
-                        uint32_t h = first_slot(cj);
-                        while (hkey[j * memo_slots + h] != cj) h = (h + 1u) & hmask;      // it is there: every pair was collected
-                        e = hval[j * memo_slots + h];
-                    } else {
-                        const float *cen = cb + (static_cast<size_t>(j) * table_size + cj) * cstride;
-                        e = entry_on_demand(yj, cen, dsub, vec4);
-                    }
+                    const uint32_t cj = codes[static_cast<size_t>(id) * M + j];
+                    const float *cen = cb + (static_cast<size_t>(j) * table_size + cj) * cstride;
+                    e = entry_on_demand(yj, cen, dsub, vec4);
                 }
                 float d = __shfl(e, static_cast<int>(lane - j));
 #pragma unroll
@@ -197,9 +246,6 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
                 if (j == 0 && t < n_pow2) a[t] = id < n_codes ? make_key(__float_as_uint(d), id) : ~0ull;
             }
         }
-        };
-        if (memo) build_keys(std::integral_constant<int, kAhead>{});      // uniform
-        else build_keys(std::integral_constant<int, 1>{});
     } else if constexpr (MODE == kFromTerms) {
         const size_t total = static_cast<size_t>(gridDim.x) * r;
         for (uint32_t t = threadIdx.x; t < n_pow2; t += blockDim.x) {
@@ -333,9 +379,9 @@ static int launch_refine_m(const float *src, uint32_t table_size, const float *c
     uint32_t memo_slots = 0;
     if (MODE == kOnDemand && static_cast<uint64_t>(r) * M >= 8u * 1024u) {
         memo_slots = 512;
-        while (memo_slots >= 64 && lds + static_cast<size_t>(8) * M * memo_slots > static_cast<size_t>(140) * 1024) memo_slots /= 2;
+        while (memo_slots >= 64 && lds + static_cast<size_t>(9) * M * memo_slots > static_cast<size_t>(140) * 1024) memo_slots /= 2;
         if (memo_slots < 64) memo_slots = 0;
-        lds += static_cast<size_t>(8) * M * memo_slots;
+        lds += static_cast<size_t>(9) * M * memo_slots;                 // keys, entries, and the list of slots in use
     }
     const int rc = allow_dynamic_lds(reinterpret_cast<const void *>(&refine_topk_kernel<M, CodeT, MODE>), static_cast<int>(lds));
     if (rc) return rc;
