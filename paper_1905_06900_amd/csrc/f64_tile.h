@@ -2,6 +2,8 @@
 // kernel and the nearest-centroid kernel (HIP translation units only).
 #pragma once
 
+#include <type_traits>
+
 #include "common.h"
 
 namespace dcpq {
@@ -32,12 +34,74 @@ __device__ inline void load_run(const float *p, int n, float (&out)[4])
 //   valid rows -- rows past the end give values the caller never uses.
 // A sum over components does not care in which order they come, so when dsub is a multiple of 4 slot g does
 // not take components g, g + 4, g + 8, ... (a 4-byte load per lane, row and step, 64 scattered requests per
-// instruction: the address path, not the matrix pipe, then sets the pace) but the g-th QUARTER of the row,
-// dsub / 4 consecutive floats, fetched as 16-byte loads four steps ahead of their use.
+// instruction: the address path, not the matrix pipe, then sets the pace) but runs of four consecutive floats,
+// fetched as 16-byte loads four steps ahead of their use: the g-th 16 bytes of every 64-byte piece of the row
+// when dsub is a multiple of 16, else the g-th quarter of the row.
 template <int MT>
 __device__ inline void f64_tile_products(const float *const (&arow)[MT], const float *const (&brow)[4], int dsub, int slot,
                                          bool want_na, double4_t (&acc)[MT][4], double (&na)[MT], double (&nb)[4])
 {
+    if ((dsub & 15) == 0) {
+        // Rows of whole 64-byte pieces: the four slots share each piece (slot g its g-th 16 bytes), so that the 64
+        // loads of an instruction fall into 16 memory lines and the next piece finds the other half of each line
+        // still in the first-level cache.  (With a quarter of the row per slot every lane walks a line of its own,
+        // 16 bytes every four steps, and at 128 components the 256 lines a wavefront has open are the whole cache:
+        // each 16-byte run then moved a line from the L2 again.)  Two sets of registers take the pieces in turn, so
+        // that the loads of one are under way while the other is multiplied, and nothing is copied between them:
+        // the ordinary vector instructions share the issue port with the matrix instructions, and at 8 matrix
+        // instructions per step every one of them saved counts (6 conversions and 4 to 6 fused norm updates remain).
+        const float *ap[MT], *bp[4];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) ap[mt] = arow[mt] + slot * 4;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) bp[nt] = brow[nt] + slot * 4;
+        auto load_piece = [&](int c, float4_any (&A)[MT], float4_any (&B)[4]) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) A[mt] = *reinterpret_cast<const float4_any *>(ap[mt] + 16 * c);
+#pragma unroll
+            for (int nt = 0; nt < 4; ++nt) B[nt] = *reinterpret_cast<const float4_any *>(bp[nt] + 16 * c);
+        };
+        // (WANT: std::true_type or std::false_type, so that the norms of the A rows cost nothing where they are
+        // not wanted; every load is unconditional, the last one of a piece that is there already: loads behind a
+        // branch make the compiler wait for ALL loads in flight where the paths join)
+        auto run = [&](auto WANT) {
+            auto multiply = [&](const float4_any (&A)[MT], const float4_any (&B)[4]) {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    double a[MT], b[4];
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) a[mt] = static_cast<double>(A[mt].v[t]);
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) b[nt] = static_cast<double>(B[nt].v[t]);
+                    if constexpr (decltype(WANT)::value) {
+#pragma unroll
+                        for (int mt = 0; mt < MT; ++mt) na[mt] = __builtin_fma(a[mt], a[mt], na[mt]);
+                    }
+#pragma unroll
+                    for (int nt = 0; nt < 4; ++nt) nb[nt] = __builtin_fma(b[nt], b[nt], nb[nt]);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < 4; ++nt)
+                            acc[mt][nt] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+                }
+            };
+            const int pieces = dsub >> 4;
+            float4_any a0[MT], b0[4], a1[MT], b1[4];
+            load_piece(0, a0, b0);
+            int c = 0;
+            for (; c + 2 <= pieces; c += 2) {
+                load_piece(c + 1, a1, b1);
+                multiply(a0, b0);
+                load_piece(c + 2 < pieces ? c + 2 : pieces - 1, a0, b0);
+                multiply(a1, b1);
+            }
+            if (c < pieces) multiply(a0, b0);                  // an odd count: the last piece is in the first set
+        };
+        if (want_na) run(std::true_type{});                    // uniform
+        else run(std::false_type{});
+        return;
+    }
     if ((dsub & 3) == 0) {
         const int q = dsub >> 2;
         const float *ap[MT], *bp[4];

@@ -63,7 +63,8 @@ __global__ __launch_bounds__(256) void full_tables_kernel(const float *__restric
     double na[MT], nb[4] = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) na[mt] = 0.0;
-    f64_tile_products<MT>(ap, bp, dsub, lk, true, acc, na, nb);
+    // (the queries' norms are wanted once per workgroup: the first wavefront computes them)
+    f64_tile_products<MT>(ap, bp, dsub, lk, __builtin_amdgcn_readfirstlane(wave) == 0, acc, na, nb);
     // sum the four component residues: lane (lr, *) then holds the norms of queries q0 + 16 mt + lr and of
     // its own four centroids; the queries' norms go through LDS, because the outputs of a lane belong to
     // other queries than its A operands
