@@ -577,10 +577,24 @@ __device__ inline void ivf_scan_unit(int q, const CodeT *__restrict__ codes, con
 }
 
 // Grid (kIvfUnitsPerQuery / 4, min(nq, kIvfRedoRows)): a wavefront takes the same unit number of every
-// kIvfRedoRows-th query.  With flags given only flagged queries are scanned, and since that is the rare case
+// kIvfRedoRows-th query.  With flags given (nq of them and, as entry nq, whether any is set: ivf_any_flag_kernel)
+// only flagged queries are scanned, and since that is the rare case
 // (the three passes redo what the single pass could not finish) a row of workgroups serves many queries, so
 // that a launch with nothing to do costs a few thousand empty workgroups, not one per (query, 4 units).
 constexpr int kIvfRedoRows = 32;
+
+// flags[nq] = whether any of flags[0 .. nq) is set.  One workgroup.
+__global__ __launch_bounds__(1024) void ivf_any_flag_kernel(uint32_t *__restrict__ flags, int nq)
+{
+    __shared__ uint32_t any;
+    if (threadIdx.x == 0) any = 0;
+    __syncthreads();
+    uint32_t mine = 0;
+    for (int q = threadIdx.x; q < nq; q += 1024) mine |= flags[q];
+    if (mine) any = 1;                                       // benign race: every writer stores 1
+    __syncthreads();
+    if (threadIdx.x == 0) flags[nq] = any;
+}
 
 template <int M, int MODE, typename CodeT>
 __global__ __launch_bounds__(256) void ivf_scan_kernel(const CodeT *__restrict__ codes, const IvfUnit *__restrict__ units,
@@ -590,6 +604,7 @@ __global__ __launch_bounds__(256) void ivf_scan_kernel(const CodeT *__restrict__
                                                       const uint32_t *__restrict__ thr, uint32_t *__restrict__ tie,
                                                       uint32_t *__restrict__ counter, uint64_t *__restrict__ keys)
 {
+    if (flags && flags[nq] == 0) return;                     // no query is flagged: one load, not nq / gridDim.y
     for (int q = blockIdx.y; q < nq; q += gridDim.y) {
         if (flags && flags[q] == 0) continue;
         ivf_scan_unit<M, MODE, CodeT>(q, codes, units, nunits, qtab, nprobe, r, unit_step, flags, hist, thr, tie, counter, keys);
@@ -909,7 +924,7 @@ static IvfScanPlan plan_ivf_scan(int nq, uint32_t r)
     }
     p.sortcap = next_pow2(2 * r) < kSortLdsKeys ? kSortLdsKeys : next_pow2(2 * r);
     p.off_tcur = off;    off = align_up(off + sizeof(int32_t) * Q, 256);
-    p.off_flags = off;   off = align_up(off + sizeof(uint32_t) * Q, 256);
+    p.off_flags = off;   off = align_up(off + sizeof(uint32_t) * (Q + 1), 256);     // and "any of them"
     p.off_probed = off;  off = align_up(off + sizeof(uint32_t) * Q, 256);
     p.off_sunits = off;  off = align_up(off + sizeof(IvfUnit) * Q * kIvfSampleUnits, 256);
     p.off_nsunits = off; off = align_up(off + sizeof(uint32_t) * Q, 256);
@@ -969,6 +984,8 @@ static int ivf_scan_m(const CodeT *codes, const int64_t *offsets, const int32_t 
     DCPQ_CHECK_LAUNCH("ivf_scan_single_kernel");
     rc = launch_fast_select(fkeys, fcount, chist, nq, r, kFastSlices, p.cap, p.sortcap, 0, fsort, cand_id, cand_qd, flags, st);
     if (rc) return rc;
+    DCPQ_LAUNCH(kStageIvf, st, ivf_any_flag_kernel, dim3(1), dim3(1024), 0, flags, nq);
+    DCPQ_CHECK_LAUNCH("ivf_any_flag_kernel");
     // the queries it flagged (a full slice, or fewer than r codes in the probed lists): three passes
     DCPQ_LAUNCH(kStageIvf, st, (ivf_scan_kernel<M, kIvfHist, CodeT>), grid, dim3(256), lds_tab + 4 * 256 * 4, codes, units,
                 nunits, qtab, nprobe, nq, r, 1u, flags, hist, thr, tie, counter, keys);
