@@ -374,8 +374,8 @@ static int launch_refine_m(const float *src, uint32_t table_size, const float *c
     // on demand: a hash set of the query's distinct (sub-quantizer, sub-code) pairs with their entries, as many
     // slots per sub-quantizer (a power of two, at most 512) as the LDS left beside the keys, the query and the
     // kernel's static arrays (17 KB) holds; none if that is fewer than 64
-    // (with fewer than 8 passes of the workgroup over its candidates, 1024 / M at a time, collecting and looking up
-    // costs more than it saves: measured at r = 1000, m = 4)
+    // (below 8192 (candidate, sub-quantizer) pairs per query collecting and looking up costs more than it saves:
+    // measured at r = 1000, m = 4)
     uint32_t memo_slots = 0;
     if (MODE == kOnDemand && static_cast<uint64_t>(r) * M >= 8u * 1024u) {
         memo_slots = 512;
