@@ -134,6 +134,40 @@ def test_on_demand_refinement_with_memoized_entries(case):
     c.check_pass_two(dids, ddist)
 
 
+def test_memoized_refinement_that_gives_up_late_or_meets_padding():
+    # Candidate lists written by hand for the stand-alone refinement call.  Query 0: the first candidates repeat 20
+    # sub-codes per sub-quantizer (the first collecting pass finds repetition and goes on), the later ones are all
+    # different (the sets fill up after that check: entries per candidate after all).  Query 1: only repeating
+    # candidates (the memoized form runs to the end), with unused slots (id 0xFFFFFFFF) scattered through the list
+    # and at its end.  Query 2: the first 256 all different (given up at the first check).  Each against the oracle's Eq. 3 distances and top-k.
+    m, dsub, N, r, k = 8, 16, 6000, 5000, 50
+    g = torch.Generator(device=DEV); g.manual_seed(4711)
+    cb = 30.0 * torch.rand((m, 65536, dsub), generator=g, device=DEV, dtype=torch.float32)
+    few = torch.randint(0, 65536, (20, m), generator=g, device=DEV)
+    codes = torch.randint(0, 65536, (N, m), generator=g, device=DEV)
+    pick = torch.randint(0, 20, (2000, m), generator=g, device=DEV)
+    codes[:2000] = torch.gather(few, 0, pick)
+    codes = codes.to(torch.int32).to(torch.int16).view(torch.uint16)
+    queries = 30.0 * torch.rand((3, m * dsub), generator=g, device=DEV, dtype=torch.float32)
+    cand = torch.full((3, r), 0xFFFFFFFF, dtype=torch.int64, device=DEV)
+    cand[0] = torch.arange(r, device=DEV)                                  # 2000 repeating, then 3000 different
+    cand[1, :3800:2] = torch.randperm(2000, generator=g, device=DEV)[:1900]   # repeating ones, every other slot unused
+    perm = 1000 + torch.randperm(5000, generator=g, device=DEV)
+    cand[2] = torch.cat([2000 + torch.arange(256, device=DEV), perm[(perm < 2000) | (perm >= 2256)]])   # nothing repeats at first
+    cand_id = cand.to(torch.uint32)
+    print("memoized refinement on hand-made candidate lists: m=%d N=%d r=%d" % (m, N, r), flush=True)
+    ids, dist = binding.refine_direct_topk(queries, cb, codes, cand_id, k)
+    torch.cuda.synchronize()
+    ids, dist = to_np(ids), to_np(dist)
+    cb_np, codes_np, q_np, cand_np = to_np(cb), to_np(codes), to_np(queries), to_np(cand_id)
+    for q in range(3):
+        real = cand_np[q][cand_np[q] != 0xFFFFFFFF]
+        exact = oracle.refine(q_np[q], cb_np, codes_np, real)
+        ref_ids, ref_dist = oracle.topk(exact, real, k)
+        assert_topk_matches(ids[q], dist[q], ref_ids, ref_dist, oracle.refine(q_np[q], cb_np, codes_np, ids[q]),
+                            cand_ref=real, tag="query %d" % q)
+
+
 def test_fused_search_m2_with_a_ragged_last_chunk():
     # m = 2 goes through the three-pass scan, whose scratch layout depends on the batch size: the
     # last chunk (48 queries after a chunk of 64) lays it out differently from the full chunks
