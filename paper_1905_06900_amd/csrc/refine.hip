@@ -137,6 +137,9 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
             // (a short first pass: it shows whether anything repeats, and after it most pairs are found by a read)
             const uint32_t first = blockDim.x < kMemoFirst ? blockDim.x : kMemoFirst;
             for (uint32_t base = 0; base < r; base += base == 0 ? first : blockDim.x) {  // uniform trip count
+                // (given up by some lane already: nothing more to collect; the passes after the first hold no barrier,
+                // so each lane may leave as soon as it sees that)
+                if (base != 0 && __hip_atomic_load(&s_over, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP)) break;
                 const uint32_t t = base + threadIdx.x;
                 uint32_t id = kEmpty;
                 if (t < r && (base != 0 || threadIdx.x < first)) id = cand_id[static_cast<size_t>(q) * r + t];
@@ -162,6 +165,7 @@ __global__ __launch_bounds__(1024) void refine_topk_kernel(const float *__restri
                                 if (cur == kEmpty) {
                                     const uint32_t at = atomicAdd(&s_claimed, 1u);
                                     if (at < M * memo_slots / 2) hlist[at] = static_cast<uint16_t>(jj * memo_slots + h);
+                                    else s_over = 1;                     // the sets are half full: give up
                                     cur = cj;
                                 }
                             }
