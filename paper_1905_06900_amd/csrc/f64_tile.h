@@ -46,7 +46,7 @@ __device__ inline void f64_tile_products(const float *const (&arow)[MT], const f
         // loads of an instruction fall into 16 memory lines and the next piece finds the other half of each line
         // still in the first-level cache.  (With a quarter of the row per slot every lane walks a line of its own,
         // 16 bytes every four steps, and at 128 components the 256 lines a wavefront has open are the whole cache:
-        // each 16-byte run then moved a line from the L2 again.)  Two sets of registers take the pieces in turn, so
+        // measured 115 M requests to the L2 per 1024 x 65536 distances instead of 21 M.)  Two sets of registers take the pieces in turn, so
         // that the loads of one are under way while the other is multiplied, and nothing is copied between them:
         // the ordinary vector instructions share the issue port with the matrix instructions, and at 8 matrix
         // instructions per step every one of them saved counts (6 conversions and 4 to 6 fused norm updates remain).
